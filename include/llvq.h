@@ -1,0 +1,102 @@
+/*
+ * llvq.h -- C ABI of the MI355X (gfx950) library for Leech Lattice Vector Quantization inference.
+ *
+ * The library decodes 48-bit indices into points of the ball cut Lambda_24(m_max) of the Leech
+ * lattice (union of shells 2..m_max, paper Sec. 2.2), applies the shape-gain scale (paper App. E,
+ * "Shape-gain": w = g * s, s = x/||x||), and multiplies activations by the dequantised weight
+ * matrix without materialising it (paper App. C).  Every step runs in HIP kernels on the device;
+ * there is no CPU fallback: a call made without a usable GPU returns LLVQ_EHIP.
+ *
+ * Conventions
+ *   - All pointers named d_* are DEVICE pointers owned by the caller.  The library allocates device
+ *     memory only inside llvq_create (constant tables) and frees it in llvq_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work on
+ *     it and return without synchronising, except llvq_validate.
+ *   - Return value: 0 on success, a negative LLVQ_E* code otherwise.  Nothing throws or aborts.
+ *   - Index (paper Sec. 3.2, App. A): 0-based, I in [0, N(m_max)); shells by increasing radius,
+ *     classes contiguous inside a shell, inside a class the Golay refinement r is the least
+ *     significant digit, then the sign pattern s, then the permutation rank I''.
+ *   - Decoded coordinates are those of L_int = sqrt(8) * Lambda_24 (paper Sec. 2.3): integers with
+ *     sum x_i^2 = 16 m on shell m.
+ *   - An index >= N(m_max) (the paper does not define it) decodes to the all-zero block.
+ *   - n_blocks == 0 is a valid no-op; the data pointers are then not examined.
+ *   - A weight matrix W_hat[N][K], K = 24*KB, is stored block-wise: one index and one fp16 gain per
+ *     (row n, block b), blocks partitioning the input channels of each row (paper App. B, Alg. 1).
+ *     Activations are supplied zero-padded to K (paper App. C uses 4096 -> 4104).
+ */
+#ifndef LLVQ_H
+#define LLVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct llvq_ctx llvq_ctx;
+
+enum {
+    LLVQ_OK = 0,
+    LLVQ_EINVAL = -1,    /* null pointer, non-positive size, unsupported dtype/format, m_max out of range */
+    LLVQ_EALIGN = -2,    /* a pointer is not aligned as its format requires                              */
+    LLVQ_EHIP = -3,      /* a HIP call failed (no device, allocation, launch); see llvq_last_hip_error   */
+    LLVQ_ENOTIMPL = -4   /* valid request that this build does not implement                             */
+};
+
+/* index storage formats */
+enum {
+    LLVQ_IDX_U48 = 0,    /* 6 bytes per index, little endian, densely packed; 2-byte aligned base        */
+    LLVQ_IDX_U64 = 1     /* one uint64 per index (upper 16 bits ignored); 8-byte aligned base            */
+};
+
+/* element types */
+enum {
+    LLVQ_F16 = 0,
+    LLVQ_BF16 = 1,
+    LLVQ_F32 = 2
+};
+
+/* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 13, on HIP device `device`.
+ * Builds the constant tables (Golay words, class records, ranking tables) on the host and copies
+ * them to the device.  The context is immutable afterwards and may be shared by threads.         */
+int llvq_create(llvq_ctx** out, int m_max, int device);
+void llvq_destroy(llvq_ctx* ctx);
+
+const char* llvq_strerror(int rc);
+/* text of the last HIP error seen by this context ("" if none) */
+const char* llvq_last_hip_error(const llvq_ctx* ctx);
+
+/* N(m_max) = |Lambda_24(m_max)| (paper Table 1): 280,974,212,784,720 for m_max = 13. */
+uint64_t llvq_num_points(const llvq_ctx* ctx);
+/* number of classes over all shells (383 for m_max = 13) */
+int llvq_num_classes(const llvq_ctx* ctx);
+
+/* Dequantiser of paper App. A: d_out[k][0..23] = integer coordinates of index k, int8.
+ * d_idx: n_blocks indices in format `fmt`.                                                        */
+int llvq_decode_i8(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
+                   int8_t* d_out, void* stream);
+
+/* Shape-gain reconstruction (paper App. E): d_out[k][i] = g_k * x_i / sqrt(16 m_k), computed in
+ * fp32 and rounded to out_dtype (LLVQ_F16, LLVQ_BF16 or LLVQ_F32).  d_gain: n_blocks fp16 gains.  */
+int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks,
+                void* d_out, int out_dtype, void* stream);
+
+/* Fused dequantise + multiply (paper App. C): d_y[m][n] = sum_k d_x[m][k] * W_hat[n][k], fp32.
+ *   d_x   : [M][24*KB] row-major, x_dtype LLVQ_F16 or LLVQ_BF16, zero-padded by the caller
+ *   d_idx : [N][KB] indices in format `fmt`;  d_gain: [N][KB] fp16
+ *   d_y   : [M][N] row-major fp32, overwritten
+ * Products x * integer coordinate are exact in fp32; accumulation is fp32.  M = 1 is the decode
+ * (matrix-vector) case the paper times; 1 <= M <= 1024.                                           */
+int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
+                const void* d_idx, int fmt, const void* d_gain, int N, int KB,
+                float* d_y, void* stream);
+
+/* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
+int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
+                  uint64_t* h_bad, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLVQ_H */

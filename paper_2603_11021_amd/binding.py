@@ -1,0 +1,148 @@
+"""ctypes binding with the same names as the C ABI (include/llvq.h).  Argument marshalling only."""
+import ctypes
+import os
+import subprocess
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_CSRC = os.path.join(_HERE, "csrc")
+_LIB = os.path.join(_HERE, "libllvq.so")
+
+LLVQ_IDX_U48, LLVQ_IDX_U64 = 0, 1
+LLVQ_F16, LLVQ_BF16, LLVQ_F32 = 0, 1, 2
+
+HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-std=c++17", "-fPIC", "-shared"]
+
+
+class LLVQError(RuntimeError):
+    pass
+
+
+def lib_path():
+    return _LIB
+
+
+def build_library():
+    """Compile the HIP kernels and the host table builder for gfx950 into libllvq.so (in-tree)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = [os.path.join(_CSRC, "llvq_kernels.hip"), os.path.join(_CSRC, "llvq_tables.cpp")]
+    subprocess.check_call([hipcc] + HIPCC_FLAGS + ["-o", _LIB] + srcs)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB):
+        raise LLVQError("libllvq.so is not built (run __graft_entry__.build()); there is no CPU fallback")
+    lib = ctypes.CDLL(_LIB)
+    vp, i32, u64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_size_t
+    lib.llvq_create.argtypes = [ctypes.POINTER(vp), i32, i32]; lib.llvq_create.restype = i32
+    lib.llvq_destroy.argtypes = [vp]; lib.llvq_destroy.restype = None
+    lib.llvq_strerror.argtypes = [i32]; lib.llvq_strerror.restype = ctypes.c_char_p
+    lib.llvq_last_hip_error.argtypes = [vp]; lib.llvq_last_hip_error.restype = ctypes.c_char_p
+    lib.llvq_num_points.argtypes = [vp]; lib.llvq_num_points.restype = u64
+    lib.llvq_num_classes.argtypes = [vp]; lib.llvq_num_classes.restype = i32
+    lib.llvq_decode_i8.argtypes = [vp, vp, i32, sz, vp, vp]; lib.llvq_decode_i8.restype = i32
+    lib.llvq_decode.argtypes = [vp, vp, i32, vp, sz, vp, i32, vp]; lib.llvq_decode.restype = i32
+    lib.llvq_matmul.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp]; lib.llvq_matmul.restype = i32
+    lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
+    _lib = lib
+    return lib
+
+
+def _stream_handle(stream):
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+class LLVQ:
+    """A context for Lambda_24(m_max) on one device.  Tensors are torch CUDA (ROCm) tensors owned by the caller."""
+
+    def __init__(self, m_max=13, device=0):
+        self._lib = _load()
+        h = ctypes.c_void_p()
+        rc = self._lib.llvq_create(ctypes.byref(h), m_max, device)
+        if rc != 0:
+            raise LLVQError("llvq_create: %s" % self._lib.llvq_strerror(rc).decode())
+        self._h = h
+        self.m_max = m_max
+        self.device = device
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.llvq_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, rc, what):
+        if rc != 0:
+            raise LLVQError("%s: %s (%s)" % (what, self._lib.llvq_strerror(rc).decode(),
+                                             self._lib.llvq_last_hip_error(self._h).decode()))
+
+    @property
+    def num_points(self):
+        return int(self._lib.llvq_num_points(self._h))
+
+    @property
+    def num_classes(self):
+        return int(self._lib.llvq_num_classes(self._h))
+
+    @staticmethod
+    def _idx_fmt(idx):
+        import torch
+        if idx.dtype == torch.uint8:
+            return LLVQ_IDX_U48, idx.numel() // 6
+        if idx.dtype in (torch.int64, torch.uint64):
+            return LLVQ_IDX_U64, idx.numel()
+        raise LLVQError("indices must be uint8 (6 bytes per index) or int64/uint64")
+
+    def llvq_decode_i8(self, idx, out=None, n_blocks=None, stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx)
+        n = n if n_blocks is None else n_blocks
+        if out is None:
+            out = torch.empty((n, 24), dtype=torch.int8, device=idx.device)
+        self._check(self._lib.llvq_decode_i8(self._h, idx.data_ptr(), fmt, n, out.data_ptr(), _stream_handle(stream)),
+                    "llvq_decode_i8")
+        return out
+
+    def llvq_decode(self, idx, gain, out_dtype=None, out=None, stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx)
+        out_dtype = out_dtype or torch.float16
+        code = {torch.float16: LLVQ_F16, torch.bfloat16: LLVQ_BF16, torch.float32: LLVQ_F32}[out_dtype]
+        if gain.dtype != torch.float16 or gain.numel() != n:
+            raise LLVQError("gain must be float16 with one entry per block")
+        if out is None:
+            out = torch.empty((n, 24), dtype=out_dtype, device=idx.device)
+        self._check(self._lib.llvq_decode(self._h, idx.data_ptr(), fmt, gain.data_ptr(), n, out.data_ptr(), code,
+                                          _stream_handle(stream)), "llvq_decode")
+        return out
+
+    def llvq_matmul(self, x, idx, gain, N, KB, out=None, stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx)
+        if n != N * KB or gain.numel() != N * KB or gain.dtype != torch.float16:
+            raise LLVQError("idx and gain must hold N*KB blocks; gain float16")
+        code = {torch.float16: LLVQ_F16, torch.bfloat16: LLVQ_BF16}[x.dtype]
+        x2 = x.reshape(-1, 24 * KB)
+        M = x2.shape[0]
+        if out is None:
+            out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+        self._check(self._lib.llvq_matmul(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, gain.data_ptr(), N, KB,
+                                          out.data_ptr(), _stream_handle(stream)), "llvq_matmul")
+        return out
+
+    def llvq_validate(self, idx, stream=None):
+        fmt, n = self._idx_fmt(idx)
+        bad = ctypes.c_uint64()
+        self._check(self._lib.llvq_validate(self._h, idx.data_ptr(), fmt, n, ctypes.byref(bad), _stream_handle(stream)),
+                    "llvq_validate")
+        return int(bad.value)

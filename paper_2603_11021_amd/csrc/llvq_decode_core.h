@@ -1,0 +1,195 @@
+// Index -> block reconstruction shared by all kernels (paper App. A, steps 1-4), written so that the
+// same source also compiles for the host, where a test harness runs it against the tables without a GPU.
+//
+// One call decodes one 48-bit index into four 32-bit words of six nibbles each.  Word j covers positions
+// 6j..6j+5; position p of the chunk sits in nibble slot kNibbleSlot[p].  A nibble is
+//     bit 3: sign,  bits 0..2: value code, an index into the class's 8-entry value table.
+// Nothing here branches on the class: odd classes, even classes and the degenerate weights 0 and 24 run
+// the same instruction stream with different class-record fields, so a wavefront holding 64 different
+// classes does not diverge (the only data-dependent loops are the two short table searches).
+#pragma once
+#include <cstdint>
+#include <cmath>
+
+#include "llvq_tables.h"
+
+#if defined(__HIPCC__)
+#define LLVQ_HD __host__ __device__ __forceinline__
+#else
+#define LLVQ_HD inline
+#endif
+
+namespace llvq {
+
+struct TabPtrs {
+    const uint32_t* gs;
+    const uint32_t* spread6;
+    const uint8_t*  pdep6;
+    const uint16_t* lut12;
+    const uint16_t* bucket;
+    const uint64_t* cls_off;
+    const ClassRec* cls;
+    const SplitEnt* split;
+    const uint8_t*  guess;
+    const uint32_t* inner;
+    uint32_t ncls;
+    uint32_t bucket_shift;
+    uint64_t npoints;
+};
+
+LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const TableLayout& L) {
+    TabPtrs T;
+    T.gs = reinterpret_cast<const uint32_t*>(base + L.gs);
+    T.spread6 = reinterpret_cast<const uint32_t*>(base + L.spread6);
+    T.pdep6 = reinterpret_cast<const uint8_t*>(base + L.pdep6);
+    T.lut12 = reinterpret_cast<const uint16_t*>(base + L.lut12);
+    T.bucket = reinterpret_cast<const uint16_t*>(base + L.bucket);
+    T.cls_off = reinterpret_cast<const uint64_t*>(base + L.cls_off);
+    T.cls = reinterpret_cast<const ClassRec*>(base + L.cls);
+    T.split = reinterpret_cast<const SplitEnt*>(base + L.split);
+    T.guess = reinterpret_cast<const uint8_t*>(base + L.guess);
+    T.inner = reinterpret_cast<const uint32_t*>(base + L.inner);
+    T.ncls = L.ncls;
+    T.bucket_shift = L.bucket_shift;
+    T.npoints = L.npoints;
+    return T;
+}
+
+LLVQ_HD uint32_t popc32(uint32_t v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return (uint32_t)__popc(v);
+#else
+    return (uint32_t)__builtin_popcount(v);
+#endif
+}
+
+LLVQ_HD uint32_t bfe6(uint32_t v, uint32_t off) { return (v >> off) & 63u; }
+
+// Decodes index I (must be < npoints).  Returns the class id; w[0..3] receive the nibble words.
+LLVQ_HD uint32_t decode_block(const TabPtrs& T, uint64_t I, uint32_t w[4]) {
+    // App. A steps 1-2: shell and class in one search over the global class offsets
+    uint32_t cid = T.bucket[(uint32_t)(I >> T.bucket_shift)];
+    while (cid + 1 < T.ncls && I >= T.cls_off[cid + 1]) cid++;
+    const ClassRec R = T.cls[cid];
+    const uint64_t Ic = I - T.cls_off[cid];
+    const uint32_t f0 = R.f0, f1 = R.f1;
+
+    // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
+    // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
+    const uint32_t acode = (f1 >> F1_ACODE) & 3u;
+    const double A = acode == 0 ? 1.0 : (acode == 1 ? 759.0 : (acode == 2 ? 2576.0 : 4096.0));
+    constexpr double kNudge = 1.0 + 0x1p-50;
+    const double invA = acode == 0 ? 1.0 : (acode == 1 ? (1.0 / 759.0) * kNudge : (acode == 2 ? (1.0 / 2576.0) * kNudge : 0x1p-12));
+    const double x = (double)Ic;
+    const double q1 = floor(x * invA);
+    const uint32_t r = (uint32_t)fma(-q1, A, x);
+    const int B = (int)((f0 >> F0_B) & 31u);
+    const double ipp = floor(ldexp(q1, -B));
+    const uint32_t s = (uint32_t)fma(-ipp, ldexp(1.0, B), q1);
+    // I'' = (d * Pin + rin) * P1 + rho1
+    const double dd = floor(ipp * R.invPP);
+    const uint32_t rem = (uint32_t)fma(-dd, (double)R.PP, ipp);
+    const uint32_t d = (uint32_t)dd;
+    const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
+    const uint32_t rho1 = rem - rin * R.P1;
+
+    // the Golay word selected by r
+    const uint32_t c = T.gs[((f1 >> F1_GOFF) & 4095u) + r];
+
+    // App. A step 4, placement: the q-subset U of the outer domain's n slots with rank d
+    uint32_t j = T.guess[((f1 >> F1_GROW) & 63u) * 32u + (d >> ((f1 >> F1_GSHIFT) & 31u))];
+    const uint32_t jmax = (f1 >> F1_JMAX) & 15u;
+    while (j < jmax && d >= T.split[(uint16_t)(R.sp + j + 1)].base) j++;
+    const SplitEnt e = T.split[(uint16_t)(R.sp + j)];
+    const uint32_t dl = d - e.base;
+    const uint32_t rk_hi = (uint32_t)((double)dl * (double)e.inv);
+    const uint32_t rk_lo = dl - rk_hi * e.div;
+    const uint32_t U = (uint32_t)T.lut12[e.b12lo + rk_lo] | ((uint32_t)T.lut12[e.b12hi + rk_hi] << 12);
+
+    // symbol planes over the slots of U (a0, b0) and over the F1 slots (a1, b1)
+    const uint32_t e0 = T.inner[R.tb0 + rin];
+    const uint32_t e1 = T.inner[R.tb1 + rho1];
+    const uint32_t a0 = e0 & 0xFFFFu, b0 = e0 >> 16, a1 = e1 & 0xFFFFu, b1 = e1 >> 16;
+
+    // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so that
+    // the number of negative F1 coordinates has the parity condition (iii) asks for
+    const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
+    uint32_t s1 = s & ((1u << wm1) - 1u);
+    const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
+    s1 |= forced << wm1;
+    const uint32_t s0 = s >> wm1;
+
+    const bool odd = (f0 >> F0_ODD) & 1u;
+    const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
+    const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? c : 0u;             // slots of the direct F1 word
+    const uint32_t om = outer_all ? 0xFFFFFFu : (~c & 0xFFFFFFu);        // positions of the outer domain
+    const uint32_t sm = odd ? 0xFFFFFFu : c;                             // positions taking a bit of sb
+    const uint32_t sb = odd ? c : s1;                                    // odd: the word itself flips signs
+    const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                 // keep U as the domain bit
+
+    uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        const uint32_t omk = bfe6(om, 6 * k);
+        const uint32_t uk = T.pdep6[omk << 6 | bfe6(U, ou)];            // U in absolute positions
+        ou += popc32(omk);
+        const uint32_t cmk = bfe6(cm, 6 * k) << 6, smk = bfe6(sm, 6 * k);
+        const uint32_t gA1 = T.spread6[cmk | bfe6(a1, o1)];
+        const uint32_t gB1 = T.spread6[cmk | bfe6(b1, o1)];
+        o1 += popc32(cmk);
+        const uint32_t gA0 = T.spread6[uk << 6 | bfe6(a0, o0)];
+        const uint32_t gB0 = T.spread6[uk << 6 | bfe6(b0, o0)];
+        const uint32_t gS0 = T.spread6[uk << 6 | bfe6(s0, o0)];
+        o0 += popc32(uk);
+        const uint32_t gS1 = T.spread6[smk << 6 | bfe6(sb, os)];
+        os += popc32(smk);
+        const uint32_t ones = 0x01011111u;
+        w[k] = ((gA1 | gA0) & ones) | (((gB1 | gB0) & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
+               (gA1 & 0x04044444u) | (gA0 & dkeep);
+    }
+    return cid;
+}
+
+// v_perm_b32-style byte select restricted to selector values 0..7: byte k of the result is byte sel_k of hi:lo
+LLVQ_HD uint32_t byte_lut8(uint32_t hi, uint32_t lo, uint32_t sel) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_perm(hi, lo, sel);
+#else
+    const uint64_t tab = ((uint64_t)hi << 32) | lo;
+    uint32_t out = 0;
+    for (int k = 0; k < 4; k++) out |= (uint32_t)((tab >> (8 * ((sel >> (8 * k)) & 7u))) & 0xFFu) << (8 * k);
+    return out;
+#endif
+}
+
+// Value bytes of one nibble word through an 8-entry table whose bytes carry a sign in bit 7 (fp8) or are
+// two's complement int8.  ev = positions (0,1,4,5) of the chunk, od = positions (2,3) in its low half.
+LLVQ_HD void chunk_codes(uint32_t w, uint32_t& ev, uint32_t& od) {
+    ev = w & 0x07070707u;
+    od = (w >> 4) & 0x00000707u;
+}
+
+// 24 int8 coordinates of a decoded block, position order, as six dwords
+LLVQ_HD void nibbles_to_i8(const uint32_t w[4], uint32_t vt_lo, uint32_t vt_hi, uint32_t out[6]) {
+    uint32_t ev[4], od[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        uint32_t ce, co;
+        chunk_codes(w[k], ce, co);
+        uint32_t ve = byte_lut8(vt_hi, vt_lo, ce), vo = byte_lut8(vt_hi, vt_lo, co) & 0xFFFFu;
+        // negate the bytes whose sign bit is set: (v ^ m) + (m & 1) per byte, no carries because v != 0 there
+        uint32_t me = ((w[k] >> 3) & 0x01010101u) * 0xFFu, mo = ((w[k] >> 7) & 0x00000101u) * 0xFFu;
+        ev[k] = (ve ^ me) + (me & 0x01010101u);
+        od[k] = (vo ^ mo) + (mo & 0x01010101u);
+    }
+    // chunk k holds (q0 q1 q4 q5) in ev and (q2 q3) in od; two chunks make three dwords in position order
+#pragma unroll
+    for (int h = 0; h < 2; h++) {
+        const uint32_t e0 = ev[2 * h], o0 = od[2 * h], e1 = ev[2 * h + 1], o1 = od[2 * h + 1];
+        out[3 * h + 0] = (e0 & 0xFFFFu) | (o0 << 16);                    // q0 q1 q2 q3
+        out[3 * h + 1] = (e0 >> 16) | (e1 << 16);                        // q4 q5 q0' q1'
+        out[3 * h + 2] = (o1 & 0xFFFFu) | (e1 & 0xFFFF0000u);            // q2' q3' q4' q5'
+    }
+}
+
+}  // namespace llvq

@@ -1,0 +1,442 @@
+// gfx950 kernels and the C ABI of the LLVQ library (see include/llvq.h for the contract).
+//
+// Work decomposition: one lane decodes one 24-block.  All constant tables live in LDS (about 150 KB, one
+// 1024-thread workgroup per compute unit); every table access is an LDS gather, every other step is VALU
+// work on registers.  The fused product streams 8 bytes per block from HBM (6-byte index + fp16 gain),
+// decodes the block into fp8-coded weights in registers, converts them pairwise to fp16 and feeds
+// v_dot2_f32_f16 against activations that consecutive lanes read as consecutive 48-byte runs.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/llvq.h"
+#include "llvq_decode_core.h"
+#include "llvq_tables.h"
+
+namespace {
+
+using llvq::ClassRec;
+using llvq::TableLayout;
+using llvq::TabPtrs;
+
+constexpr int kThreads = 1024;
+constexpr int kWaves = kThreads / 64;
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+extern __shared__ __align__(16) unsigned char g_lds[];
+
+__device__ __forceinline__ void load_tables(const unsigned char* __restrict__ blob, uint32_t bytes) {
+    const uint4* src = reinterpret_cast<const uint4*>(blob);
+    uint4* dst = reinterpret_cast<uint4*>(g_lds);
+    for (uint32_t i = threadIdx.x; i < bytes / 16; i += blockDim.x) dst[i] = src[i];
+    __syncthreads();
+}
+
+template <int FMT>
+__device__ __forceinline__ uint64_t load_index(const void* __restrict__ idx, size_t k) {
+    if constexpr (FMT == LLVQ_IDX_U64) {
+        return reinterpret_cast<const uint64_t*>(idx)[k] & 0xFFFFFFFFFFFFull;
+    } else {
+        const uint16_t* p = reinterpret_cast<const uint16_t*>(idx) + 3 * k;
+        return (uint64_t)p[0] | ((uint64_t)p[1] << 16) | ((uint64_t)p[2] << 32);
+    }
+}
+
+// ---- llvq_decode_i8 ---------------------------------------------------------------------------------
+template <int FMT>
+__global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                             const void* __restrict__ idx, size_t n,
+                                                             uint32_t* __restrict__ out) {
+    load_tables(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
+        const uint64_t I = load_index<FMT>(idx, k);
+        const bool ok = I < T.npoints;
+        uint32_t w[4], o[6];
+        const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
+        llvq::nibbles_to_i8(w, T.cls[cid].vti_lo, T.cls[cid].vti_hi, o);
+        uint2* dst = reinterpret_cast<uint2*>(out + 6 * k);
+        dst[0] = ok ? make_uint2(o[0], o[1]) : make_uint2(0, 0);
+        dst[1] = ok ? make_uint2(o[2], o[3]) : make_uint2(0, 0);
+        dst[2] = ok ? make_uint2(o[4], o[5]) : make_uint2(0, 0);
+    }
+}
+
+// fp8 (e4m3) byte pair -> two fp16 / bf16, exact for the small integers stored in the value tables
+__device__ __forceinline__ half2_t fp8x2_to_f16(uint32_t v, bool hi) {
+    return hi ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(v, 1.0f, false);
+}
+__device__ __forceinline__ bf16x2_t fp8x2_to_bf16(uint32_t v, bool hi) {
+    return hi ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v, 1.0f, false);
+}
+
+// signed fp8 bytes of chunk word w: fe = positions (0,1,4,5), fo = positions (2,3)
+__device__ __forceinline__ void chunk_fp8(uint32_t w, uint32_t vt_lo, uint32_t vt_hi, uint32_t& fe, uint32_t& fo) {
+    uint32_t ce, co;
+    llvq::chunk_codes(w, ce, co);
+    fe = llvq::byte_lut8(vt_hi, vt_lo, ce) ^ ((w << 4) & 0x80808080u);
+    fo = llvq::byte_lut8(vt_hi, vt_lo, co) ^ (w & 0x00008080u);
+}
+
+// ---- llvq_decode (shape-gain reconstruction) ------------------------------------------------------------
+template <int FMT, int OUT>
+__global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                           size_t n, void* __restrict__ out) {
+    load_tables(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
+        const uint64_t I = load_index<FMT>(idx, k);
+        const bool ok = I < T.npoints;
+        uint32_t w[4];
+        const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
+        const ClassRec* R = &T.cls[cid];
+        const uint32_t vt_lo = R->vt8_lo, vt_hi = R->vt8_hi;
+        const uint32_t m = (R->f0 >> llvq::F0_M) & 15u;
+        const float g = __half2float(__ushort_as_half(gain[k]));
+        const float scale = ok ? g * lay.rnorm[m] : 0.0f;
+        float v[24];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            uint32_t fe, fo;
+            chunk_fp8(w[c], vt_lo, vt_hi, fe, fo);
+            const half2_t h01 = fp8x2_to_f16(fe, false), h45 = fp8x2_to_f16(fe, true), h23 = fp8x2_to_f16(fo, false);
+            v[6 * c + 0] = (float)h01[0]; v[6 * c + 1] = (float)h01[1];
+            v[6 * c + 2] = (float)h23[0]; v[6 * c + 3] = (float)h23[1];
+            v[6 * c + 4] = (float)h45[0]; v[6 * c + 5] = (float)h45[1];
+        }
+        if constexpr (OUT == LLVQ_F32) {
+            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + 24 * k);
+#pragma unroll
+            for (int i = 0; i < 6; i++) dst[i] = make_float4(v[4 * i] * scale, v[4 * i + 1] * scale, v[4 * i + 2] * scale, v[4 * i + 3] * scale);
+        } else {
+            uint32_t pk[12];
+#pragma unroll
+            for (int i = 0; i < 12; i++) {
+                const float a = v[2 * i] * scale, b = v[2 * i + 1] * scale;
+                if constexpr (OUT == LLVQ_F16) {
+                    pk[i] = (uint32_t)__half_as_ushort(__float2half_rn(a)) | ((uint32_t)__half_as_ushort(__float2half_rn(b)) << 16);
+                } else {
+                    // bf16 round to nearest even from fp32 bits (finite inputs)
+                    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
+                    ua += 0x7FFFu + ((ua >> 16) & 1u); ub += 0x7FFFu + ((ub >> 16) & 1u);
+                    pk[i] = (ua >> 16) | (ub & 0xFFFF0000u);
+                }
+            }
+            uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + 24 * k);
+            dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            dst[2] = make_uint4(pk[8], pk[9], pk[10], pk[11]);
+        }
+    }
+}
+
+// ---- llvq_matmul, lane-per-block kernel ---------------------------------------------------------------
+// A workgroup owns `rows_per_wg` consecutive rows, i.e. a contiguous run of rows_per_wg*KB blocks of the
+// row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the 16
+// waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
+// gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
+constexpr int kMaxMChunk = 8;     // activation rows handled per pass over the indices
+
+template <typename X2> struct Dot;
+template <> struct Dot<half2_t> {
+    static __device__ __forceinline__ half2_t cvt(uint32_t v, bool hi) { return fp8x2_to_f16(v, hi); }
+    static __device__ __forceinline__ float dot(half2_t a, half2_t b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+};
+template <> struct Dot<bf16x2_t> {
+    static __device__ __forceinline__ bf16x2_t cvt(uint32_t v, bool hi) { return fp8x2_to_bf16(v, hi); }
+    static __device__ __forceinline__ float dot(bf16x2_t a, bf16x2_t b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+};
+
+template <int FMT, typename X2>
+__global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                          const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                          const uint32_t* __restrict__ x, int M, int N, int KB,
+                                                          int rows_per_wg, float* __restrict__ y) {
+    load_tables(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [rows_per_wg][kMaxMChunk]
+    const int r0 = blockIdx.x * rows_per_wg;
+    const int nrows = min(rows_per_wg, N - r0);
+    if (nrows <= 0) return;
+    const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
+    const size_t blk0 = (size_t)r0 * KB;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
+
+    for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
+        const int mc = min(kMaxMChunk, M - m0);
+        for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+        __syncthreads();
+        for (uint32_t base = (uint32_t)wave * 64; base < nblk; base += kWaves * 64) {
+            const uint32_t fb = base + lane;
+            const bool live = fb < nblk;
+            const uint32_t fbc = live ? fb : nblk - 1;
+            const uint32_t row = fbc / (uint32_t)KB, b = fbc - row * (uint32_t)KB;
+            const uint64_t I = load_index<FMT>(idx, blk0 + fbc);
+            const bool ok = live && I < T.npoints;
+            uint32_t w[4];
+            const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
+            const ClassRec* R = &T.cls[cid];
+            const uint32_t vt_lo = R->vt8_lo, vt_hi = R->vt8_hi;
+            const uint32_t m = (R->f0 >> llvq::F0_M) & 15u;
+            const float g = __half2float(__ushort_as_half(gain[blk0 + fbc]));
+            const float scale = ok ? g * lay.rnorm[m] : 0.0f;
+            X2 wt[12];
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                uint32_t fe, fo;
+                chunk_fp8(w[c], vt_lo, vt_hi, fe, fo);
+                wt[3 * c + 0] = Dot<X2>::cvt(fe, false);   // positions 6c+0, 6c+1
+                wt[3 * c + 1] = Dot<X2>::cvt(fo, false);   // positions 6c+2, 6c+3
+                wt[3 * c + 2] = Dot<X2>::cvt(fe, true);    // positions 6c+4, 6c+5
+            }
+            // lanes sharing a row are contiguous; head = first lane of its row in this batch
+            const uint32_t row_up = __shfl_up(row, 1);
+            const bool head = (lane == 0) || (row_up != row);
+            for (int mi = 0; mi < mc; mi++) {
+                const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)b * 12);
+                const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
+                const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
+                float acc = 0.0f;
+#pragma unroll
+                for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
+                float p = acc * scale;
+                // segmented suffix sum over lanes of equal row
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) {
+                    const float pv = __shfl_down(p, off);
+                    const uint32_t rv = __shfl_down(row, off);
+                    if (lane + off < 64 && rv == row) p += pv;
+                }
+                if (head && live) atomicAdd(&ysum[row * kMaxMChunk + mi], p);
+            }
+        }
+        __syncthreads();
+        for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
+            const int rr = i / mc, mi = i - rr * mc;
+            y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
+        }
+        __syncthreads();
+    }
+}
+
+// ---- llvq_validate ------------------------------------------------------------------------------------
+template <int FMT>
+__global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
+    unsigned long long local = 0;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
+        local += load_index<FMT>(idx, k) >= npoints;
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
+    if ((threadIdx.x & 63) == 0 && local) atomicAdd(bad, local);
+}
+
+}  // namespace
+
+// ---- C ABI -------------------------------------------------------------------------------------------
+struct llvq_ctx {
+    int device = 0;
+    int m_max = 0;
+    int num_cu = 0;
+    llvq::TableLayout lay{};
+    unsigned char* d_blob = nullptr;
+    unsigned long long* d_counter = nullptr;
+    std::string hip_error;
+};
+
+namespace {
+
+int hip_fail(llvq_ctx* ctx, hipError_t e, const char* what) {
+    if (ctx) ctx->hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    return LLVQ_EHIP;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+int check_idx(const void* d_idx, int fmt) {
+    if (!d_idx) return LLVQ_EINVAL;
+    if (fmt == LLVQ_IDX_U48) return aligned(d_idx, 2) ? LLVQ_OK : LLVQ_EALIGN;
+    if (fmt == LLVQ_IDX_U64) return aligned(d_idx, 8) ? LLVQ_OK : LLVQ_EALIGN;
+    return LLVQ_EINVAL;
+}
+
+template <typename K>
+int set_lds(llvq_ctx* ctx, K kernel, size_t bytes) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "hipFuncSetAttribute");
+}
+
+int grid_for(const llvq_ctx* ctx, size_t n) {
+    size_t wgs = (n + kThreads - 1) / kThreads;
+    size_t cap = (size_t)ctx->num_cu * 4;
+    return (int)(wgs < 1 ? 1 : (wgs > cap ? cap : wgs));
+}
+
+}  // namespace
+
+template <int FMT>
+static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, size_t n, void* d_out, int out_dtype, hipStream_t st) {
+    const size_t lds = ctx->lay.lds_bytes;
+    const int grid = grid_for(ctx, n);
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
+#define LLVQ_LAUNCH_DQ(OUT)                                                                                     \
+    do {                                                                                                          \
+        if (int rc = set_lds(ctx, dequant_kernel<FMT, OUT>, lds)) return rc;                                      \
+        hipLaunchKernelGGL((dequant_kernel<FMT, OUT>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, n, d_out); \
+    } while (0)
+    if (out_dtype == LLVQ_F16) LLVQ_LAUNCH_DQ(LLVQ_F16);
+    else if (out_dtype == LLVQ_BF16) LLVQ_LAUNCH_DQ(LLVQ_BF16);
+    else LLVQ_LAUNCH_DQ(LLVQ_F32);
+#undef LLVQ_LAUNCH_DQ
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "dequant launch");
+}
+
+template <int FMT, typename X2>
+static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+    // rows per workgroup: enough workgroups to cover every compute unit a few times over, but at least
+    // ~2 wave-batches per wave so that the table load is amortised
+    const size_t blocks_total = (size_t)N * KB;
+    int rows = (int)((size_t)(2 * kThreads) / (size_t)KB);
+    if (rows < 1) rows = 1;
+    const int min_wgs = ctx->num_cu * 2;
+    while (rows > 1 && (N + rows - 1) / rows < min_wgs && (size_t)rows * KB > (size_t)kThreads) rows--;
+    if (rows > 64) rows = 64;
+    (void)blocks_total;
+    const int grid = (N + rows - 1) / rows;
+    const size_t lds = ctx->lay.lds_bytes + (size_t)rows * kMaxMChunk * sizeof(float);
+    if (int rc = set_lds(ctx, matmul_kernel<FMT, X2>, lds)) return rc;
+    hipLaunchKernelGGL((matmul_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, rows, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
+}
+
+extern "C" {
+
+const char* llvq_strerror(int rc) {
+    switch (rc) {
+        case LLVQ_OK: return "ok";
+        case LLVQ_EINVAL: return "invalid argument";
+        case LLVQ_EALIGN: return "misaligned pointer";
+        case LLVQ_EHIP: return "HIP call failed";
+        case LLVQ_ENOTIMPL: return "not implemented";
+        default: return "unknown error";
+    }
+}
+
+const char* llvq_last_hip_error(const llvq_ctx* ctx) { return ctx ? ctx->hip_error.c_str() : ""; }
+
+int llvq_create(llvq_ctx** out, int m_max, int device) {
+    if (!out || m_max < 2 || m_max > 13 || device < 0) return LLVQ_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return LLVQ_EHIP;
+    llvq::Tables tabs;
+    if (!llvq::build_tables(m_max, tabs)) return LLVQ_EINVAL;
+    llvq_ctx* ctx = new (std::nothrow) llvq_ctx;
+    if (!ctx) return LLVQ_EINVAL;
+    ctx->device = device; ctx->m_max = m_max; ctx->lay = tabs.lay;
+    hipError_t e;
+    if ((e = hipSetDevice(device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
+    hipDeviceProp_t prop;
+    if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
+    ctx->num_cu = prop.multiProcessorCount;
+    if (tabs.lay.lds_bytes + 4096 > prop.sharedMemPerBlock && tabs.lay.lds_bytes + 4096 > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
+    if ((e = hipMalloc(&ctx->d_blob, tabs.blob.size())) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
+    if ((e = hipMalloc(&ctx->d_counter, sizeof(unsigned long long))) != hipSuccess) { (void)hipFree(ctx->d_blob); delete ctx; return LLVQ_EHIP; }
+    if ((e = hipMemcpy(ctx->d_blob, tabs.blob.data(), tabs.blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {
+        (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
+    }
+    *out = ctx;
+    return LLVQ_OK;
+}
+
+void llvq_destroy(llvq_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    if (ctx->d_blob) (void)hipFree(ctx->d_blob);
+    if (ctx->d_counter) (void)hipFree(ctx->d_counter);
+    delete ctx;
+}
+
+uint64_t llvq_num_points(const llvq_ctx* ctx) { return ctx ? ctx->lay.npoints : 0; }
+int llvq_num_classes(const llvq_ctx* ctx) { return ctx ? (int)ctx->lay.ncls : 0; }
+
+int llvq_decode_i8(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, int8_t* d_out, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    if (n_blocks == 0) return (fmt == LLVQ_IDX_U48 || fmt == LLVQ_IDX_U64) ? LLVQ_OK : LLVQ_EINVAL;   // nothing to read or write
+    if (!d_out) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_out, 8)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t lds = ctx->lay.lds_bytes;
+    const int grid = grid_for(ctx, n_blocks);
+    if (fmt == LLVQ_IDX_U48) {
+        if (int rc = set_lds(ctx, decode_i8_kernel<LLVQ_IDX_U48>, lds)) return rc;
+        hipLaunchKernelGGL(decode_i8_kernel<LLVQ_IDX_U48>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, n_blocks, reinterpret_cast<uint32_t*>(d_out));
+    } else {
+        if (int rc = set_lds(ctx, decode_i8_kernel<LLVQ_IDX_U64>, lds)) return rc;
+        hipLaunchKernelGGL(decode_i8_kernel<LLVQ_IDX_U64>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, n_blocks, reinterpret_cast<uint32_t*>(d_out));
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "decode_i8 launch");
+}
+
+int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks, void* d_out, int out_dtype, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    if (out_dtype != LLVQ_F16 && out_dtype != LLVQ_BF16 && out_dtype != LLVQ_F32) return LLVQ_EINVAL;
+    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
+    if (n_blocks == 0) return LLVQ_OK;
+    if (!d_out || !d_gain) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_out, 16) || !aligned(d_gain, 2)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return fmt == LLVQ_IDX_U48 ? launch_dequant<LLVQ_IDX_U48>(ctx, d_idx, d_gain, n_blocks, d_out, out_dtype, st)
+                               : launch_dequant<LLVQ_IDX_U64>(ctx, d_idx, d_gain, n_blocks, d_out, out_dtype, st);
+}
+
+int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
+                int N, int KB, float* d_y, void* stream) {
+    if (!ctx || !d_x || !d_gain || !d_y) return LLVQ_EINVAL;
+    if (M < 1 || M > 1024 || N < 1 || KB < 1) return LLVQ_EINVAL;
+    if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
+    if ((size_t)N * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (x_dtype == LLVQ_F16)
+        return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
+                                   : launch_matmul<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+    return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
+                               : launch_matmul<LLVQ_IDX_U64, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+}
+
+int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, uint64_t* h_bad, void* stream) {
+    if (!ctx || !h_bad) return LLVQ_EINVAL;
+    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
+    if (n_blocks) { if (int rc = check_idx(d_idx, fmt)) return rc; }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e;
+    unsigned long long zero = 0;
+    if ((e = hipMemcpyAsync(ctx->d_counter, &zero, sizeof zero, hipMemcpyHostToDevice, st)) != hipSuccess) return hip_fail(ctx, e, "validate reset");
+    if (n_blocks) {
+        const int grid = grid_for(ctx, n_blocks);
+        if (fmt == LLVQ_IDX_U48) hipLaunchKernelGGL(validate_kernel<LLVQ_IDX_U48>, dim3(grid), dim3(256), 0, st, d_idx, n_blocks, ctx->lay.npoints, ctx->d_counter);
+        else hipLaunchKernelGGL(validate_kernel<LLVQ_IDX_U64>, dim3(grid), dim3(256), 0, st, d_idx, n_blocks, ctx->lay.npoints, ctx->d_counter);
+        if ((e = hipGetLastError()) != hipSuccess) return hip_fail(ctx, e, "validate launch");
+    }
+    unsigned long long got = 0;
+    if ((e = hipMemcpyAsync(&got, ctx->d_counter, sizeof got, hipMemcpyDeviceToHost, st)) != hipSuccess) return hip_fail(ctx, e, "validate read");
+    if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(ctx, e, "validate sync");
+    *h_bad = got;
+    return LLVQ_OK;
+}
+
+}  // extern "C"

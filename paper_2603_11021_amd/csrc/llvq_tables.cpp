@@ -1,0 +1,408 @@
+// Host-side builder of the dequantiser's constant tables (see llvq_tables.h for what each holds).
+//
+// What the tables encode, with the passages that define it:
+//   - Golay words: cyclic (23,12) code of generator x^11+x^10+x^6+x^5+x^4+x^2+1 extended by a parity
+//     bit at coordinate 23; words ordered by (weight, message)                        [paper Sec. 2.3]
+//   - classes of a shell: multisets of 24 absolute values with sum of squares 16 m, all even with
+//     #(2 mod 4) a Golay weight (and #(4 mod 8) even when that weight is 0), or all odd [Sec. 2.3-2.5]
+//   - class cardinality A * 2^B * (arrangements on F1) * (arrangements on F0)          [Sec. 2.5]
+//   - index order: shells by radius, classes contiguous, local digits r, s, I''       [Sec. 3.2, App. A]
+// The orders the paper leaves free (class order, word order, sign-bit order, ranking of placements)
+// are those of this library's index format; they are restated where each table is built.
+#include "llvq_tables.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <map>
+
+namespace llvq {
+namespace {
+
+uint64_t g_binom[25][25];
+
+void init_binom() {
+    for (int n = 0; n <= 24; n++)
+        for (int k = 0; k <= 24; k++)
+            g_binom[n][k] = (k == 0) ? 1 : (n == 0 ? 0 : g_binom[n - 1][k - 1] + g_binom[n - 1][k]);
+}
+
+inline int popcnt(uint32_t v) { return __builtin_popcount(v); }
+
+// masks of popcount p below 2^nbits in increasing numeric order (= colex order of the subsets)
+std::vector<uint32_t> masks_in_colex_order(int nbits, int p) {
+    std::vector<uint32_t> out;
+    for (uint32_t m = 0; m < (1u << nbits); m++)
+        if (popcnt(m) == p) out.push_back(m);
+    return out;
+}
+
+// deposit the low bits of `src` into the set bits of `mask`, lowest first
+uint32_t deposit(uint32_t src, uint32_t mask) {
+    uint32_t out = 0;
+    for (int pos = 0, k = 0; pos < 32; pos++)
+        if ((mask >> pos) & 1u) { if ((src >> k) & 1u) out |= 1u << pos; k++; }
+    return out;
+}
+
+struct Leader {
+    std::vector<int> val, cnt;   // distinct absolute values descending, multiplicities
+    int m = 0;
+    bool odd = false;
+    int w = 0;
+    uint64_t A = 0, size = 0, offset = 0, P1 = 1, P0 = 1;
+    int B = 0;
+};
+
+uint64_t multinomial(const std::vector<int>& c) {
+    int n = 0;
+    for (int v : c) n += v;
+    uint64_t r = 1;
+    for (int v : c) { r *= g_binom[n][v]; n -= v; }
+    return r;
+}
+
+void enumerate(int m, bool odd, int v, int left, int leftsq, Leader& cur, std::vector<Leader>& out) {
+    const int vmin = odd ? 1 : 0;
+    if (v == vmin) {
+        if (left * v * v != leftsq) return;
+        Leader L = cur;
+        if (left > 0) { L.val.push_back(v); L.cnt.push_back(left); }
+        out.push_back(L);
+        return;
+    }
+    for (int k = std::min(left, leftsq / (v * v)); k >= 0; k--) {
+        if (k) { cur.val.push_back(v); cur.cnt.push_back(k); }
+        enumerate(m, odd, v - 2, left - k, leftsq - k * v * v, cur, out);
+        if (k) { cur.val.pop_back(); cur.cnt.pop_back(); }
+    }
+}
+
+bool leader_less(const Leader& a, const Leader& b) {
+    if (a.odd != b.odd) return !a.odd;
+    if (a.w != b.w) return a.w < b.w;
+    // descending-ordered leaders compared lexicographically
+    std::vector<int> ea, eb;
+    for (size_t i = 0; i < a.val.size(); i++) ea.insert(ea.end(), a.cnt[i], a.val[i]);
+    for (size_t i = 0; i < b.val.size(); i++) eb.insert(eb.end(), b.cnt[i], b.val[i]);
+    return ea < eb;
+}
+
+uint8_t fp8_e4m3(int v) {   // small non-negative integers are exact in e4m3 (bias 7)
+    if (v == 0) return 0;
+    int e = 0;
+    while ((v >> (e + 1)) != 0) e++;
+    int frac = ((v << 3) >> e) & 7;   // three mantissa bits below the leading one (v <= 15)
+    return (uint8_t)(((e + 7) << 3) | frac);
+}
+
+template <typename T>
+uint32_t append(std::vector<unsigned char>& blob, const std::vector<T>& v) {
+    while (blob.size() % 16) blob.push_back(0);
+    uint32_t off = (uint32_t)blob.size();
+    const unsigned char* p = reinterpret_cast<const unsigned char*>(v.data());
+    blob.insert(blob.end(), p, p + v.size() * sizeof(T));
+    return off;
+}
+
+}  // namespace
+
+bool build_tables(int m_max, Tables& out) {
+    if (m_max < 2 || m_max > 13) return false;
+    init_binom();
+
+    // ---- Golay words ----------------------------------------------------------------------------
+    std::vector<uint32_t> word(4096), gs;
+    const uint32_t gen = 0xC75;
+    for (uint32_t u = 0; u < 4096; u++) {
+        uint32_t c = 0;
+        for (int k = 0; k < 12; k++) if ((u >> k) & 1u) c ^= gen << k;
+        if (popcnt(c) & 1) c |= 1u << 23;
+        word[u] = c;
+    }
+    int woff[25];
+    for (int wt = 0; wt <= 24; wt++) {
+        woff[wt] = (int)gs.size();
+        for (uint32_t u = 0; u < 4096; u++) if (popcnt(word[u]) == wt) gs.push_back(word[u]);
+    }
+    if (gs.size() != 4096 || woff[8] != 1 || woff[12] != 760 || woff[16] != 3336 || woff[24] != 4095) return false;
+
+    // ---- classes ----------------------------------------------------------------------------------
+    std::vector<Leader> cls;
+    uint64_t running = 0;
+    for (int m = 2; m <= m_max; m++) {
+        std::vector<Leader> shell;
+        int vmax = (int)std::floor(std::sqrt(16.0 * m) + 1e-9);
+        for (int odd = 0; odd < 2; odd++) {
+            Leader cur;
+            std::vector<Leader> raw;
+            int v0 = (vmax % 2 == odd) ? vmax : vmax - 1;
+            enumerate(m, odd != 0, v0, 24, 16 * m, cur, raw);
+            for (Leader& L : raw) {
+                L.m = m; L.odd = odd != 0;
+                if (L.odd) {
+                    L.w = 0; L.A = 4096; L.B = 0; L.P1 = multinomial(L.cnt); L.P0 = 1;
+                } else {
+                    std::vector<int> c1, c0;
+                    int w = 0, n4 = 0, nnz0 = 0;
+                    for (size_t i = 0; i < L.val.size(); i++) {
+                        if (L.val[i] % 4 == 2) { c1.push_back(L.cnt[i]); w += L.cnt[i]; }
+                        else { c0.push_back(L.cnt[i]); if (L.val[i]) nnz0 += L.cnt[i]; }
+                        if (L.val[i] % 8 == 4) n4 += L.cnt[i];
+                    }
+                    if (!(w == 0 || w == 8 || w == 12 || w == 16 || w == 24)) continue;
+                    if (w == 0 && (n4 & 1)) continue;
+                    L.w = w;
+                    L.A = (w == 0 || w == 24) ? 1 : (w == 12 ? 2576 : 759);
+                    L.B = (w ? w - 1 : 0) + nnz0;
+                    L.P1 = multinomial(c1); L.P0 = multinomial(c0);
+                }
+                L.size = L.A * L.P1 * L.P0 << L.B;
+                shell.push_back(L);
+            }
+        }
+        std::sort(shell.begin(), shell.end(), leader_less);
+        for (Leader& L : shell) { L.offset = running; running += L.size; cls.push_back(L); }
+    }
+    const uint32_t ncls = (uint32_t)cls.size();
+    if (running >= (1ull << 48)) return false;
+
+    // ---- lut12: colex rank -> mask, grouped by popcount ---------------------------------------------
+    std::vector<uint16_t> lut12;
+    int b12[14];
+    for (int p = 0; p <= 12; p++) {
+        b12[p] = (int)lut12.size();
+        for (uint32_t mk : masks_in_colex_order(12, p)) lut12.push_back((uint16_t)mk);
+    }
+    b12[13] = (int)lut12.size();
+
+    // ---- inner-word tables ------------------------------------------------------------------------
+    // Pattern = multiplicities of the values of the word in descending value order, over q slots.
+    // Entry rho: mixed radix, digit of the largest value least significant, each digit the colex rank of
+    // the subset that value occupies among the slots still free; the smallest value takes the rest.
+    // Planes: bit k of plane a/b = bit 0/1 of (symbol index + sym_base) of the value on slot k.
+    std::vector<uint32_t> inner;
+    std::map<std::pair<std::vector<int>, int>, uint32_t> inner_base;
+    auto inner_table = [&](const std::vector<int>& cnt, int sym_base) -> int64_t {
+        auto key = std::make_pair(cnt, sym_base);
+        auto it = inner_base.find(key);
+        if (it != inner_base.end()) return it->second;
+        int q = 0;
+        for (int c : cnt) q += c;
+        if (q > 16 || (int)cnt.size() + sym_base > 4) return -1;
+        uint64_t P = multinomial(cnt);
+        uint32_t base = (uint32_t)inner.size();
+        std::vector<std::vector<uint32_t>> cm(cnt.size());
+        for (size_t i = 0; i < cnt.size(); i++) cm[i] = masks_in_colex_order(q, cnt[i]);   // over-long lists are harmless
+        for (uint64_t rho = 0; rho < P; rho++) {
+            uint64_t r = rho;
+            uint32_t freemask = (q == 32) ? 0xFFFFFFFFu : ((1u << q) - 1u), pa = 0, pb = 0;
+            for (size_t i = 0; i < cnt.size(); i++) {
+                uint32_t occ;
+                int nfree = popcnt(freemask);
+                if (i + 1 == cnt.size()) occ = freemask;
+                else {
+                    uint64_t radix = g_binom[nfree][cnt[i]];
+                    occ = deposit(cm[i][r % radix], freemask);
+                    r /= radix;
+                }
+                int sym = (int)i + sym_base;
+                if (sym & 1) pa |= occ;
+                if (sym & 2) pb |= occ;
+                freemask &= ~occ;
+            }
+            inner.push_back(pa | (pb << 16));
+        }
+        inner_base[key] = base;
+        return base;
+    };
+    const int64_t dummy_tb = inner_table(std::vector<int>{}, 0);   // one all-zero entry
+    if (dummy_tb != 0) return false;
+
+    // ---- subset ranking tables ---------------------------------------------------------------------
+    // q-subsets of n slots, slots 0..11 low, 12..n-1 high; order: number j of high slots, then colex rank
+    // of the high part, then colex rank of the low part.
+    std::vector<SplitEnt> split;
+    std::vector<uint8_t> guess;
+    struct SplitInfo { uint16_t sp; int shift, jmax, row; };
+    std::map<std::pair<int, int>, SplitInfo> split_of;
+    auto split_table = [&](int n, int q) -> SplitInfo {
+        auto key = std::make_pair(n, q);
+        auto it = split_of.find(key);
+        if (it != split_of.end()) return it->second;
+        int nl = std::min(n, 12), nh = n - nl;
+        int jmin = std::max(0, q - nl), jmax = std::min(q, nh);
+        SplitInfo si;
+        si.sp = (uint16_t)((int)split.size() - jmin);      // entry of j is split[sp + j]
+        si.jmax = jmax;
+        si.row = (int)(guess.size() / 32);
+        std::vector<uint64_t> bases;
+        uint64_t base = 0;
+        for (int j = jmin; j <= jmax; j++) {
+            SplitEnt e{};
+            uint64_t div = g_binom[nl][q - j];
+            e.base = (uint32_t)base;
+            e.div = (uint16_t)div;
+            float inv = 1.0f / (float)div;
+            while ((double)inv * (double)div < 1.0) inv = std::nextafterf(inv, 2.0f);
+            e.inv = inv;
+            e.b12lo = (uint16_t)b12[q - j];
+            e.b12hi = (uint16_t)b12[j];
+            split.push_back(e);
+            bases.push_back(base);
+            base += g_binom[nh][j] * div;
+        }
+        uint64_t total = base;                              // C(n, q)
+        int shift = 0;
+        while (((total - 1) >> shift) >= 32) shift++;
+        si.shift = shift;
+        for (int b = 0; b < 32; b++) {
+            uint64_t d0 = (uint64_t)b << shift;
+            int j = jmin;
+            while (j < jmax && bases[j + 1 - jmin] <= d0) j++;
+            guess.push_back((uint8_t)j);
+        }
+        split_of[key] = si;
+        return si;
+    };
+
+    // ---- class records ---------------------------------------------------------------------------
+    std::vector<ClassRec> recs(ncls);
+    std::vector<uint64_t> cls_off(ncls + 1);
+    for (uint32_t ci = 0; ci < ncls; ci++) {
+        const Leader& L = cls[ci];
+        ClassRec R{};
+        cls_off[ci] = L.offset;
+        bool f1direct = !L.odd && L.w > 0 && L.w <= 16;
+        bool outer_all = L.odd || L.w == 24;
+        // values of the outer domain and of the direct F1 word
+        std::vector<int> ov, oc, dv, dc;
+        for (size_t i = 0; i < L.val.size(); i++) {
+            bool isF1 = !L.odd && (L.val[i] % 4 == 2);
+            if (f1direct && isF1) { dv.push_back(L.val[i]); dc.push_back(L.cnt[i]); }
+            else { ov.push_back(L.val[i]); oc.push_back(L.cnt[i]); }
+        }
+        int n = 0;
+        for (int c : oc) n += c;
+        // outside value: 0 for the F0 domain of even classes (whether present or not), otherwise the most
+        // frequent value, ties towards the smaller value
+        int outside = 0;
+        if (outer_all) {
+            size_t best = 0;
+            for (size_t i = 0; i < ov.size(); i++)
+                if (oc[i] > oc[best] || (oc[i] == oc[best] && ov[i] < ov[best])) best = i;
+            outside = ov[best];
+        }
+        std::vector<int> mv, mc;    // minority values, descending
+        for (size_t i = 0; i < ov.size(); i++) if (ov[i] != outside) { mv.push_back(ov[i]); mc.push_back(oc[i]); }
+        int q = 0;
+        for (int c : mc) q += c;
+        uint64_t Pin = multinomial(mc);
+        uint64_t P1 = f1direct ? multinomial(dc) : 1;
+        // consistency with the class cardinality
+        uint64_t arr = g_binom[n][q] * Pin * P1;
+        if (arr != L.P1 * L.P0) return false;
+        int sym_base0 = outer_all ? 0 : 1;
+        int64_t tb0 = mc.empty() ? dummy_tb : inner_table(mc, sym_base0);
+        int64_t tb1 = f1direct ? inner_table(dc, 0) : dummy_tb;
+        if (tb0 < 0 || tb1 < 0 || tb0 > 0xFFFF || tb1 > 0xFFFF) return false;
+        SplitInfo si = split_table(n, q);
+        uint64_t PP = P1 * Pin;
+        if (PP >= (1u << 22) || P1 > 0xFFFF) return false;
+        R.PP = (uint32_t)PP;
+        R.invPP = (1.0 / (double)PP) * (1.0 + std::ldexp(1.0, -50));
+        float i1 = 1.0f / (float)P1;
+        while ((double)i1 * (double)P1 < 1.0) i1 = std::nextafterf(i1, 2.0f);
+        R.invP1 = i1;
+        R.P1 = (uint16_t)P1; R.tb0 = (uint16_t)tb0; R.tb1 = (uint16_t)tb1; R.sp = si.sp;
+        // parity of the number of negative signs on F1 (condition (iii) of L_even): with a = 4y on F0 and
+        // a = 2 + 4u on F1, sum x = 4 (sum y + sum u + #negative F1) (mod 8) because 2w = 0 (mod 8).
+        int kappa = 0;
+        if (!L.odd) for (size_t i = 0; i < L.val.size(); i++) {
+            int t = (L.val[i] % 4 == 2) ? (L.val[i] - 2) / 4 : L.val[i] / 4;
+            kappa ^= (t * L.cnt[i]) & 1;
+        }
+        int acode = L.A == 1 ? 0 : (L.A == 759 ? 1 : (L.A == 2576 ? 2 : 3));
+        int wm1 = (!L.odd && L.w > 0) ? L.w - 1 : 0;
+        R.f0 = (uint32_t)(L.odd ? 1 : 0) << F0_ODD | (uint32_t)(f1direct ? 1 : 0) << F0_F1DIRECT |
+               (uint32_t)(outer_all ? 1 : 0) << F0_OUTER_ALL | (uint32_t)wm1 << F0_WM1 |
+               (uint32_t)((!L.odd && L.w > 0) ? 1 : 0) << F0_FEN | (uint32_t)kappa << F0_KAPPA |
+               (uint32_t)L.B << F0_B | (uint32_t)L.m << F0_M | (uint32_t)n << F0_N | (uint32_t)q << F0_Q;
+        int goff = L.odd ? 0 : woff[L.w];
+        R.f1 = (uint32_t)goff << F1_GOFF | (uint32_t)acode << F1_ACODE | (uint32_t)si.shift << F1_GSHIFT |
+               (uint32_t)si.jmax << F1_JMAX | (uint32_t)si.row << F1_GROW;
+        // value of each nibble code.  Outer domain = all positions (odd, w = 24): code 0 = outside value,
+        // 4 + i = i-th minority value.  Otherwise: 0 = zero, 1 + i = i-th nonzero F0 value, 4 + i = i-th F1 value.
+        int code_val[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (outer_all) {
+            code_val[0] = outside;
+            for (size_t i = 0; i < mv.size(); i++) code_val[4 + i] = mv[i];
+        } else {
+            for (size_t i = 0; i < mv.size(); i++) code_val[1 + i] = mv[i];
+            for (size_t i = 0; i < dv.size(); i++) code_val[4 + i] = dv[i];
+        }
+        uint64_t v8 = 0, vi = 0;
+        for (int k = 0; k < 8; k++) {
+            int v = code_val[k];
+            bool neg = L.odd && (v % 4 == 3);      // odd classes: x_i = 1 + 2 c_i (mod 4); the word bit flips it again
+            v8 |= (uint64_t)(fp8_e4m3(v) | (neg ? 0x80 : 0)) << (8 * k);
+            vi |= (uint64_t)(uint8_t)(int8_t)(neg ? -v : v) << (8 * k);
+        }
+        R.vt8_lo = (uint32_t)v8; R.vt8_hi = (uint32_t)(v8 >> 32);
+        R.vti_lo = (uint32_t)vi; R.vti_hi = (uint32_t)(vi >> 32);
+        recs[ci] = R;
+    }
+    cls_off[ncls] = running;
+
+    // ---- bucket table: index >> shift -> class holding the first index of the bucket --------------------
+    const uint32_t bucket_shift = 37, nbuckets = 2048;
+    std::vector<uint16_t> bucket(nbuckets);
+    for (uint32_t b = 0; b < nbuckets; b++) {
+        uint64_t first = (uint64_t)b << bucket_shift;
+        uint32_t ci = (uint32_t)(std::upper_bound(cls_off.begin(), cls_off.begin() + ncls, first) - cls_off.begin());
+        bucket[b] = (uint16_t)(ci == 0 ? 0 : ci - 1);
+    }
+
+    // ---- 6-bit deposit tables ---------------------------------------------------------------------
+    std::vector<uint8_t> pdep6(4096);
+    std::vector<uint32_t> spread6(4096);
+    for (uint32_t F = 0; F < 64; F++)
+        for (uint32_t mbits = 0; mbits < 64; mbits++) {
+            uint32_t dep = deposit(mbits, F);
+            pdep6[F << 6 | mbits] = (uint8_t)dep;
+            uint32_t sp = 0;
+            for (int p = 0; p < 6; p++) {
+                if ((dep >> p) & 1u) sp |= 1u << (4 * kNibbleSlot[p]);
+                if ((F >> p) & 1u) sp |= 4u << (4 * kNibbleSlot[p]);
+            }
+            spread6[F << 6 | mbits] = sp;
+        }
+
+    // ---- blob ------------------------------------------------------------------------------------
+    TableLayout lay{};
+    std::vector<unsigned char> blob;
+    lay.gs = append(blob, gs);
+    lay.spread6 = append(blob, spread6);
+    lay.pdep6 = append(blob, pdep6);
+    lay.lut12 = append(blob, lut12);
+    lay.bucket = append(blob, bucket);
+    lay.cls_off = append(blob, cls_off);
+    lay.cls = append(blob, recs);
+    lay.split = append(blob, split);
+    lay.guess = append(blob, guess);
+    lay.inner = append(blob, inner);
+    while (blob.size() % 16) blob.push_back(0);
+    lay.lds_bytes = (uint32_t)blob.size();
+    lay.total_bytes = (uint32_t)blob.size();
+    lay.ncls = ncls;
+    lay.inner_entries = (uint32_t)inner.size();
+    lay.bucket_shift = bucket_shift;
+    lay.nbuckets = nbuckets;
+    lay.npoints = running;
+    for (int m = 0; m < 16; m++) lay.rnorm[m] = m >= 1 ? (float)(1.0 / std::sqrt(16.0 * m)) : 0.0f;
+    out.lay = lay;
+    out.blob.swap(blob);
+    return true;
+}
+
+}  // namespace llvq

@@ -1,0 +1,39 @@
+// Test-only harness: runs the library's table builder and its index -> block reconstruction on the host CPU
+// so that the host logic (tables, digit extraction, ranking) can be compared with the oracle without a GPU.
+// It is not part of the library and nothing in the product links to it.
+#include <cstdint>
+#include <cstring>
+
+#include "../../paper_2603_11021_amd/csrc/llvq_decode_core.h"
+#include "../../paper_2603_11021_amd/csrc/llvq_tables.h"
+
+static llvq::Tables g_tabs;
+static bool g_ok = false;
+
+extern "C" {
+
+int emul_init(int m_max) {
+    g_ok = llvq::build_tables(m_max, g_tabs);
+    return g_ok ? 0 : -1;
+}
+
+uint32_t emul_lds_bytes() { return g_tabs.lay.lds_bytes; }
+uint32_t emul_num_classes() { return g_tabs.lay.ncls; }
+uint64_t emul_num_points() { return g_tabs.lay.npoints; }
+uint32_t emul_inner_entries() { return g_tabs.lay.inner_entries; }
+
+// returns the number of out-of-range indices (decoded to zero)
+uint64_t emul_decode_i8(const uint64_t* idx, uint64_t n, int8_t* out) {
+    const llvq::TabPtrs T = llvq::make_tab_ptrs(g_tabs.blob.data(), g_tabs.lay);
+    uint64_t bad = 0;
+    for (uint64_t k = 0; k < n; k++) {
+        if (idx[k] >= T.npoints) { bad++; std::memset(out + 24 * k, 0, 24); continue; }
+        uint32_t w[4], o[6];
+        const uint32_t cid = llvq::decode_block(T, idx[k], w);
+        llvq::nibbles_to_i8(w, T.cls[cid].vti_lo, T.cls[cid].vti_hi, o);
+        std::memcpy(out + 24 * k, o, 24);
+    }
+    return bad;
+}
+
+}  // extern "C"

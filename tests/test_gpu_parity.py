@@ -1,0 +1,184 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the oracle on the same seeded inputs.
+
+Bar: bit-exact for decoded integer coordinates; max|y - y_ref| / max|y_ref| <= 2e-3 for the fused product
+(fp16/bf16 activations, fp32 accumulation) against the oracle in fp64."""
+import numpy as np
+import pytest
+
+from paper_2603_11021_amd import synth
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_11021_amd import LLVQ
+    return LLVQ(13, 0)
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def _decode_both_formats(gpu, idx):
+    got48 = gpu.llvq_decode_i8(_dev(synth.pack_u48(idx).reshape(-1))).cpu().numpy()
+    got64 = gpu.llvq_decode_i8(_dev(idx.view(np.int64))).cpu().numpy()
+    return got48, got64
+
+
+def test_context_matches_oracle_tables(gpu, oracle13):
+    assert gpu.num_points == oracle13.num_points == synth.N_POINTS_M13
+    assert gpu.num_classes == oracle13.num_classes
+
+
+def test_config1_first_shell(gpu, oracle13):
+    # 65,536 seeded-uniform indices over the 196,560 minimal vectors, and then all of them
+    idx = synth.indices(synth.rng_for(1), 65536, synth.N_SHELL2)
+    want, _ = oracle13.decode(idx)
+    got48, got64 = _decode_both_formats(gpu, idx)
+    assert np.array_equal(got48, want) and np.array_equal(got64, want)
+    assert ((got48.astype(np.int64) ** 2).sum(axis=1) == 32).all()
+    allidx = np.arange(synth.N_SHELL2, dtype=np.uint64)
+    want, _ = oracle13.decode(allidx)
+    got48, _ = _decode_both_formats(gpu, allidx)
+    assert np.array_equal(got48, want)
+
+
+def test_union_every_class(gpu, oracle13):
+    rng = np.random.default_rng(31)
+    picks = []
+    for c in oracle13.classes():
+        picks += [c["offset"], c["offset"] + c["size"] - 1]
+        picks += [c["offset"] + int(v) for v in rng.integers(0, c["size"], 30)]
+    idx = np.array(picks, dtype=np.uint64)
+    want, _ = oracle13.decode(idx)
+    got48, got64 = _decode_both_formats(gpu, idx)
+    assert np.array_equal(got48, want) and np.array_equal(got64, want)
+
+
+@pytest.mark.parametrize("n", [1, 63, 64, 65, 1023, 1025, 4099, 300007])
+def test_union_random_ragged_sizes(gpu, oracle13, n):
+    idx = synth.indices(synth.rng_for(3, n), n)
+    want, _ = oracle13.decode(idx)
+    got48, got64 = _decode_both_formats(gpu, idx)
+    assert np.array_equal(got48, want) and np.array_equal(got64, want)
+
+
+def test_large_random_union(gpu, oracle13):
+    n = 1 << 21
+    idx = synth.indices(synth.rng_for(3, 77), n)
+    want, _ = oracle13.decode(idx)
+    got = gpu.llvq_decode_i8(_dev(synth.pack_u48(idx).reshape(-1))).cpu().numpy()
+    assert np.array_equal(got, want)
+
+
+def test_empty_and_invalid(gpu, oracle13):
+    import torch
+    out = gpu.llvq_decode_i8(torch.empty(0, dtype=torch.uint8, device="cuda:0"))
+    assert out.shape == (0, 24)
+    N = oracle13.num_points
+    idx = np.array([5, N, N - 1, 2 ** 48 - 1, 0, N + 12345], dtype=np.uint64)
+    want, bad = oracle13.decode(idx)
+    assert bad == 3
+    got48, got64 = _decode_both_formats(gpu, idx)
+    assert np.array_equal(got48, want) and np.array_equal(got64, want)
+    assert gpu.llvq_validate(_dev(synth.pack_u48(idx).reshape(-1))) == 3
+    assert gpu.llvq_validate(_dev(idx.view(np.int64))) == 3
+    from paper_2603_11021_amd import LLVQError
+    with pytest.raises(LLVQError):
+        gpu.llvq_decode_i8(torch.empty(6, dtype=torch.float32, device="cuda:0"))
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_shape_gain_decode(gpu, oracle13, dtype):
+    import torch
+    n = 50021
+    rng = synth.rng_for(5, 1)
+    idx = synth.indices(rng, n)
+    gain = synth.gains(rng, n)
+    want = oracle13.dequant(idx, gain)
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+    got = gpu.llvq_decode(_dev(synth.pack_u48(idx).reshape(-1)), _dev(gain), out_dtype=tdt).float().cpu().numpy().astype(np.float64)
+    # fp32 scale (two roundings) then one rounding to the output type
+    rel = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8, "f32": 0.0}[dtype] + 3 * 2.0 ** -24
+    assert (np.abs(got - want) <= rel * np.abs(want) + 1e-30).all()
+    # the block norm equals the gain
+    nrm = np.sqrt((got ** 2).sum(axis=1))
+    assert np.allclose(nrm, gain.astype(np.float64), rtol=4 * rel + 1e-6)
+
+
+def _matmul_case(gpu, oracle, config, ordinal, N, K, M, x_dtype=np.float16, sample_rows=None):
+    import torch
+    idx, gain, x = synth.layer(config, ordinal, N, K, M, x_dtype=x_dtype)
+    KB = idx.shape[1]
+    d_x = _dev(x).to(torch.bfloat16 if x_dtype == "bf16" else torch.float16)
+    assert np.array_equal(d_x.float().cpu().numpy(), x)                   # the device sees exactly the oracle's inputs
+    y = gpu.llvq_matmul(d_x, _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), N, KB).cpu().numpy().astype(np.float64)
+    assert y.shape == (M, N)
+    if sample_rows is None:
+        ref = oracle.matmul(x, idx, gain)
+        got = y
+    else:
+        rows = np.sort(np.random.default_rng(N + K).choice(N, sample_rows, replace=False))
+        ref = oracle.matmul(x, idx[rows], gain[rows])
+        got = y[:, rows]
+    err = np.abs(got - ref).max() / np.abs(ref).max()
+    assert err <= TOL, err
+    return err
+
+
+def test_config2_gemv_4096x4104(gpu, oracle13):
+    err = _matmul_case(gpu, oracle13, 2, 0, 4096, 4096, 1)
+    assert err < 1e-5        # fp32 accumulation of exact products: far inside the 2e-3 bar
+
+
+@pytest.mark.parametrize("N,K,M", [(1, 24, 1), (1, 23, 1), (37, 100, 1), (64, 24, 3), (129, 4104, 2), (1000, 1000, 1),
+                                   (513, 171 * 24, 5), (300, 14336, 1), (77, 600, 16), (50, 480, 17)])
+def test_matmul_ragged_shapes(gpu, oracle13, N, K, M):
+    _matmul_case(gpu, oracle13, 6, N * 7 + M, N, K, M)
+
+
+def test_matmul_bf16_activations(gpu, oracle13):
+    _matmul_case(gpu, oracle13, 4, 0, 256, 4096, 4, x_dtype="bf16")
+
+
+def test_matmul_u64_indices(gpu, oracle13):
+    import torch
+    idx, gain, x = synth.layer(6, 999, 200, 960, 2)
+    y48 = gpu.llvq_matmul(_dev(x).half(), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), 200, 40)
+    y64 = gpu.llvq_matmul(_dev(x).half(), _dev(idx.view(np.int64).reshape(-1)), _dev(gain.reshape(-1)), 200, 40)
+    assert torch.equal(y48, y64)
+    ref = oracle13.matmul(x, idx, gain)
+    assert np.abs(y64.cpu().numpy() - ref).max() / np.abs(ref).max() <= TOL
+
+
+@pytest.mark.parametrize("name", ["k", "gate", "down"])
+def test_llama3_8b_layer_shapes_batch1_and_16(gpu, oracle13, name):
+    N, K = synth.LLAMA3_8B[name]
+    for M in (1, 16):
+        _matmul_case(gpu, oracle13, 3, hash(name) % 100 + M, N, K, M, sample_rows=256)
+
+
+@pytest.mark.parametrize("name", ["q", "down"])
+def test_llama3_70b_layer_shapes_batch1(gpu, oracle13, name):
+    N, K = synth.LLAMA3_70B[name]
+    _matmul_case(gpu, oracle13, 5, hash(name) % 100, N, K, 1, sample_rows=128)
+
+
+def test_matmul_invalid_arguments(gpu):
+    import torch
+    from paper_2603_11021_amd import LLVQError
+    x = torch.zeros(1, 48, dtype=torch.float16, device="cuda:0")
+    idx = torch.zeros(2 * 2 * 6, dtype=torch.uint8, device="cuda:0")
+    g = torch.ones(4, dtype=torch.float16, device="cuda:0")
+    y = gpu.llvq_matmul(x, idx, g, 2, 2)          # index 0 = (4,4,0,...)/sqrt(32), x = 0
+    assert not y.any()
+    with pytest.raises(LLVQError):
+        gpu.llvq_matmul(x, idx, g, 3, 2)          # sizes do not match
+    with pytest.raises(LLVQError):
+        gpu._check(gpu._lib.llvq_matmul(gpu._h, x.data_ptr() + 2, 0, 1, idx.data_ptr(), 0, g.data_ptr(), 2, 2, y.data_ptr(), None), "misaligned x")

@@ -1,0 +1,114 @@
+"""CPU-only tests of the library's host side: C-ABI surface, table builder and the index -> block
+reconstruction code compiled for the host (tests/host_emul), compared with the oracle."""
+import ctypes
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2603_11021_amd", "libllvq.so")
+EMUL = os.path.join(ROOT, "tests", "host_emul", "libemul.so")
+
+
+@pytest.fixture(scope="module")
+def emul():
+    if not os.path.exists(EMUL):
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", EMUL,
+                               os.path.join(ROOT, "tests", "host_emul", "emul.cpp"),
+                               os.path.join(ROOT, "paper_2603_11021_amd", "csrc", "llvq_tables.cpp")])
+    lib = ctypes.CDLL(EMUL)
+    lib.emul_num_points.restype = ctypes.c_uint64
+    lib.emul_decode_i8.restype = ctypes.c_uint64
+    lib.emul_decode_i8.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+    assert lib.emul_init(13) == 0
+
+    def decode(idx):
+        idx = np.ascontiguousarray(idx, dtype=np.uint64)
+        out = np.empty((idx.size, 24), dtype=np.int8)
+        bad = lib.emul_decode_i8(idx.ctypes.data, idx.size, out.ctypes.data)
+        return out, int(bad)
+
+    decode.lib = lib
+    return decode
+
+
+def _built_lib():
+    if not os.path.exists(LIB):
+        pytest.skip("libllvq.so not built (run __graft_entry__.build())")
+    return ctypes.CDLL(LIB)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = _built_lib()
+    header = open(os.path.join(ROOT, "include", "llvq.h")).read()
+    names = sorted(set(re.findall(r"\b(llvq_[a-z0-9_]+)\s*\(", header)))
+    assert {"llvq_create", "llvq_destroy", "llvq_decode_i8", "llvq_decode", "llvq_matmul", "llvq_validate"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_no_cpu_fallback_without_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    lib = _built_lib()
+    h = ctypes.c_void_p()
+    rc = lib.llvq_create(ctypes.byref(h), 13, 0)
+    assert rc == -3 and not h.value                       # LLVQ_EHIP: fails loudly, no context
+    lib.llvq_strerror.restype = ctypes.c_char_p
+    assert b"HIP" in lib.llvq_strerror(rc)
+    assert lib.llvq_create(ctypes.byref(h), 14, 0) == -1  # LLVQ_EINVAL
+    assert lib.llvq_create(None, 13, 0) == -1
+
+
+def test_tables_fit_in_lds(emul, oracle13):
+    lib = emul.lib
+    assert lib.emul_num_classes() == oracle13.num_classes == 383
+    assert lib.emul_num_points() == oracle13.num_points
+    assert lib.emul_lds_bytes() + 64 * 8 * 4 <= 160 * 1024       # tables + the product kernel's row accumulators
+
+
+def test_host_decode_matches_oracle_on_shell2(emul, oracle13):
+    I = np.arange(196560, dtype=np.uint64)
+    got, bad = emul(I)
+    want, _ = oracle13.decode(I)
+    assert bad == 0 and np.array_equal(got, want)
+
+
+def test_host_decode_matches_oracle_on_every_class(emul, oracle13):
+    rng = np.random.default_rng(21)
+    picks = []
+    for c in oracle13.classes():
+        picks += [c["offset"], c["offset"] + c["size"] - 1]
+        picks += [c["offset"] + int(v) for v in rng.integers(0, c["size"], 64)]
+    I = np.array(picks, dtype=np.uint64)
+    got, bad = emul(I)
+    want, _ = oracle13.decode(I)
+    assert bad == 0 and np.array_equal(got, want)
+
+
+def test_host_decode_matches_oracle_on_random_union(emul, oracle13):
+    rng = np.random.default_rng(22)
+    I = rng.integers(0, oracle13.num_points, 400000, dtype=np.uint64)
+    got, bad = emul(I)
+    want, _ = oracle13.decode(I)
+    assert bad == 0 and np.array_equal(got, want)
+
+
+def test_host_decode_out_of_range(emul, oracle13):
+    got, bad = emul(np.array([oracle13.num_points, 2 ** 48 - 1, 5], dtype=np.uint64))
+    assert bad == 2 and not got[:2].any() and got[2].any()
+
+
+def test_synth_pack_u48():
+    from paper_2603_11021_amd import synth
+    idx = np.array([[0, 1, 2 ** 48 - 1], [0x0102030405, 280974212784719, 7]], dtype=np.uint64)
+    b = synth.pack_u48(idx)
+    assert b.shape == (2, 3, 6) and b.dtype == np.uint8
+    back = sum(b[..., i].astype(np.uint64) << np.uint64(8 * i) for i in range(6))
+    assert np.array_equal(back, idx)
+    x = synth.activations(synth.rng_for(2), 2, 4096)
+    assert x.shape == (2, 4104) and not x[:, 4096:].any() and x[:, :4096].any()
