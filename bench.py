@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the LLVQ hot path on one MI355X: fused dequant-GEMV at batch 1 (paper App. C).
+
+A step = one call of llvq_matmul (index fetch, class lookup, unflatten, placement, signs, shape-gain scale,
+24-wide dot products, row reduction) over one synthetic 4096 x 4104 layer at ~2 bits/weight (48-bit index +
+fp16 gain per block of 24 weights), inputs resident in HBM.  Steps cycle through a ring of distinct layers
+larger than the last-level cache, so the packed weights really stream from HBM.
+
+Prints ONE JSON line: whole-job packed-weight GB/s, the HBM roofline of the matmul kernel (algorithmic bytes:
+8 per block), and the oracle timed on the host CPU on the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--layers", type=int, default=96, help="distinct layers in the ring (96 x 5.6 MB = 538 MB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set (stderr)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (sharding is design-only)" % args.gpus)
+
+    import numpy as np
+    import torch
+    from paper_2603_11021_amd import LLVQ, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the library has no CPU path")
+    dev = torch.device("cuda:0")
+    q = LLVQ(13, 0)
+
+    N, K, M = 4096, 4096, 1
+    KB = synth.blocks_per_row(K)            # 171 blocks, K_pad = 4104
+    nblk = N * KB
+    # ring of distinct layers: uniform indices over the union of shells 2..13, log-normal gains
+    rng = synth.rng_for(2, 0)
+    idx0 = synth.indices(rng, (N, KB))
+    gain0 = synth.gains(rng, (N, KB))
+    x0 = synth.activations(rng, M, K)
+    ring_idx, ring_gain = [], []
+    for l in range(args.layers):
+        if l == 0:
+            idx, gain = idx0, gain0
+        else:
+            r = synth.rng_for(2, l)
+            idx, gain = synth.indices(r, (N, KB)), synth.gains(r, (N, KB))
+        ring_idx.append(torch.from_numpy(synth.pack_u48(idx).reshape(-1)).to(dev))
+        ring_gain.append(torch.from_numpy(gain.reshape(-1)).to(dev))
+    d_x = torch.from_numpy(x0.astype(np.float16)).to(dev)
+    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+
+    def step(i):
+        l = i % args.layers
+        q.llvq_matmul(d_x, ring_idx[l], ring_gain[l], N, KB, out=y)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(args.warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = e0.elapsed_time(e1) / args.steps          # HIP events on the launch stream: avg per launch
+    ms_per_step = wall * 1e3 / args.steps
+    gbs = BYTES_PER_BLOCK * nblk / (ms_per_step * 1e-3) / 1e9
+    ach = BYTES_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e9
+
+    # parity of the timed configuration against the oracle on sampled rows (layer 0)
+    from oracle.llvq_oracle import Oracle
+    oracle = Oracle(13)
+    step(0)
+    rows = np.arange(0, N, 64)
+    ref = oracle.matmul(x0, idx0[rows], gain0[rows])
+    err = float(np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - ref).max() / np.abs(ref).max())
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        t = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - t < 10.0:
+            oracle.matmul(x0, idx0, gain0)
+            reps += 1
+        dt = (time.perf_counter() - t) / reps
+        cpu = {"value": BYTES_PER_BLOCK * nblk / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "sample": "full 4096x4104 batch-1 layer (700,416 blocks), %d repetitions, single thread" % reps,
+               "blocks_per_s": nblk / dt}
+
+    if args.extra:
+        extra_layer_set(q, synth, torch, dev)
+
+    out = {
+        "metric": "LLVQ dequant-GEMV GB/s (packed weights)", "value": gbs, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": "dequant-GEMV batch 1, W 4096x4104 (171 blocks of 24 per row), 48-bit indices uniform over "
+                               "Lambda24(13) + fp16 gain per block, x fp16, y fp32; ring of %d distinct layers" % args.layers,
+                   "N": N, "K_pad": 24 * KB, "M": M, "blocks_per_step": nblk},
+        "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
+        "max_rel_err_vs_oracle": err,
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": None, "kernel": "matmul_kernel<U48,f16>", "kernel_ms": kern_ms,
+                     "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+def extra_layer_set(q, synth, torch, dev):
+    """One pass over the seven linear layers of a Llama-3-8B-shaped block, distinct buffers, batch 1 (stderr)."""
+    import numpy as np
+    layers = []
+    tot = 0
+    for rep in range(4):
+        for i, (name, (N, K)) in enumerate(synth.LLAMA3_8B.items()):
+            KB = synth.blocks_per_row(K)
+            r = synth.rng_for(3, 10 * rep + i)
+            idx = torch.from_numpy(synth.pack_u48(synth.indices(r, (N, KB))).reshape(-1)).to(dev)
+            gain = torch.from_numpy(synth.gains(r, (N, KB)).reshape(-1)).to(dev)
+            x = torch.from_numpy(synth.activations(r, 1, K).astype(np.float16)).to(dev)
+            y = torch.empty((1, N), dtype=torch.float32, device=dev)
+            layers.append((name, x, idx, gain, N, KB, y))
+            tot += N * KB
+    for _ in range(2):
+        for (_, x, idx, gain, N, KB, y) in layers:
+            q.llvq_matmul(x, idx, gain, N, KB, out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 5
+    e0.record()
+    for _ in range(reps):
+        for (_, x, idx, gain, N, KB, y) in layers:
+            q.llvq_matmul(x, idx, gain, N, KB, out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    print("llama3-8b layer set x4 (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed" % (tot * 8 / 1e6, ms, tot * 8 / ms / 1e6),
+          file=sys.stderr)
+
+
+if __name__ == "__main__":
+    main()

@@ -65,89 +65,176 @@ LLVQ_HD uint32_t popc32(uint32_t v) {
 
 LLVQ_HD uint32_t bfe6(uint32_t v, uint32_t off) { return (v >> off) & 63u; }
 
-// Decodes index I (must be < npoints).  Returns the class id; w[0..3] receive the nibble words.
-LLVQ_HD uint32_t decode_block(const TabPtrs& T, uint64_t I, uint32_t w[4]) {
+// Entry (F, m) of the 6-bit deposit tables sits at F*64 + (m ^ F): the frequent all-zero sources of different
+// masks then fall into different LDS banks instead of all into bank 0.
+LLVQ_HD uint32_t dep_key(uint32_t F, uint32_t m) { return (F << 6) | (m ^ F); }
+
+// true when `v` holds for any active lane of the wavefront (always true on the host, where it only gates work)
+LLVQ_HD bool wave_any(bool v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_ballot_w64(v) != 0;
+#else
+    (void)v;
+    return true;
+#endif
+}
+
+// Decodes NB indices per lane (each must be < npoints), stage by stage so that the table reads of the NB
+// blocks are independent and overlap.  cid[u] receives the class id, w[u][0..3] the nibble words.
+struct BlockInfo {
+    uint32_t cid;                // class id
+    uint32_t m;                  // shell
+    uint32_t vt8_lo, vt8_hi;     // value table of the class, fp8 bytes
+    uint32_t vti_lo, vti_hi;     // value table of the class, int8
+};
+
+template <int NB>
+LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
+    uint32_t cid[NB];
     // App. A steps 1-2: shell and class in one search over the global class offsets
-    uint32_t cid = T.bucket[(uint32_t)(I >> T.bucket_shift)];
-    while (cid + 1 < T.ncls && I >= T.cls_off[cid + 1]) cid++;
-    const ClassRec R = T.cls[cid];
-    const uint64_t Ic = I - T.cls_off[cid];
-    const uint32_t f0 = R.f0, f1 = R.f1;
+    uint64_t off[NB], nxt[NB];
+#pragma unroll
+    for (int u = 0; u < NB; u++) {
+        cid[u] = T.bucket[(uint32_t)(I[u] >> T.bucket_shift)];
+        off[u] = T.cls_off[cid[u]];
+        nxt[u] = T.cls_off[cid[u] + 1];
+    }
+    for (;;) {
+        bool more = false;
+#pragma unroll
+        for (int u = 0; u < NB; u++) {
+            if (I[u] >= nxt[u] && cid[u] + 1 < T.ncls) {
+                cid[u]++;
+                off[u] = nxt[u];
+                nxt[u] = T.cls_off[cid[u] + 1];
+                more = true;
+            }
+        }
+        if (!more) break;
+    }
 
-    // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
-    // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
-    const uint32_t acode = (f1 >> F1_ACODE) & 3u;
-    const double A = acode == 0 ? 1.0 : (acode == 1 ? 759.0 : (acode == 2 ? 2576.0 : 4096.0));
-    constexpr double kNudge = 1.0 + 0x1p-50;
-    const double invA = acode == 0 ? 1.0 : (acode == 1 ? (1.0 / 759.0) * kNudge : (acode == 2 ? (1.0 / 2576.0) * kNudge : 0x1p-12));
-    const double x = (double)Ic;
-    const double q1 = floor(x * invA);
-    const uint32_t r = (uint32_t)fma(-q1, A, x);
-    const int B = (int)((f0 >> F0_B) & 31u);
-    const double ipp = floor(ldexp(q1, -B));
-    const uint32_t s = (uint32_t)fma(-ipp, ldexp(1.0, B), q1);
-    // I'' = (d * Pin + rin) * P1 + rho1
-    const double dd = floor(ipp * R.invPP);
-    const uint32_t rem = (uint32_t)fma(-dd, (double)R.PP, ipp);
-    const uint32_t d = (uint32_t)dd;
-    const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
-    const uint32_t rho1 = rem - rin * R.P1;
-
-    // the Golay word selected by r
-    const uint32_t c = T.gs[((f1 >> F1_GOFF) & 4095u) + r];
+    ClassRec R[NB];
+    uint32_t c[NB], U[NB], e0[NB], e1[NB], s[NB], d[NB], j[NB];
+#pragma unroll
+    for (int u = 0; u < NB; u++) {
+        R[u] = T.cls[cid[u]];
+        const uint64_t Ic = I[u] - off[u];
+        const uint32_t f0 = R[u].f0, f1 = R[u].f1;
+        // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
+        // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
+        const uint32_t acode = (f1 >> F1_ACODE) & 3u;
+        const double A = acode == 0 ? 1.0 : (acode == 1 ? 759.0 : (acode == 2 ? 2576.0 : 4096.0));
+        constexpr double kNudge = 1.0 + 0x1p-50;
+        const double invA = acode == 0 ? 1.0 : (acode == 1 ? (1.0 / 759.0) * kNudge : (acode == 2 ? (1.0 / 2576.0) * kNudge : 0x1p-12));
+        const double x = (double)Ic;
+        const double q1 = floor(x * invA);
+        const uint32_t r = (uint32_t)fma(-q1, A, x);
+        const int B = (int)((f0 >> F0_B) & 31u);
+        const double ipp = floor(ldexp(q1, -B));
+        s[u] = (uint32_t)fma(-ipp, ldexp(1.0, B), q1);
+        // I'' = (d * Pin + rin) * P1 + rho1
+        const double dd = floor(ipp * R[u].invPP);
+        const uint32_t rem = (uint32_t)fma(-dd, (double)R[u].PP, ipp);
+        d[u] = (uint32_t)dd;
+        const uint32_t rin = (uint32_t)((double)rem * (double)R[u].invP1);
+        const uint32_t rho1 = rem - rin * R[u].P1;
+        // the Golay word selected by r, the symbol planes over the slots of U (e0) and over the F1 slots (e1)
+        c[u] = T.gs[((f1 >> F1_GOFF) & 4095u) + r];
+        e0[u] = T.inner[R[u].tb0 + rin];
+        e1[u] = T.inner[R[u].tb1 + rho1];
+        j[u] = T.guess[((f1 >> F1_GROW) & 63u) * 32u + (d[u] >> ((f1 >> F1_GSHIFT) & 31u))];
+    }
 
     // App. A step 4, placement: the q-subset U of the outer domain's n slots with rank d
-    uint32_t j = T.guess[((f1 >> F1_GROW) & 63u) * 32u + (d >> ((f1 >> F1_GSHIFT) & 31u))];
-    const uint32_t jmax = (f1 >> F1_JMAX) & 15u;
-    while (j < jmax && d >= T.split[(uint16_t)(R.sp + j + 1)].base) j++;
-    const SplitEnt e = T.split[(uint16_t)(R.sp + j)];
-    const uint32_t dl = d - e.base;
-    const uint32_t rk_hi = (uint32_t)((double)dl * (double)e.inv);
-    const uint32_t rk_lo = dl - rk_hi * e.div;
-    const uint32_t U = (uint32_t)T.lut12[e.b12lo + rk_lo] | ((uint32_t)T.lut12[e.b12hi + rk_hi] << 12);
-
-    // symbol planes over the slots of U (a0, b0) and over the F1 slots (a1, b1)
-    const uint32_t e0 = T.inner[R.tb0 + rin];
-    const uint32_t e1 = T.inner[R.tb1 + rho1];
-    const uint32_t a0 = e0 & 0xFFFFu, b0 = e0 >> 16, a1 = e1 & 0xFFFFu, b1 = e1 >> 16;
-
-    // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so that
-    // the number of negative F1 coordinates has the parity condition (iii) asks for
-    const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
-    uint32_t s1 = s & ((1u << wm1) - 1u);
-    const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
-    s1 |= forced << wm1;
-    const uint32_t s0 = s >> wm1;
-
-    const bool odd = (f0 >> F0_ODD) & 1u;
-    const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
-    const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? c : 0u;             // slots of the direct F1 word
-    const uint32_t om = outer_all ? 0xFFFFFFu : (~c & 0xFFFFFFu);        // positions of the outer domain
-    const uint32_t sm = odd ? 0xFFFFFFu : c;                             // positions taking a bit of sb
-    const uint32_t sb = odd ? c : s1;                                    // odd: the word itself flips signs
-    const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                 // keep U as the domain bit
-
-    uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
+    SplitEnt e[NB];
+    uint32_t nbase[NB];
 #pragma unroll
-    for (int k = 0; k < 4; k++) {
-        const uint32_t omk = bfe6(om, 6 * k);
-        const uint32_t uk = T.pdep6[omk << 6 | bfe6(U, ou)];            // U in absolute positions
-        ou += popc32(omk);
-        const uint32_t cmk = bfe6(cm, 6 * k) << 6, smk = bfe6(sm, 6 * k);
-        const uint32_t gA1 = T.spread6[cmk | bfe6(a1, o1)];
-        const uint32_t gB1 = T.spread6[cmk | bfe6(b1, o1)];
-        o1 += popc32(cmk);
-        const uint32_t gA0 = T.spread6[uk << 6 | bfe6(a0, o0)];
-        const uint32_t gB0 = T.spread6[uk << 6 | bfe6(b0, o0)];
-        const uint32_t gS0 = T.spread6[uk << 6 | bfe6(s0, o0)];
-        o0 += popc32(uk);
-        const uint32_t gS1 = T.spread6[smk << 6 | bfe6(sb, os)];
-        os += popc32(smk);
-        const uint32_t ones = 0x01011111u;
-        w[k] = ((gA1 | gA0) & ones) | (((gB1 | gB0) & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
-               (gA1 & 0x04044444u) | (gA0 & dkeep);
+    for (int u = 0; u < NB; u++) {
+        e[u] = T.split[(uint16_t)(R[u].sp + j[u])];
+        nbase[u] = T.split[(uint16_t)(R[u].sp + j[u] + 1)].base;       // one past the last entry is never used
     }
-    return cid;
+    for (;;) {
+        bool more = false;
+#pragma unroll
+        for (int u = 0; u < NB; u++) {
+            const uint32_t jmax = (R[u].f1 >> F1_JMAX) & 15u;
+            if (j[u] < jmax && d[u] >= nbase[u]) {
+                j[u]++;
+                e[u] = T.split[(uint16_t)(R[u].sp + j[u])];
+                nbase[u] = T.split[(uint16_t)(R[u].sp + j[u] + 1)].base;
+                more = true;
+            }
+        }
+        if (!more) break;
+    }
+#pragma unroll
+    for (int u = 0; u < NB; u++) {
+        const uint32_t dl = d[u] - e[u].base;
+        const uint32_t rk_hi = (uint32_t)((double)dl * (double)e[u].inv);
+        const uint32_t rk_lo = dl - rk_hi * e[u].div;
+        U[u] = (uint32_t)T.lut12[e[u].b12lo + rk_lo] | ((uint32_t)T.lut12[e[u].b12hi + rk_hi] << 12);
+    }
+
+    bool any_b1 = false;
+#pragma unroll
+    for (int u = 0; u < NB; u++) any_b1 |= (e1[u] >> 16) != 0;
+    any_b1 = wave_any(any_b1);                                           // a third F1 value (10) is rare
+
+#pragma unroll
+    for (int u = 0; u < NB; u++) {
+        const uint32_t f0 = R[u].f0;
+        info[u].cid = cid[u]; info[u].m = (f0 >> F0_M) & 15u;
+        info[u].vt8_lo = R[u].vt8_lo; info[u].vt8_hi = R[u].vt8_hi; info[u].vti_lo = R[u].vti_lo; info[u].vti_hi = R[u].vti_hi;
+        const uint32_t a0 = e0[u] & 0xFFFFu, b0 = e0[u] >> 16, a1 = e1[u] & 0xFFFFu, b1 = e1[u] >> 16;
+        // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so
+        // that the number of negative F1 coordinates has the parity condition (iii) asks for
+        const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
+        uint32_t s1 = s[u] & ((1u << wm1) - 1u);
+        const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
+        s1 |= forced << wm1;
+        const uint32_t s0 = s[u] >> wm1;
+
+        const bool odd = (f0 >> F0_ODD) & 1u;
+        const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
+        const uint32_t cw = c[u];
+        const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? cw : 0u;           // slots of the direct F1 word
+        const uint32_t om = outer_all ? 0xFFFFFFu : (~cw & 0xFFFFFFu);      // positions of the outer domain
+        const uint32_t sm = odd ? 0xFFFFFFu : cw;                           // positions taking a bit of sb
+        const uint32_t sb = odd ? cw : s1;                                  // odd: the word itself flips signs
+        const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                // keep U as the domain bit
+
+        uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t omk = bfe6(om, 6 * k);
+            const uint32_t uk = T.pdep6[dep_key(omk, bfe6(U[u], ou))];        // U in absolute positions
+            ou += popc32(omk);
+            const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
+            const uint32_t gA1 = T.spread6[dep_key(cmk, bfe6(a1, o1))];
+            uint32_t gB = 0;
+            if (any_b1) gB = T.spread6[dep_key(cmk, bfe6(b1, o1))];
+            o1 += popc32(cmk);
+            const uint32_t gA0 = T.spread6[dep_key(uk, bfe6(a0, o0))];
+            gB |= T.spread6[dep_key(uk, bfe6(b0, o0))];
+            const uint32_t gS0 = T.spread6[dep_key(uk, bfe6(s0, o0))];
+            o0 += popc32(uk);
+            const uint32_t gS1 = T.spread6[dep_key(smk, bfe6(sb, os))];
+            os += popc32(smk);
+            const uint32_t ones = 0x01011111u;
+            w[u][k] = ((gA1 | gA0) & ones) | ((gB & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
+                      (gA1 & 0x04044444u) | (gA0 & dkeep);
+        }
+    }
+}
+
+// Decodes one index I (must be < npoints); w[0..3] receive the nibble words.
+LLVQ_HD BlockInfo decode_block(const TabPtrs& T, uint64_t I, uint32_t w[4]) {
+    const uint64_t Iv[1] = {I};
+    uint32_t wv[1][4];
+    BlockInfo bi[1];
+    decode_blocks<1>(T, Iv, wv, bi);
+    w[0] = wv[0][0]; w[1] = wv[0][1]; w[2] = wv[0][2]; w[3] = wv[0][3];
+    return bi[0];
 }
 
 // v_perm_b32-style byte select restricted to selector values 0..7: byte k of the result is byte sel_k of hi:lo

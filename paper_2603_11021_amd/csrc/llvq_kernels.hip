@@ -32,10 +32,35 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 extern __shared__ __align__(16) unsigned char g_lds[];
 
 __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ blob, uint32_t bytes) {
+    // all global loads of a thread are issued before its first LDS store, so their latencies overlap
     const uint4* src = reinterpret_cast<const uint4*>(blob);
     uint4* dst = reinterpret_cast<uint4*>(g_lds);
-    for (uint32_t i = threadIdx.x; i < bytes / 16; i += blockDim.x) dst[i] = src[i];
+    const uint32_t n16 = bytes / 16;
+    constexpr int kPer = 10;                                    // 10 x 16 B x 1024 threads = 160 KB
+    uint4 v[kPer];
+#pragma unroll
+    for (int i = 0; i < kPer; i++) {
+        const uint32_t k = threadIdx.x + i * kThreads;
+        v[i] = k < n16 ? src[k] : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; i++) {
+        const uint32_t k = threadIdx.x + i * kThreads;
+        if (k < n16) dst[k] = v[i];
+    }
     __syncthreads();
+}
+
+// sum over the 64 lanes of a wavefront with DPP adds inside each row of 16 lanes and four lane reads; every
+// lane receives the total
+__device__ __forceinline__ float wave_sum(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+    const int iv = __builtin_bit_cast(int, v);
+    return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16))) +
+           (__builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48)));
 }
 
 template <int FMT>
@@ -59,8 +84,8 @@ __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char
         const uint64_t I = load_index<FMT>(idx, k);
         const bool ok = I < T.npoints;
         uint32_t w[4], o[6];
-        const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
-        llvq::nibbles_to_i8(w, T.cls[cid].vti_lo, T.cls[cid].vti_hi, o);
+        const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
+        llvq::nibbles_to_i8(w, bi.vti_lo, bi.vti_hi, o);
         uint2* dst = reinterpret_cast<uint2*>(out + 6 * k);
         dst[0] = ok ? make_uint2(o[0], o[1]) : make_uint2(0, 0);
         dst[1] = ok ? make_uint2(o[2], o[3]) : make_uint2(0, 0);
@@ -95,10 +120,8 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
         const uint64_t I = load_index<FMT>(idx, k);
         const bool ok = I < T.npoints;
         uint32_t w[4];
-        const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
-        const ClassRec* R = &T.cls[cid];
-        const uint32_t vt_lo = R->vt8_lo, vt_hi = R->vt8_hi;
-        const uint32_t m = (R->f0 >> llvq::F0_M) & 15u;
+        const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
+        const uint32_t vt_lo = bi.vt8_lo, vt_hi = bi.vt8_hi, m = bi.m;
         const float g = __half2float(__ushort_as_half(gain[k]));
         const float scale = ok ? g * lay.rnorm[m] : 0.0f;
         float v[24];
@@ -143,6 +166,7 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
 // waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
 // gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
 constexpr int kMaxMChunk = 8;     // activation rows handled per pass over the indices
+constexpr int kRowsPerPass = 64;  // output rows accumulated in LDS at a time
 
 template <typename X2> struct Dot;
 template <> struct Dot<half2_t> {
@@ -154,76 +178,128 @@ template <> struct Dot<bf16x2_t> {
     static __device__ __forceinline__ float dot(bf16x2_t a, bf16x2_t b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
 };
 
+constexpr int kNB = 1;              // blocks decoded per lane and pass, interleaved to overlap table reads
+
 template <int FMT, typename X2>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
                                                           int rows_per_wg, float* __restrict__ y) {
+    // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
-    float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [rows_per_wg][kMaxMChunk]
-    const int r0 = blockIdx.x * rows_per_wg;
-    const int nrows = min(rows_per_wg, N - r0);
-    if (nrows <= 0) return;
-    const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
-    const size_t blk0 = (size_t)r0 * KB;
+    float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kRowsPerPass][kMaxMChunk]
+    const int wg_r0 = blockIdx.x * rows_per_wg;
+    const int wg_r1 = min(N, wg_r0 + rows_per_wg);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
-    for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
-        const int mc = min(kMaxMChunk, M - m0);
-        for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
-        __syncthreads();
-        for (uint32_t base = (uint32_t)wave * 64; base < nblk; base += kWaves * 64) {
-            const uint32_t fb = base + lane;
-            const bool live = fb < nblk;
-            const uint32_t fbc = live ? fb : nblk - 1;
-            const uint32_t row = fbc / (uint32_t)KB, b = fbc - row * (uint32_t)KB;
-            const uint64_t I = load_index<FMT>(idx, blk0 + fbc);
-            const bool ok = live && I < T.npoints;
-            uint32_t w[4];
-            const uint32_t cid = llvq::decode_block(T, ok ? I : 0, w);
-            const ClassRec* R = &T.cls[cid];
-            const uint32_t vt_lo = R->vt8_lo, vt_hi = R->vt8_hi;
-            const uint32_t m = (R->f0 >> llvq::F0_M) & 15u;
-            const float g = __half2float(__ushort_as_half(gain[blk0 + fbc]));
-            const float scale = ok ? g * lay.rnorm[m] : 0.0f;
-            X2 wt[12];
+    for (int r0 = wg_r0; r0 < wg_r1; r0 += kRowsPerPass) {
+        const int nrows = min(kRowsPerPass, wg_r1 - r0);
+        const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
+        const size_t blk0 = (size_t)r0 * KB;
+        for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
+            const int mc = min(kMaxMChunk, M - m0);
+            for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+            __syncthreads();
+            // a wave takes kNB consecutive batches of 64 blocks per pass; the indices and gains of the next
+            // pass and the first activation row of this pass are requested before this pass is decoded
+            struct Fetch { uint64_t I[kNB]; uint32_t row[kNB], b[kNB]; uint16_t g[kNB]; bool live[kNB]; };
+            auto fetch = [&](uint32_t base, Fetch& f) {
 #pragma unroll
-            for (int c = 0; c < 4; c++) {
-                uint32_t fe, fo;
-                chunk_fp8(w[c], vt_lo, vt_hi, fe, fo);
-                wt[3 * c + 0] = Dot<X2>::cvt(fe, false);   // positions 6c+0, 6c+1
-                wt[3 * c + 1] = Dot<X2>::cvt(fo, false);   // positions 6c+2, 6c+3
-                wt[3 * c + 2] = Dot<X2>::cvt(fe, true);    // positions 6c+4, 6c+5
-            }
-            // lanes sharing a row are contiguous; head = first lane of its row in this batch
-            const uint32_t row_up = __shfl_up(row, 1);
-            const bool head = (lane == 0) || (row_up != row);
-            for (int mi = 0; mi < mc; mi++) {
-                const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)b * 12);
-                const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
-                const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
-                float acc = 0.0f;
-#pragma unroll
-                for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
-                float p = acc * scale;
-                // segmented suffix sum over lanes of equal row
-#pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    const float pv = __shfl_down(p, off);
-                    const uint32_t rv = __shfl_down(row, off);
-                    if (lane + off < 64 && rv == row) p += pv;
+                for (int u = 0; u < kNB; u++) {
+                    const uint32_t fb = base + 64 * u + lane;
+                    f.live[u] = fb < nblk;
+                    const uint32_t fbc = f.live[u] ? fb : nblk - 1;
+                    f.row[u] = fbc / (uint32_t)KB;
+                    f.b[u] = fbc - f.row[u] * (uint32_t)KB;
+                    f.I[u] = load_index<FMT>(idx, blk0 + fbc);
+                    f.g[u] = gain[blk0 + fbc];
                 }
-                if (head && live) atomicAdd(&ysum[row * kMaxMChunk + mi], p);
+            };
+            const uint32_t stride = kWaves * 64 * kNB;
+            uint32_t base = (uint32_t)wave * (64 * kNB);
+            Fetch cur, nxt;
+            if (base < nblk) fetch(base, cur);
+            for (; base < nblk; base += stride) {
+                if (base + stride < nblk) fetch(base + stride, nxt);
+                uint4 xq[kNB][3];
+#pragma unroll
+                for (int u = 0; u < kNB; u++) {
+                    const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)m0 * xpitch + (size_t)cur.b[u] * 12);
+                    xq[u][0] = xp[0]; xq[u][1] = xp[1]; xq[u][2] = xp[2];
+                }
+                uint64_t I[kNB];
+                bool ok[kNB];
+#pragma unroll
+                for (int u = 0; u < kNB; u++) {
+                    ok[u] = cur.live[u] && cur.I[u] < T.npoints;
+                    I[u] = ok[u] ? cur.I[u] : 0;
+                }
+                uint32_t w[kNB][4];
+                llvq::BlockInfo bi[kNB];
+                llvq::decode_blocks<kNB>(T, I, w, bi);
+#pragma unroll
+                for (int u = 0; u < kNB; u++) {
+                    if (base + 64 * u >= nblk) break;                       // wave-uniform: this batch is empty
+                    const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi, m = bi[u].m;
+                    const float g = __half2float(__ushort_as_half(cur.g[u]));
+                    const float scale = ok[u] ? g * lay.rnorm[m] : 0.0f;
+                    X2 wt[12];
+#pragma unroll
+                    for (int c = 0; c < 4; c++) {
+                        uint32_t fe, fo;
+                        chunk_fp8(w[u][c], vt_lo, vt_hi, fe, fo);
+                        wt[3 * c + 0] = Dot<X2>::cvt(fe, false);   // positions 6c+0, 6c+1
+                        wt[3 * c + 1] = Dot<X2>::cvt(fo, false);   // positions 6c+2, 6c+3
+                        wt[3 * c + 2] = Dot<X2>::cvt(fe, true);    // positions 6c+4, 6c+5
+                    }
+                    // rows are contiguous runs of lanes; with KB >= 64 a batch touches at most two rows
+                    const uint32_t row = cur.row[u];
+                    const uint32_t row_lo = __builtin_amdgcn_readfirstlane(row);
+                    const uint32_t row_hi = __builtin_amdgcn_readlane(row, 63);
+                    const bool two_rows = row_hi <= row_lo + 1;
+                    for (int mi = 0; mi < mc; mi++) {
+                        uint4 x0 = xq[u][0], x1 = xq[u][1], x2 = xq[u][2];
+                        if (mi > 0) {
+                            const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b[u] * 12);
+                            x0 = xp[0]; x1 = xp[1]; x2 = xp[2];
+                        }
+                        const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
+                        float acc = 0.0f;
+#pragma unroll
+                        for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
+                        float p = cur.live[u] ? acc * scale : 0.0f;
+                        if (two_rows) {
+                            const float p_lo = row == row_lo ? p : 0.0f;
+                            const float s_lo = wave_sum(p_lo), s_hi = wave_sum(p - p_lo);
+                            if (lane == 0) {
+                                atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_lo);
+                                if (row_hi != row_lo) atomicAdd(&ysum[row_hi * kMaxMChunk + mi], s_hi);
+                            }
+                        } else {
+                            // general case: segmented suffix sum over lanes of equal row
+                            const uint32_t row_up = __shfl_up(row, 1);
+                            const bool head = (lane == 0) || (row_up != row);
+#pragma unroll
+                            for (int off = 1; off < 64; off <<= 1) {
+                                const float pv = __shfl_down(p, off);
+                                const uint32_t rv = __shfl_down(row, off);
+                                if (lane + off < 64 && rv == row) p += pv;
+                            }
+                            if (head && cur.live[u]) atomicAdd(&ysum[row * kMaxMChunk + mi], p);
+                        }
+                    }
+                }
+                cur = nxt;
             }
+            __syncthreads();
+            for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
+                const int rr = i / mc, mi = i - rr * mc;
+                y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
-            const int rr = i / mc, mi = i - rr * mc;
-            y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
-        }
-        __syncthreads();
     }
 }
 
@@ -300,17 +376,11 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
 
 template <int FMT, typename X2>
 static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
-    // rows per workgroup: enough workgroups to cover every compute unit a few times over, but at least
-    // ~2 wave-batches per wave so that the table load is amortised
-    const size_t blocks_total = (size_t)N * KB;
-    int rows = (int)((size_t)(2 * kThreads) / (size_t)KB);
-    if (rows < 1) rows = 1;
-    const int min_wgs = ctx->num_cu * 2;
-    while (rows > 1 && (N + rows - 1) / rows < min_wgs && (size_t)rows * KB > (size_t)kThreads) rows--;
-    if (rows > 64) rows = 64;
-    (void)blocks_total;
-    const int grid = (N + rows - 1) / rows;
-    const size_t lds = ctx->lay.lds_bytes + (size_t)rows * kMaxMChunk * sizeof(float);
+    // one persistent workgroup per compute unit (the tables fill its LDS), rows split evenly among them
+    int grid = ctx->num_cu < N ? ctx->num_cu : N;
+    const int rows = (N + grid - 1) / grid;
+    grid = (N + rows - 1) / rows;
+    const size_t lds = ctx->lay.lds_bytes + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
     if (int rc = set_lds(ctx, matmul_kernel<FMT, X2>, lds)) return rc;
     hipLaunchKernelGGL((matmul_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, rows, d_y);

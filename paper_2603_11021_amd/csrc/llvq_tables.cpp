@@ -369,13 +369,13 @@ bool build_tables(int m_max, Tables& out) {
     for (uint32_t F = 0; F < 64; F++)
         for (uint32_t mbits = 0; mbits < 64; mbits++) {
             uint32_t dep = deposit(mbits, F);
-            pdep6[F << 6 | mbits] = (uint8_t)dep;
+            pdep6[F << 6 | (mbits ^ F)] = (uint8_t)dep;       // swizzled: see dep_key()
             uint32_t sp = 0;
             for (int p = 0; p < 6; p++) {
                 if ((dep >> p) & 1u) sp |= 1u << (4 * kNibbleSlot[p]);
                 if ((F >> p) & 1u) sp |= 4u << (4 * kNibbleSlot[p]);
             }
-            spread6[F << 6 | mbits] = sp;
+            spread6[F << 6 | (mbits ^ F)] = sp;
         }
 
     // ---- blob ------------------------------------------------------------------------------------

@@ -29,8 +29,8 @@ uint64_t emul_decode_i8(const uint64_t* idx, uint64_t n, int8_t* out) {
     for (uint64_t k = 0; k < n; k++) {
         if (idx[k] >= T.npoints) { bad++; std::memset(out + 24 * k, 0, 24); continue; }
         uint32_t w[4], o[6];
-        const uint32_t cid = llvq::decode_block(T, idx[k], w);
-        llvq::nibbles_to_i8(w, T.cls[cid].vti_lo, T.cls[cid].vti_hi, o);
+        const llvq::BlockInfo bi = llvq::decode_block(T, idx[k], w);
+        llvq::nibbles_to_i8(w, bi.vti_lo, bi.vti_hi, o);
         std::memcpy(out + 24 * k, o, 24);
     }
     return bad;
