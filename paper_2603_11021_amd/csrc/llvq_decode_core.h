@@ -21,38 +21,26 @@
 
 namespace llvq {
 
+// The tables are addressed as `base + constant offset + key`; on the device `base` is the start of LDS and
+// the constant folds into the offset field of the LDS instruction.
 struct TabPtrs {
-    const uint32_t* gs;
-    const uint32_t* spread6;
-    const uint8_t*  pdep6;
-    const uint16_t* lut12;
-    const uint16_t* bucket;
-    const uint64_t* cls_off;
-    const ClassRec* cls;
-    const SplitEnt* split;
-    const uint8_t*  guess;
-    const uint32_t* inner;
+    const unsigned char* base;
     uint32_t ncls;
-    uint32_t bucket_shift;
     uint64_t npoints;
 };
 
 LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const TableLayout& L) {
     TabPtrs T;
-    T.gs = reinterpret_cast<const uint32_t*>(base + L.gs);
-    T.spread6 = reinterpret_cast<const uint32_t*>(base + L.spread6);
-    T.pdep6 = reinterpret_cast<const uint8_t*>(base + L.pdep6);
-    T.lut12 = reinterpret_cast<const uint16_t*>(base + L.lut12);
-    T.bucket = reinterpret_cast<const uint16_t*>(base + L.bucket);
-    T.cls_off = reinterpret_cast<const uint64_t*>(base + L.cls_off);
-    T.cls = reinterpret_cast<const ClassRec*>(base + L.cls);
-    T.split = reinterpret_cast<const SplitEnt*>(base + L.split);
-    T.guess = reinterpret_cast<const uint8_t*>(base + L.guess);
-    T.inner = reinterpret_cast<const uint32_t*>(base + L.inner);
+    T.base = base;
     T.ncls = L.ncls;
-    T.bucket_shift = L.bucket_shift;
     T.npoints = L.npoints;
     return T;
+}
+
+// element `byte_off` bytes into the table at constant offset OFF
+template <typename V, uint32_t OFF>
+LLVQ_HD V tab_at(const TabPtrs& T, uint32_t byte_off) {
+    return *reinterpret_cast<const V*>(T.base + OFF + byte_off);
 }
 
 LLVQ_HD uint32_t popc32(uint32_t v) {
@@ -67,7 +55,10 @@ LLVQ_HD uint32_t bfe6(uint32_t v, uint32_t off) { return (v >> off) & 63u; }
 
 // Entry (F, m) of the 6-bit deposit tables sits at F*64 + (m ^ F): the frequent all-zero sources of different
 // masks then fall into different LDS banks instead of all into bank 0.
-LLVQ_HD uint32_t dep_key(uint32_t F, uint32_t m) { return (F << 6) | (m ^ F); }
+// spread6: byte offset of entry (F, bits o..o+5 of plane) given plane2 = plane << 2 and Fx = F * 0x104
+LLVQ_HD uint32_t spread6_at(const TabPtrs& T, uint32_t Fx, uint32_t plane2, uint32_t o) {
+    return tab_at<uint32_t, kOffSpread6>(T, ((plane2 >> o) & 0xFCu) ^ Fx);
+}
 
 // true when `v` holds for any active lane of the wavefront (always true on the host, where it only gates work)
 LLVQ_HD bool wave_any(bool v) {
@@ -79,8 +70,6 @@ LLVQ_HD bool wave_any(bool v) {
 #endif
 }
 
-// Decodes NB indices per lane (each must be < npoints), stage by stage so that the table reads of the NB
-// blocks are independent and overlap.  cid[u] receives the class id, w[u][0..3] the nibble words.
 struct BlockInfo {
     uint32_t cid;                // class id
     uint32_t m;                  // shell
@@ -88,6 +77,8 @@ struct BlockInfo {
     uint32_t vti_lo, vti_hi;     // value table of the class, int8
 };
 
+// Decodes NB indices per lane (each must be < npoints), stage by stage so that the table reads of the NB
+// blocks are independent and overlap.  w[u][0..3] receive the nibble words of block u.
 template <int NB>
 LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
     uint32_t cid[NB];
@@ -95,9 +86,9 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
     uint64_t off[NB], nxt[NB];
 #pragma unroll
     for (int u = 0; u < NB; u++) {
-        cid[u] = T.bucket[(uint32_t)(I[u] >> T.bucket_shift)];
-        off[u] = T.cls_off[cid[u]];
-        nxt[u] = T.cls_off[cid[u] + 1];
+        cid[u] = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I[u] >> kBucketShift) * 2u);
+        off[u] = tab_at<uint64_t, kOffClsOff>(T, cid[u] * 8u);
+        nxt[u] = tab_at<uint64_t, kOffClsOff + 8>(T, cid[u] * 8u);
     }
     for (;;) {
         bool more = false;
@@ -106,7 +97,7 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
             if (I[u] >= nxt[u] && cid[u] + 1 < T.ncls) {
                 cid[u]++;
                 off[u] = nxt[u];
-                nxt[u] = T.cls_off[cid[u] + 1];
+                nxt[u] = tab_at<uint64_t, kOffClsOff + 8>(T, cid[u] * 8u);
                 more = true;
             }
         }
@@ -117,15 +108,14 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
     uint32_t c[NB], U[NB], e0[NB], e1[NB], s[NB], d[NB], j[NB];
 #pragma unroll
     for (int u = 0; u < NB; u++) {
-        R[u] = T.cls[cid[u]];
+        R[u] = tab_at<ClassRec, kOffCls>(T, cid[u] * (uint32_t)sizeof(ClassRec));
         const uint64_t Ic = I[u] - off[u];
         const uint32_t f0 = R[u].f0, f1 = R[u].f1;
         // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
         // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
         const uint32_t acode = (f1 >> F1_ACODE) & 3u;
-        const double A = acode == 0 ? 1.0 : (acode == 1 ? 759.0 : (acode == 2 ? 2576.0 : 4096.0));
-        constexpr double kNudge = 1.0 + 0x1p-50;
-        const double invA = acode == 0 ? 1.0 : (acode == 1 ? (1.0 / 759.0) * kNudge : (acode == 2 ? (1.0 / 2576.0) * kNudge : 0x1p-12));
+        const double A = tab_at<double, kOffAtab>(T, acode * 16u);
+        const double invA = tab_at<double, kOffAtab + 8>(T, acode * 16u);
         const double x = (double)Ic;
         const double q1 = floor(x * invA);
         const uint32_t r = (uint32_t)fma(-q1, A, x);
@@ -139,10 +129,10 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
         const uint32_t rin = (uint32_t)((double)rem * (double)R[u].invP1);
         const uint32_t rho1 = rem - rin * R[u].P1;
         // the Golay word selected by r, the symbol planes over the slots of U (e0) and over the F1 slots (e1)
-        c[u] = T.gs[((f1 >> F1_GOFF) & 4095u) + r];
-        e0[u] = T.inner[R[u].tb0 + rin];
-        e1[u] = T.inner[R[u].tb1 + rho1];
-        j[u] = T.guess[((f1 >> F1_GROW) & 63u) * 32u + (d[u] >> ((f1 >> F1_GSHIFT) & 31u))];
+        c[u] = tab_at<uint32_t, kOffGs>(T, (((f1 >> F1_GOFF) & 4095u) + r) * 4u);
+        e0[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb0 + rin) * 4u);
+        e1[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb1 + rho1) * 4u);
+        j[u] = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * 32u + (d[u] >> ((f1 >> F1_GSHIFT) & 31u)));
     }
 
     // App. A step 4, placement: the q-subset U of the outer domain's n slots with rank d
@@ -150,8 +140,9 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
     uint32_t nbase[NB];
 #pragma unroll
     for (int u = 0; u < NB; u++) {
-        e[u] = T.split[(uint16_t)(R[u].sp + j[u])];
-        nbase[u] = T.split[(uint16_t)(R[u].sp + j[u] + 1)].base;       // one past the last entry is never used
+        const uint32_t eo = (uint32_t)(uint16_t)(R[u].sp + j[u]) * (uint32_t)sizeof(SplitEnt);
+        e[u] = tab_at<SplitEnt, kOffSplit>(T, eo);
+        nbase[u] = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);   // one past the last entry is never used
     }
     for (;;) {
         bool more = false;
@@ -160,8 +151,9 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
             const uint32_t jmax = (R[u].f1 >> F1_JMAX) & 15u;
             if (j[u] < jmax && d[u] >= nbase[u]) {
                 j[u]++;
-                e[u] = T.split[(uint16_t)(R[u].sp + j[u])];
-                nbase[u] = T.split[(uint16_t)(R[u].sp + j[u] + 1)].base;
+                const uint32_t eo = (uint32_t)(uint16_t)(R[u].sp + j[u]) * (uint32_t)sizeof(SplitEnt);
+                e[u] = tab_at<SplitEnt, kOffSplit>(T, eo);
+                nbase[u] = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);
                 more = true;
             }
         }
@@ -172,7 +164,8 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
         const uint32_t dl = d[u] - e[u].base;
         const uint32_t rk_hi = (uint32_t)((double)dl * (double)e[u].inv);
         const uint32_t rk_lo = dl - rk_hi * e[u].div;
-        U[u] = (uint32_t)T.lut12[e[u].b12lo + rk_lo] | ((uint32_t)T.lut12[e[u].b12hi + rk_hi] << 12);
+        U[u] = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e[u].b12lo + rk_lo) * 2u) |
+               ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e[u].b12hi + rk_hi) * 2u) << 12);
     }
 
     bool any_b1 = false;
@@ -185,14 +178,15 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
         const uint32_t f0 = R[u].f0;
         info[u].cid = cid[u]; info[u].m = (f0 >> F0_M) & 15u;
         info[u].vt8_lo = R[u].vt8_lo; info[u].vt8_hi = R[u].vt8_hi; info[u].vti_lo = R[u].vti_lo; info[u].vti_hi = R[u].vti_hi;
-        const uint32_t a0 = e0[u] & 0xFFFFu, b0 = e0[u] >> 16, a1 = e1[u] & 0xFFFFu, b1 = e1[u] >> 16;
+        // planes pre-shifted by two: the deposit keys below are byte offsets into a table of dwords
+        const uint32_t a0 = (e0[u] & 0xFFFFu) << 2, b0 = (e0[u] >> 16) << 2, a1 = (e1[u] & 0xFFFFu) << 2, b1 = (e1[u] >> 16) << 2;
         // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so
         // that the number of negative F1 coordinates has the parity condition (iii) asks for
         const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
         uint32_t s1 = s[u] & ((1u << wm1) - 1u);
         const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
         s1 |= forced << wm1;
-        const uint32_t s0 = s[u] >> wm1;
+        const uint32_t s0 = (s[u] >> wm1) << 2;
 
         const bool odd = (f0 >> F0_ODD) & 1u;
         const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
@@ -200,25 +194,26 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
         const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? cw : 0u;           // slots of the direct F1 word
         const uint32_t om = outer_all ? 0xFFFFFFu : (~cw & 0xFFFFFFu);      // positions of the outer domain
         const uint32_t sm = odd ? 0xFFFFFFu : cw;                           // positions taking a bit of sb
-        const uint32_t sb = odd ? cw : s1;                                  // odd: the word itself flips signs
+        const uint32_t sb = (odd ? cw : s1) << 2;                           // odd: the word itself flips signs
         const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                // keep U as the domain bit
 
         uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
-            const uint32_t uk = T.pdep6[dep_key(omk, bfe6(U[u], ou))];        // U in absolute positions
+            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, (omk << 6) | (bfe6(U[u], ou) ^ omk));   // U in absolute positions
             ou += popc32(omk);
             const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
-            const uint32_t gA1 = T.spread6[dep_key(cmk, bfe6(a1, o1))];
+            const uint32_t cx = cmk * 0x104u, ux = uk * 0x104u, sx = smk * 0x104u;
+            const uint32_t gA1 = spread6_at(T, cx, a1, o1);
             uint32_t gB = 0;
-            if (any_b1) gB = T.spread6[dep_key(cmk, bfe6(b1, o1))];
+            if (any_b1) gB = spread6_at(T, cx, b1, o1);
             o1 += popc32(cmk);
-            const uint32_t gA0 = T.spread6[dep_key(uk, bfe6(a0, o0))];
-            gB |= T.spread6[dep_key(uk, bfe6(b0, o0))];
-            const uint32_t gS0 = T.spread6[dep_key(uk, bfe6(s0, o0))];
+            const uint32_t gA0 = spread6_at(T, ux, a0, o0);
+            gB |= spread6_at(T, ux, b0, o0);
+            const uint32_t gS0 = spread6_at(T, ux, s0, o0);
             o0 += popc32(uk);
-            const uint32_t gS1 = T.spread6[dep_key(smk, bfe6(sb, os))];
+            const uint32_t gS1 = spread6_at(T, sx, sb, os);
             os += popc32(smk);
             const uint32_t ones = 0x01011111u;
             w[u][k] = ((gA1 | gA0) & ones) | ((gB & ones) << 1) | (((gS1 | gS0) & ones) << 3) |

@@ -165,7 +165,7 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
 // row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the 16
 // waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
 // gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
-constexpr int kMaxMChunk = 8;     // activation rows handled per pass over the indices
+constexpr int kMaxMChunk = 16;    // activation rows handled per pass over the indices
 constexpr int kRowsPerPass = 64;  // output rows accumulated in LDS at a time
 
 template <typename X2> struct Dot;
@@ -184,7 +184,7 @@ template <int FMT, typename X2>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                          int rows_per_wg, float* __restrict__ y) {
+                                                          uint32_t kb_magic, int rows_per_wg, float* __restrict__ y) {
     // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
@@ -211,7 +211,8 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                     const uint32_t fb = base + 64 * u + lane;
                     f.live[u] = fb < nblk;
                     const uint32_t fbc = f.live[u] ? fb : nblk - 1;
-                    f.row[u] = fbc / (uint32_t)KB;
+                    // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
+                    f.row[u] = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
                     f.b[u] = fbc - f.row[u] * (uint32_t)KB;
                     f.I[u] = load_index<FMT>(idx, blk0 + fbc);
                     f.g[u] = gain[blk0 + fbc];
@@ -381,9 +382,10 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     const int rows = (N + grid - 1) / grid;
     grid = (N + rows - 1) / rows;
     const size_t lds = ctx->lay.lds_bytes + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
+    const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
     if (int rc = set_lds(ctx, matmul_kernel<FMT, X2>, lds)) return rc;
     hipLaunchKernelGGL((matmul_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, rows, d_y);
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, kb_magic, rows, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }

@@ -355,7 +355,7 @@ bool build_tables(int m_max, Tables& out) {
     cls_off[ncls] = running;
 
     // ---- bucket table: index >> shift -> class holding the first index of the bucket --------------------
-    const uint32_t bucket_shift = 37, nbuckets = 2048;
+    const uint32_t bucket_shift = kBucketShift, nbuckets = 2048;
     std::vector<uint16_t> bucket(nbuckets);
     for (uint32_t b = 0; b < nbuckets; b++) {
         uint64_t first = (uint64_t)b << bucket_shift;
@@ -379,25 +379,30 @@ bool build_tables(int m_max, Tables& out) {
         }
 
     // ---- blob ------------------------------------------------------------------------------------
+    std::vector<double> atab = {1.0, 1.0, 759.0, (1.0 / 759.0) * (1.0 + std::ldexp(1.0, -50)),
+                                2576.0, (1.0 / 2576.0) * (1.0 + std::ldexp(1.0, -50)), 4096.0, 1.0 / 4096.0};
     TableLayout lay{};
-    std::vector<unsigned char> blob;
-    lay.gs = append(blob, gs);
-    lay.spread6 = append(blob, spread6);
-    lay.pdep6 = append(blob, pdep6);
-    lay.lut12 = append(blob, lut12);
-    lay.bucket = append(blob, bucket);
-    lay.cls_off = append(blob, cls_off);
-    lay.cls = append(blob, recs);
-    lay.split = append(blob, split);
-    lay.guess = append(blob, guess);
-    lay.inner = append(blob, inner);
-    while (blob.size() % 16) blob.push_back(0);
+    const uint32_t inner_end = kOffInner + (uint32_t)(inner.size() * sizeof(uint32_t));
+    if (guess.size() > kOffAtab - kOffGuess || cls_off.size() * 8 > kOffSplit - kOffClsOff ||
+        (split.size() + 1) * sizeof(SplitEnt) > kOffCls - kOffSplit || recs.size() * sizeof(ClassRec) > kOffInner - kOffCls ||
+        inner_end > kMaxBlob)
+        return false;
+    std::vector<unsigned char> blob((inner_end + 15u) & ~15u, 0);
+    auto put = [&](uint32_t off, const void* src, size_t bytes) { std::memcpy(blob.data() + off, src, bytes); };
+    put(kOffGs, gs.data(), gs.size() * 4);
+    put(kOffSpread6, spread6.data(), spread6.size() * 4);
+    put(kOffPdep6, pdep6.data(), pdep6.size());
+    put(kOffLut12, lut12.data(), lut12.size() * 2);
+    put(kOffBucket, bucket.data(), bucket.size() * 2);
+    put(kOffGuess, guess.data(), guess.size());
+    put(kOffAtab, atab.data(), atab.size() * 8);
+    put(kOffClsOff, cls_off.data(), cls_off.size() * 8);
+    put(kOffSplit, split.data(), split.size() * sizeof(SplitEnt));
+    put(kOffCls, recs.data(), recs.size() * sizeof(ClassRec));
+    put(kOffInner, inner.data(), inner.size() * 4);
     lay.lds_bytes = (uint32_t)blob.size();
-    lay.total_bytes = (uint32_t)blob.size();
     lay.ncls = ncls;
     lay.inner_entries = (uint32_t)inner.size();
-    lay.bucket_shift = bucket_shift;
-    lay.nbuckets = nbuckets;
     lay.npoints = running;
     for (int m = 0; m < 16; m++) lay.rnorm[m] = m >= 1 ? (float)(1.0 / std::sqrt(16.0 * m)) : 0.0f;
     out.lay = lay;

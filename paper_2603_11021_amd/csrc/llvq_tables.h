@@ -53,15 +53,28 @@ struct alignas(16) SplitEnt {
 };
 static_assert(sizeof(SplitEnt) == 16, "SplitEnt layout");
 
-// Byte offsets of the tables inside the blob; the first `lds_bytes` bytes are what a kernel copies to LDS.
+// Fixed byte offsets of the tables inside the blob (and inside LDS, where kernels copy the blob verbatim).
+// They are compile-time constants so that the kernels can fold them into the offset field of the LDS
+// instructions; the small, frequently read tables sit below 64 KB, the reach of that field.
+constexpr uint32_t kOffGs      = 0;        // 4096 x u32
+constexpr uint32_t kOffSpread6 = 16384;    // 4096 x u32
+constexpr uint32_t kOffPdep6   = 32768;    // 4096 x u8
+constexpr uint32_t kOffLut12   = 36864;    // 4096 x u16
+constexpr uint32_t kOffBucket  = 45056;    // 2048 x u16
+constexpr uint32_t kOffGuess   = 49152;    // up to 64 rows x 32 x u8
+constexpr uint32_t kOffAtab    = 51200;    // 4 x {A, 1/A} doubles
+constexpr uint32_t kOffClsOff  = 51264;    // (ncls + 1) x u64, ncls <= 383
+constexpr uint32_t kOffSplit   = 54400;    // up to 392 x SplitEnt
+constexpr uint32_t kOffCls     = 60672;    // ncls x ClassRec
+constexpr uint32_t kOffInner   = 79072;    // inner-word planes, u32
+constexpr uint32_t kMaxBlob    = 159744;   // 156 KB; the rest of the 160 KB of LDS is kernel scratch
+constexpr uint32_t kBucketShift = 37;      // bucket index = I >> 37 (2048 buckets cover 48 bits)
+
 struct TableLayout {
-    uint32_t gs, spread6, pdep6, lut12, bucket, cls_off, cls, split, guess, inner;
-    uint32_t lds_bytes;      // bytes resident in LDS
-    uint32_t total_bytes;
+    uint32_t lds_bytes;      // bytes of the blob = bytes resident in LDS
     uint32_t ncls;
     uint32_t inner_entries;
-    uint32_t bucket_shift;   // bucket index = I >> bucket_shift
-    uint32_t nbuckets;
+    uint32_t pad;
     uint64_t npoints;        // N(m_max)
     float    rnorm[16];      // 1/sqrt(16 m)
 };
