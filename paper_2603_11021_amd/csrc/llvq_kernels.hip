@@ -9,6 +9,7 @@
 #include <hip/hip_fp16.h>
 
 #include <cstdio>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <string>
@@ -304,6 +305,133 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     }
 }
 
+// ---- llvq_matmul, MFMA kernel for 2 <= M (batched decode and prefill) --------------------------------------
+// A wave owns 32 weight rows and two neighbouring blocks of 24 input channels per step: lanes 0..31 decode
+// block b of rows r0..r0+31, lanes 32..63 block b+1 of the same rows.  The decoded block, scaled by
+// gain/sqrt(16 m) and rounded to the activation type, is exactly the B operand of v_mfma_f32_32x32x8 (lane l
+// supplies k = 4*(l/32)..+3 of column l%32), so the weights go from the decoder's registers straight into the
+// matrix cores; the A operand (32 tokens x the same 8 channels) is read from global memory.  Six MFMAs consume
+// the 24 channels of both blocks.  Steps are dealt to the waves of the whole grid as contiguous ranges (split
+// along K), partial tiles are added to y with fp32 atomics, y is cleared first by fill_kernel.
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+__global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+template <typename X2> struct Mma;
+template <> struct Mma<half2_t> {
+    static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
+        const half2_t h = fp8x2_to_f16(fp8, hi);
+        const _Float16 sh = (_Float16)scale;
+        const half2_t r = h * half2_t{sh, sh};
+        return __builtin_bit_cast(uint32_t, r);
+    }
+    static __device__ __forceinline__ float16_t mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float16_t c) {
+        const uint2 av = make_uint2(a0, a1), bv = make_uint2(b0, b1);
+        return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(half4_t, av), __builtin_bit_cast(half4_t, bv), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<bf16x2_t> {
+    static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
+        const uint32_t u = __builtin_bit_cast(uint32_t, fp8x2_to_bf16(fp8, hi));
+        const float f0 = __uint_as_float(u << 16) * scale, f1 = __uint_as_float(u & 0xFFFF0000u) * scale;
+        // round to nearest even (finite values)
+        uint32_t u0 = __float_as_uint(f0), u1 = __float_as_uint(f1);
+        u0 += 0x7FFFu + ((u0 >> 16) & 1u); u1 += 0x7FFFu + ((u1 >> 16) & 1u);
+        return (u0 >> 16) | (u1 & 0xFFFF0000u);
+    }
+    static __device__ __forceinline__ float16_t mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float16_t c) {
+        const uint2 av = make_uint2(a0, a1), bv = make_uint2(b0, b1);
+        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4_t, av), __builtin_bit_cast(short4_t, bv), c, 0, 0, 0);
+    }
+};
+
+constexpr int kMfmaMinM = 3;        // from this many activation rows on, llvq_matmul uses the MFMA kernel
+constexpr int kTokTiles = 2;        // token tiles of 32 accumulated per pass over the weights
+
+template <int FMT, typename X2>
+__global__ void __launch_bounds__(kThreads) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                        const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                        const uint32_t* __restrict__ x, int M, int N, int KB,
+                                                        uint32_t steps_per_wave, float* __restrict__ y) {
+    load_tables(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps per row tile
+    const uint32_t n_rt = ((uint32_t)N + 31) / 32;
+    const uint32_t total = n_rt * spt;
+    const uint32_t gw = (uint32_t)blockIdx.x * kWaves + wave;
+    const uint32_t s0 = gw * steps_per_wave;
+    const uint32_t s1 = min(total, s0 + steps_per_wave);
+    if (s0 >= s1) return;
+    const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
+
+    for (int m0 = 0; m0 < M; m0 += 32 * kTokTiles) {
+        const int ntile = min(kTokTiles, (M - m0 + 31) / 32);
+        float16_t acc[kTokTiles];
+#pragma unroll
+        for (int t = 0; t < kTokTiles; t++) for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
+        uint32_t rt = s0 / spt, st = s0 - rt * spt;
+        // activation row pointers of this lane, one per token tile (clamped: out-of-range tokens are never stored)
+        const uint32_t* xrow[kTokTiles];
+#pragma unroll
+        for (int t = 0; t < kTokTiles; t++) xrow[t] = x + (size_t)min(M - 1, m0 + 32 * t + col) * xpitch;
+
+        auto flush = [&](uint32_t tile) {
+            const int wrow = (int)tile * 32 + col;
+#pragma unroll
+            for (int t = 0; t < kTokTiles; t++) {
+                if (t >= ntile) break;
+#pragma unroll
+                for (int v = 0; v < 16; v++) {
+                    const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
+                    if (tok < M && wrow < N) atomicAdd(&y[(size_t)tok * N + wrow], acc[t][v]);
+                    acc[t][v] = 0.0f;
+                }
+            }
+        };
+
+        for (uint32_t s = s0; s < s1; s++) {
+            const int row = (int)rt * 32 + col;
+            const uint32_t b = 2 * st + half;
+            const bool live = row < N && b < (uint32_t)KB;
+            const size_t k = (size_t)min(row, N - 1) * KB + min(b, (uint32_t)KB - 1);
+            uint64_t I = load_index<FMT>(idx, k);
+            const float g = __half2float(__ushort_as_half(gain[k]));
+            const bool ok = live && I < T.npoints;
+            if (!ok) I = 0;
+            uint32_t w[4];
+            const llvq::BlockInfo bi = llvq::decode_block(T, I, w);
+            const float scale = ok ? g * lay.rnorm[bi.m] : 0.0f;
+            uint32_t wt[12];
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                uint32_t fe, fo;
+                chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
+                wt[3 * c + 0] = Mma<X2>::scaled(fe, false, scale);
+                wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
+                wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
+            }
+            const uint32_t bx = min(b, (uint32_t)KB - 1) * 12;
+#pragma unroll
+            for (int t = 0; t < kTokTiles; t++) {
+                if (t >= ntile) break;
+                const uint4* xp = reinterpret_cast<const uint4*>(xrow[t] + bx);
+                const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
+                const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
+#pragma unroll
+                for (int j = 0; j < 6; j++) acc[t] = Mma<X2>::mma(xs[2 * j], xs[2 * j + 1], wt[2 * j], wt[2 * j + 1], acc[t]);
+            }
+            if (++st == spt) { flush(rt); st = 0; rt++; }
+        }
+        if (st != 0) flush(rt);
+    }
+}
+
 // ---- llvq_validate ------------------------------------------------------------------------------------
 template <int FMT>
 __global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
@@ -388,6 +516,23 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, kb_magic, rows, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
+}
+
+template <int FMT, typename X2>
+static int launch_mfma(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+    const size_t ny = (size_t)M * N;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+    const uint32_t total = (uint32_t)((N + 31) / 32) * (uint32_t)((KB + 1) / 2);
+    const uint32_t waves = (uint32_t)ctx->num_cu * kWaves;
+    uint32_t spw = (total + waves - 1) / waves;
+    if (spw < 2) spw = 2;                                               // amortise the write-back of a partial tile
+    const int grid = (int)((total + spw * kWaves - 1) / (spw * kWaves));
+    const size_t lds = ctx->lay.lds_bytes;
+    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2>, lds)) return rc;
+    hipLaunchKernelGGL((mfma_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, spw, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
 }
 
 extern "C" {
@@ -483,6 +628,14 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* 
     if (int rc = check_idx(d_idx, fmt)) return rc;
     if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (M >= kMfmaMinM) {
+        if ((size_t)((N + 31) / 32) * (size_t)((KB + 1) / 2) >= (1ull << 32)) return LLVQ_EINVAL;
+        if (x_dtype == LLVQ_F16)
+            return fmt == LLVQ_IDX_U48 ? launch_mfma<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
+                                       : launch_mfma<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+        return fmt == LLVQ_IDX_U48 ? launch_mfma<LLVQ_IDX_U48, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
+                                   : launch_mfma<LLVQ_IDX_U64, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+    }
     if (x_dtype == LLVQ_F16)
         return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
                                    : launch_matmul<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
