@@ -32,22 +32,25 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 extern __shared__ __align__(16) unsigned char g_lds[];
 
+template <int THREADS = kThreads>
 __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ blob, uint32_t bytes) {
-    // all global loads of a thread are issued before its first LDS store, so their latencies overlap
+    // global loads are issued ten at a time before their LDS stores, so their latencies overlap
     const uint4* src = reinterpret_cast<const uint4*>(blob);
     uint4* dst = reinterpret_cast<uint4*>(g_lds);
     const uint32_t n16 = bytes / 16;
     constexpr int kPer = 10;                                    // 10 x 16 B x 1024 threads = 160 KB
-    uint4 v[kPer];
+    for (uint32_t base = 0; base < n16; base += kPer * THREADS) {
+        uint4 v[kPer];
 #pragma unroll
-    for (int i = 0; i < kPer; i++) {
-        const uint32_t k = threadIdx.x + i * kThreads;
-        v[i] = k < n16 ? src[k] : make_uint4(0, 0, 0, 0);
-    }
+        for (int i = 0; i < kPer; i++) {
+            const uint32_t k = base + threadIdx.x + i * THREADS;
+            v[i] = k < n16 ? src[k] : make_uint4(0, 0, 0, 0);
+        }
 #pragma unroll
-    for (int i = 0; i < kPer; i++) {
-        const uint32_t k = threadIdx.x + i * kThreads;
-        if (k < n16) dst[k] = v[i];
+        for (int i = 0; i < kPer; i++) {
+            const uint32_t k = base + threadIdx.x + i * THREADS;
+            if (k < n16) dst[k] = v[i];
+        }
     }
     __syncthreads();
 }
@@ -350,21 +353,23 @@ template <> struct Mma<bf16x2_t> {
 };
 
 constexpr int kMfmaMinM = 3;        // from this many activation rows on, llvq_matmul uses the MFMA kernel
-constexpr int kTokTiles = 2;        // token tiles of 32 accumulated per pass over the weights
-
-template <int FMT, typename X2>
-__global__ void __launch_bounds__(kThreads) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+// THREADS x TOKTILES: more token tiles per pass over the weights need more accumulator registers, i.e. fewer
+// waves per SIMD: 1024 threads x 2 tiles (64 tokens per pass) or 512 threads x 8 tiles (256 tokens per pass)
+template <int FMT, typename X2, int THREADS, int kTokTiles>
+__global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                         const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                         const uint32_t* __restrict__ x, int M, int N, int KB,
                                                         uint32_t steps_per_wave, float* __restrict__ y) {
-    load_tables(blob, lay.lds_bytes);
+    constexpr int kWavesHere = THREADS / 64;
+    load_tables<THREADS>(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
+    // steps (row tile, block pair) are numbered row tile major and dealt to the waves of the grid as contiguous ranges
     const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps per row tile
     const uint32_t n_rt = ((uint32_t)N + 31) / 32;
     const uint32_t total = n_rt * spt;
-    const uint32_t gw = (uint32_t)blockIdx.x * kWaves + wave;
+    const uint32_t gw = (uint32_t)blockIdx.x * kWavesHere + wave;
     const uint32_t s0 = gw * steps_per_wave;
     const uint32_t s1 = min(total, s0 + steps_per_wave);
     if (s0 >= s1) return;
@@ -374,27 +379,52 @@ __global__ void __launch_bounds__(kThreads) mfma_kernel(const unsigned char* __r
         const int ntile = min(kTokTiles, (M - m0 + 31) / 32);
         float16_t acc[kTokTiles];
 #pragma unroll
-        for (int t = 0; t < kTokTiles; t++) for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
-        uint32_t rt = s0 / spt, st = s0 - rt * spt;
-        // activation row pointers of this lane, one per token tile (clamped: out-of-range tokens are never stored)
-        const uint32_t* xrow[kTokTiles];
+        for (int t = 0; t < kTokTiles; t++) {
 #pragma unroll
-        for (int t = 0; t < kTokTiles; t++) xrow[t] = x + (size_t)min(M - 1, m0 + 32 * t + col) * xpitch;
+            for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
+        }
+        // activation rows of this lane as dword offsets, one per token tile (clamped: out-of-range tokens are never stored)
+        uint32_t xoff[kTokTiles];
+#pragma unroll
+        for (int t = 0; t < kTokTiles; t++) xoff[t] = (uint32_t)min(M - 1, m0 + 32 * t + col) * (uint32_t)xpitch;
 
+        // adds the accumulated tiles of weight-row tile `tile` to y and clears them
         auto flush = [&](uint32_t tile) {
             const int wrow = (int)tile * 32 + col;
+            if (wrow < N) {
+                // element offset of (token m0 + 4*half, weight row wrow); M*N < 2^32 is checked by the caller.
+                // Register v of tile t belongs to token m0 + 32 t + 8 (v/4) + 4 half + v%4.
+                uint32_t ot = (uint32_t)(m0 + 4 * half) * (uint32_t)N + (uint32_t)wrow;
+                const uint32_t un = (uint32_t)N;
+#pragma unroll
+                for (int t = 0; t < kTokTiles; t++) {
+                    if (t < ntile) {
+                        const int tok0 = m0 + 32 * t + 4 * half;
+                        const bool full = m0 + 32 * t + 32 <= M;
+                        uint32_t og = ot;
+#pragma unroll
+                        for (int q = 0; q < 4; q++) {
+                            uint32_t ov = og;
+#pragma unroll
+                            for (int r = 0; r < 4; r++) {
+                                if (full || tok0 + 8 * q + r < M) atomicAdd(y + ov, acc[t][4 * q + r]);
+                                ov += un;
+                            }
+                            og += 8 * un;
+                        }
+                    }
+                    ot += 32 * un;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
 #pragma unroll
             for (int t = 0; t < kTokTiles; t++) {
-                if (t >= ntile) break;
 #pragma unroll
-                for (int v = 0; v < 16; v++) {
-                    const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
-                    if (tok < M && wrow < N) atomicAdd(&y[(size_t)tok * N + wrow], acc[t][v]);
-                    acc[t][v] = 0.0f;
-                }
+                for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
             }
         };
 
+        uint32_t rt = s0 / spt, st = s0 - rt * spt;
         for (uint32_t s = s0; s < s1; s++) {
             const int row = (int)rt * 32 + col;
             const uint32_t b = 2 * st + half;
@@ -419,16 +449,20 @@ __global__ void __launch_bounds__(kThreads) mfma_kernel(const unsigned char* __r
             const uint32_t bx = min(b, (uint32_t)KB - 1) * 12;
 #pragma unroll
             for (int t = 0; t < kTokTiles; t++) {
-                if (t >= ntile) break;
-                const uint4* xp = reinterpret_cast<const uint4*>(xrow[t] + bx);
-                const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
-                const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
+                if (t < ntile) {
+                    const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(xoff[t] + bx));
+                    const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
+                    const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
 #pragma unroll
-                for (int j = 0; j < 6; j++) acc[t] = Mma<X2>::mma(xs[2 * j], xs[2 * j + 1], wt[2 * j], wt[2 * j + 1], acc[t]);
+                    for (int j = 0; j < 6; j++) acc[t] = Mma<X2>::mma(xs[2 * j], xs[2 * j + 1], wt[2 * j], wt[2 * j + 1], acc[t]);
+                }
+                if (kTokTiles > 2 && (t & 1)) __builtin_amdgcn_sched_barrier(0);   // keep only two tiles of activations in flight
             }
-            if (++st == spt) { flush(rt); st = 0; rt++; }
+            if (++st == spt || s + 1 == s1) {                                // end of the row tile or of this wave's range
+                flush(rt);
+                if (st == spt) { st = 0; rt++; }
+            }
         }
-        if (st != 0) flush(rt);
     }
 }
 
@@ -518,21 +552,28 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }
 
+template <int FMT, typename X2, int THREADS, int TOKTILES>
+static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+    const uint32_t total = (uint32_t)((N + 31) / 32) * (uint32_t)((KB + 1) / 2);
+    constexpr uint32_t wpg = THREADS / 64;
+    const uint32_t waves = (uint32_t)ctx->num_cu * wpg;
+    uint32_t spw = (total + waves - 1) / waves;
+    if (spw < 2) spw = 2;                                               // amortise the write-back of a partial tile
+    const int grid = (int)((total + spw * wpg - 1) / (spw * wpg));
+    const size_t lds = ctx->lay.lds_bytes;
+    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES>, lds)) return rc;
+    hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(grid), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, spw, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
+}
+
 template <int FMT, typename X2>
 static int launch_mfma(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
-    const uint32_t total = (uint32_t)((N + 31) / 32) * (uint32_t)((KB + 1) / 2);
-    const uint32_t waves = (uint32_t)ctx->num_cu * kWaves;
-    uint32_t spw = (total + waves - 1) / waves;
-    if (spw < 2) spw = 2;                                               // amortise the write-back of a partial tile
-    const int grid = (int)((total + spw * kWaves - 1) / (spw * kWaves));
-    const size_t lds = ctx->lay.lds_bytes;
-    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2>, lds)) return rc;
-    hipLaunchKernelGGL((mfma_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, spw, d_y);
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
+    if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+    return launch_mfma_cfg<FMT, X2, 512, 8>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
 }
 
 extern "C" {
@@ -629,7 +670,9 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* 
     if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     if (M >= kMfmaMinM) {
-        if ((size_t)((N + 31) / 32) * (size_t)((KB + 1) / 2) >= (1ull << 32)) return LLVQ_EINVAL;
+        if ((size_t)((N + 31) / 32) * (size_t)((KB + 1) / 2) >= (1ull << 32) || (size_t)M * (size_t)N >= (1ull << 32) ||
+            (size_t)M * (size_t)KB * 12 >= (1ull << 32))
+            return LLVQ_EINVAL;
         if (x_dtype == LLVQ_F16)
             return fmt == LLVQ_IDX_U48 ? launch_mfma<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
                                        : launch_mfma<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
