@@ -83,11 +83,16 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
                 void* d_out, int out_dtype, void* stream);
 
 /* Fused dequantise + multiply (paper App. C): d_y[m][n] = sum_k d_x[m][k] * W_hat[n][k], fp32.
- *   d_x   : [M][24*KB] row-major, x_dtype LLVQ_F16 or LLVQ_BF16, zero-padded by the caller
+ *   d_x   : [M][24*KB] row-major, x_dtype LLVQ_F16 or LLVQ_BF16, zero-padded by the caller; 16-byte aligned
  *   d_idx : [N][KB] indices in format `fmt`;  d_gain: [N][KB] fp16
  *   d_y   : [M][N] row-major fp32, overwritten
- * Products x * integer coordinate are exact in fp32; accumulation is fp32.  M = 1 is the decode
- * (matrix-vector) case the paper times; 1 <= M <= 1024.                                           */
+ * 1 <= M <= 1024.  M = 1 is the decode (matrix-vector) case the paper times.
+ * M <= 2: products activation * integer coordinate are exact in fp32, accumulated in fp32 and scaled by
+ *   gain / sqrt(16 m) per block (v_dot2 kernel).
+ * M >= 3 (batched decode, prefill): the weights gain * x / sqrt(16 m) are rounded to the activation type
+ *   (fp16: relative 2^-10, bf16: 2^-9) and contracted on the matrix cores with fp32 accumulation; partial sums
+ *   of different K ranges are combined with fp32 atomic adds, so the last bits of y can differ between calls.
+ *   Requires M*N < 2^32.                                                                               */
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
                 float* d_y, void* stream);

@@ -182,3 +182,41 @@ def test_matmul_invalid_arguments(gpu):
         gpu.llvq_matmul(x, idx, g, 3, 2)          # sizes do not match
     with pytest.raises(LLVQError):
         gpu._check(gpu._lib.llvq_matmul(gpu._h, x.data_ptr() + 2, 0, 1, idx.data_ptr(), 0, g.data_ptr(), 2, 2, y.data_ptr(), None), "misaligned x")
+
+
+def _round_to(a, kind):
+    """float64 array rounded to fp16 / bf16 (round to nearest even), returned as float64"""
+    if kind == "f16":
+        return a.astype(np.float16).astype(np.float64)
+    u = a.astype(np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("name,M,xd", [("q", 64, "f16"), ("q", 64, "bf16"), ("k", 256, "bf16"), ("q", 1024, "bf16"),
+                                       ("down", 64, "bf16"), ("gate", 100, "f16")])
+def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
+    """Config 4: the matrix-core path.  Weights enter the MFMA scaled and rounded to the activation type, so two
+    errors are checked: against the exact fp64 oracle (the 2e-3 bar) and against the oracle whose dequantised
+    weights are rounded to that type first, which isolates kernel mistakes from format rounding."""
+    import torch
+    N, K = synth.LLAMA3_8B[name]
+    x_dtype = "bf16" if xd == "bf16" else np.float16
+    idx, gain, x = synth.layer(4, hash((name, M)) % 1000, N, K, M, x_dtype=x_dtype)
+    KB = idx.shape[1]
+    d_x = _dev(x).to(torch.bfloat16 if xd == "bf16" else torch.float16)
+    y = gpu.llvq_matmul(d_x, _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), N, KB).cpu().numpy().astype(np.float64)
+    rows = np.sort(np.random.default_rng(M + N).choice(N, 48, replace=False))
+    ref = oracle13.matmul(x, idx[rows], gain[rows])
+    err = np.abs(y[:, rows] - ref).max() / np.abs(ref).max()
+    W = _round_to(oracle13.dequant(idx[rows], gain[rows]).reshape(rows.size, KB * 24), xd)
+    ref2 = x.astype(np.float64) @ W.T
+    err2 = np.abs(y[:, rows] - ref2).max() / np.abs(ref2).max()
+    print("prefill %s M=%d %s: err vs exact %.2e, vs rounded-weight oracle %.2e" % (name, M, xd, err, err2))
+    assert err <= TOL, err
+    assert err2 <= 5e-4, err2
+
+
+@pytest.mark.parametrize("N,K,M", [(33, 48, 3), (31, 24, 40), (100, 72, 65), (257, 24 * 7, 130), (64, 24 * 9, 300)])
+def test_mfma_ragged_shapes(gpu, oracle13, N, K, M):
+    _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M)
