@@ -21,6 +21,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
+ALU_PEAK_TLOPS = 39.3          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one vector instruction per lane and cycle
+VALU_PER_BLOCK = 454           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
+TRAFFIC_BYTES_PER_LAUNCH = 11881249  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
 
 
 def main():
@@ -30,7 +33,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--layers", type=int, default=96, help="distinct layers in the ring (96 x 5.6 MB = 538 MB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set (stderr)")
+    ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set, batch 16, prefill and bulk decode (stderr)")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy, so that a rocprofv3 --pmc run has a kernel of known HBM traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus %d is not supported (sharding is design-only)" % args.gpus)
@@ -106,6 +111,13 @@ def main():
 
     if args.extra:
         extra_layer_set(q, synth, torch, dev)
+        extra_shapes(q, synth, torch, dev)
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                       # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
 
     out = {
         "metric": "LLVQ dequant-GEMV GB/s (packed weights)", "value": gbs, "unit": "GB/s", "n_gpus": 1,
@@ -118,8 +130,12 @@ def main():
         "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
         "max_rel_err_vs_oracle": err,
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                     "traffic": None, "kernel": "matmul_kernel<U48,f16>", "kernel_ms": kern_ms,
-                     "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk},
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "kernel": "matmul_kernel<U48,f16>", "kernel_ms": kern_ms,
+                     "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk,
+                     # the kernel is bound by the vector ALU work of the index decode, not by HBM: second roofline
+                     "alu": {"achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
+                             "unit": "T lane-ops/s", "frac": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12 / ALU_PEAK_TLOPS,
+                             "valu_instructions_per_block": VALU_PER_BLOCK}},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
@@ -155,6 +171,46 @@ def extra_layer_set(q, synth, torch, dev):
     ms = e0.elapsed_time(e1) / reps
     print("llama3-8b layer set x4 (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed" % (tot * 8 / 1e6, ms, tot * 8 / ms / 1e6),
           file=sys.stderr)
+
+
+def extra_shapes(q, synth, torch, dev):
+    """Batch 16, prefill and bulk-decode timings on one gate/up-shaped layer (14336 x 4104), to stderr."""
+    import numpy as np
+    N, K = synth.LLAMA3_8B["gate"]
+    KB = synth.blocks_per_row(K)
+    r = synth.rng_for(3, 77)
+    idx = torch.from_numpy(synth.pack_u48(synth.indices(r, (N, KB))).reshape(-1)).to(dev)
+    gain = torch.from_numpy(synth.gains(r, (N, KB)).reshape(-1)).to(dev)
+
+    def timeit(f, reps=20):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    for M, dt in ((1, torch.float16), (16, torch.float16), (64, torch.bfloat16), (256, torch.bfloat16), (1024, torch.bfloat16)):
+        x = torch.from_numpy(synth.activations(r, M, K)).to(dev).to(dt)
+        y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        us = timeit(lambda: q.llvq_matmul(x, idx, gain, N, KB, out=y))
+        print("matmul %dx%d M=%-4d %s: %9.2f us  %.1f GB/s packed  %.1f TFLOP/s" %
+              (N, 24 * KB, M, str(dt).split(".")[-1], us, N * KB * 8 / us / 1e3, 2.0 * M * N * KB * 24 / us / 1e6), file=sys.stderr)
+    n = N * KB
+    for name, dt in (("int8", None), ("float16", torch.float16), ("bfloat16", torch.bfloat16), ("float32", torch.float32)):
+        if dt is None:
+            out = torch.empty((n, 24), dtype=torch.int8, device=dev)
+            us = timeit(lambda: q.llvq_decode_i8(idx, out=out))
+        else:
+            out = torch.empty((n, 24), dtype=dt, device=dev)
+            us = timeit(lambda: q.llvq_decode(idx, gain, out_dtype=dt, out=out))
+        ob = 24 * out.element_size()
+        print("bulk decode -> %-8s %d blocks: %9.2f us  %.2f G blocks/s  read+write %.1f GB/s" %
+              (name, n, us, n / us / 1e3, n * (8 + ob) / us / 1e3), file=sys.stderr)
 
 
 if __name__ == "__main__":
