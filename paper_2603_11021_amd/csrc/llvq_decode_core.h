@@ -132,7 +132,7 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
         c[u] = tab_at<uint32_t, kOffGs>(T, (((f1 >> F1_GOFF) & 4095u) + r) * 4u);
         e0[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb0 + rin) * 4u);
         e1[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb1 + rho1) * 4u);
-        j[u] = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * 32u + (d[u] >> ((f1 >> F1_GSHIFT) & 31u)));
+        j[u] = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * kGuessBuckets + (d[u] >> ((f1 >> F1_GSHIFT) & 31u)));
     }
 
     // App. A step 4, placement: the q-subset U of the outer domain's n slots with rank d

@@ -169,7 +169,7 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
 // row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the 16
 // waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
 // gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
-constexpr int kMaxMChunk = 16;    // activation rows handled per pass over the indices
+constexpr int kMaxMChunk = 2;     // activation rows handled per pass over the indices
 constexpr int kRowsPerPass = 64;  // output rows accumulated in LDS at a time
 
 template <typename X2> struct Dot;
@@ -189,13 +189,21 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
                                                           uint32_t kb_magic, int rows_per_wg, float* __restrict__ y) {
+    const int wg_r0 = blockIdx.x * rows_per_wg;
+    const int wg_r1 = min(N, wg_r0 + rows_per_wg);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    {
+        // touch this thread's first index and gain now: their trip from HBM overlaps the table load below
+        const size_t nb = (size_t)(wg_r1 - wg_r0) * KB;
+        const size_t k = (size_t)wg_r0 * KB + min((size_t)threadIdx.x, nb - 1);
+        const uint64_t warm_i = load_index<FMT>(idx, k);
+        const uint16_t warm_g = gain[k];
+        asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
+    }
     // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
     float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kRowsPerPass][kMaxMChunk]
-    const int wg_r0 = blockIdx.x * rows_per_wg;
-    const int wg_r1 = min(N, wg_r0 + rows_per_wg);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     for (int r0 = wg_r0; r0 < wg_r1; r0 += kRowsPerPass) {
@@ -606,7 +614,8 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     ctx->num_cu = prop.multiProcessorCount;
-    if (tabs.lay.lds_bytes + 4096 > prop.sharedMemPerBlock && tabs.lay.lds_bytes + 4096 > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
+    constexpr size_t kScratch = (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);    // the largest kernel scratch beside the tables
+    if (tabs.lay.lds_bytes + kScratch > prop.sharedMemPerBlock && tabs.lay.lds_bytes + kScratch > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
     if ((e = hipMalloc(&ctx->d_blob, tabs.blob.size())) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     if ((e = hipMalloc(&ctx->d_counter, sizeof(unsigned long long))) != hipSuccess) { (void)hipFree(ctx->d_blob); delete ctx; return LLVQ_EHIP; }
     if ((e = hipMemcpy(ctx->d_blob, tabs.blob.data(), tabs.blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {

@@ -235,7 +235,7 @@ bool build_tables(int m_max, Tables& out) {
         SplitInfo si;
         si.sp = (uint16_t)((int)split.size() - jmin);      // entry of j is split[sp + j]
         si.jmax = jmax;
-        si.row = (int)(guess.size() / 32);
+        si.row = (int)(guess.size() / kGuessBuckets);
         std::vector<uint64_t> bases;
         uint64_t base = 0;
         for (int j = jmin; j <= jmax; j++) {
@@ -254,9 +254,9 @@ bool build_tables(int m_max, Tables& out) {
         }
         uint64_t total = base;                              // C(n, q)
         int shift = 0;
-        while (((total - 1) >> shift) >= 32) shift++;
+        while (((total - 1) >> shift) >= kGuessBuckets) shift++;
         si.shift = shift;
-        for (int b = 0; b < 32; b++) {
+        for (uint32_t b = 0; b < kGuessBuckets; b++) {
             uint64_t d0 = (uint64_t)b << shift;
             int j = jmin;
             while (j < jmax && bases[j + 1 - jmin] <= d0) j++;
@@ -355,7 +355,7 @@ bool build_tables(int m_max, Tables& out) {
     cls_off[ncls] = running;
 
     // ---- bucket table: index >> shift -> class holding the first index of the bucket --------------------
-    const uint32_t bucket_shift = kBucketShift, nbuckets = 2048;
+    const uint32_t bucket_shift = kBucketShift, nbuckets = 1u << (48 - kBucketShift);
     std::vector<uint16_t> bucket(nbuckets);
     for (uint32_t b = 0; b < nbuckets; b++) {
         uint64_t first = (uint64_t)b << bucket_shift;

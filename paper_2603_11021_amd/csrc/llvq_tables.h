@@ -60,15 +60,16 @@ constexpr uint32_t kOffGs      = 0;        // 4096 x u32
 constexpr uint32_t kOffSpread6 = 16384;    // 4096 x u32
 constexpr uint32_t kOffPdep6   = 32768;    // 4096 x u8
 constexpr uint32_t kOffLut12   = 36864;    // 4096 x u16
-constexpr uint32_t kOffBucket  = 45056;    // 2048 x u16
-constexpr uint32_t kOffGuess   = 49152;    // up to 64 rows x 32 x u8
-constexpr uint32_t kOffAtab    = 51200;    // 4 x {A, 1/A} doubles
-constexpr uint32_t kOffClsOff  = 51264;    // (ncls + 1) x u64, ncls <= 383
-constexpr uint32_t kOffSplit   = 54400;    // up to 392 x SplitEnt
-constexpr uint32_t kOffCls     = 60672;    // ncls x ClassRec
-constexpr uint32_t kOffInner   = 79072;    // inner-word planes, u32
-constexpr uint32_t kMaxBlob    = 159744;   // 156 KB; the rest of the 160 KB of LDS is kernel scratch
-constexpr uint32_t kBucketShift = 37;      // bucket index = I >> 37 (2048 buckets cover 48 bits)
+constexpr uint32_t kOffBucket  = 45056;    // 4096 x u16
+constexpr uint32_t kOffGuess   = 53248;    // up to 48 rows x 64 x u8
+constexpr uint32_t kOffAtab    = 56320;    // 4 x {A, 1/A} doubles
+constexpr uint32_t kOffClsOff  = 56384;    // (ncls + 1) x u64, ncls <= 383
+constexpr uint32_t kOffSplit   = 59520;    // up to 352 x SplitEnt
+constexpr uint32_t kOffCls     = 65152;    // ncls x ClassRec
+constexpr uint32_t kOffInner   = 83552;    // inner-word planes, u32
+constexpr uint32_t kMaxBlob    = 162816;   // 159 KB; the last KB of the 160 KB of LDS is kernel scratch
+constexpr uint32_t kBucketShift = 36;      // bucket index = I >> 36 (4096 buckets cover 48 bits)
+constexpr uint32_t kGuessBuckets = 64;     // buckets of the subset-split guess table per (n, q)
 
 struct TableLayout {
     uint32_t lds_bytes;      // bytes of the blob = bytes resident in LDS
