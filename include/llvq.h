@@ -97,6 +97,16 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
                 float* d_y, void* stream);
 
+/* llvq_matmul with a caller-provided device workspace of ws_bytes >= N*KB*48 bytes (16-byte aligned).  For
+ * M >= 96 the weights are then dequantised ONCE into the workspace in the activation type (the kernel of
+ * llvq_decode) and multiplied by a plain dense library GEMM (rocBLAS, matrix cores, fp32 accumulation): the
+ * prefill path for large M, where re-decoding per token tile would dominate.  With a smaller workspace, a NULL
+ * one or a smaller M it behaves exactly like llvq_matmul.  The workspace content is overwritten; nothing is
+ * kept in it between calls.                                                                              */
+int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
+                   const void* d_idx, int fmt, const void* d_gain, int N, int KB,
+                   float* d_y, void* d_ws, size_t ws_bytes, void* stream);
+
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                   uint64_t* h_bad, void* stream);

@@ -12,6 +12,7 @@ LLVQ_F16, LLVQ_BF16, LLVQ_F32 = 0, 1, 2
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-std=c++17", "-fPIC", "-shared"]
+HIPCC_LIBS = ["-L/opt/rocm/lib", "-lrocblas"]
 
 
 class LLVQError(RuntimeError):
@@ -26,7 +27,7 @@ def build_library():
     """Compile the HIP kernels and the host table builder for gfx950 into libllvq.so (in-tree)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = [os.path.join(_CSRC, "llvq_kernels.hip"), os.path.join(_CSRC, "llvq_tables.cpp")]
-    subprocess.check_call([hipcc] + HIPCC_FLAGS + ["-o", _LIB] + srcs)
+    subprocess.check_call([hipcc] + HIPCC_FLAGS + ["-o", _LIB] + srcs + HIPCC_LIBS)
     return _LIB
 
 
@@ -50,6 +51,7 @@ def _load():
     lib.llvq_decode_i8.argtypes = [vp, vp, i32, sz, vp, vp]; lib.llvq_decode_i8.restype = i32
     lib.llvq_decode.argtypes = [vp, vp, i32, vp, sz, vp, i32, vp]; lib.llvq_decode.restype = i32
     lib.llvq_matmul.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp]; lib.llvq_matmul.restype = i32
+    lib.llvq_matmul_ws.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp, sz, vp]; lib.llvq_matmul_ws.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     _lib = lib
     return lib
@@ -126,7 +128,7 @@ class LLVQ:
                                           _stream_handle(stream)), "llvq_decode")
         return out
 
-    def llvq_matmul(self, x, idx, gain, N, KB, out=None, stream=None):
+    def llvq_matmul(self, x, idx, gain, N, KB, out=None, stream=None, workspace=None):
         import torch
         fmt, n = self._idx_fmt(idx)
         if n != N * KB or gain.numel() != N * KB or gain.dtype != torch.float16:
@@ -136,6 +138,11 @@ class LLVQ:
         M = x2.shape[0]
         if out is None:
             out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+        if workspace is not None:
+            self._check(self._lib.llvq_matmul_ws(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, gain.data_ptr(), N, KB,
+                                                 out.data_ptr(), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                 _stream_handle(stream)), "llvq_matmul_ws")
+            return out
         self._check(self._lib.llvq_matmul(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, gain.data_ptr(), N, KB,
                                           out.data_ptr(), _stream_handle(stream)), "llvq_matmul")
         return out

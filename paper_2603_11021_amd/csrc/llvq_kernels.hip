@@ -7,6 +7,7 @@
 // v_dot2_f32_f16 against activations that consecutive lanes read as consecutive 48-byte runs.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <rocblas/rocblas.h>
 
 #include <cstdio>
 #include <algorithm>
@@ -360,6 +361,7 @@ template <> struct Mma<bf16x2_t> {
     }
 };
 
+constexpr int kGemmMinM = 96;       // from this many activation rows on, llvq_matmul_ws dequantises once and calls a dense GEMM
 constexpr int kMfmaMinM = 3;        // from this many activation rows on, llvq_matmul uses the MFMA kernel
 // THREADS x TOKTILES: more token tiles per pass over the weights need more accumulator registers, i.e. fewer
 // waves per SIMD: 1024 threads x 2 tiles (64 tokens per pass) or 512 threads x 8 tiles (256 tokens per pass)
@@ -494,6 +496,7 @@ struct llvq_ctx {
     llvq::TableLayout lay{};
     unsigned char* d_blob = nullptr;
     unsigned long long* d_counter = nullptr;
+    rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     std::string hip_error;
 };
 
@@ -520,8 +523,9 @@ int set_lds(llvq_ctx* ctx, K kernel, size_t bytes) {
 }
 
 int grid_for(const llvq_ctx* ctx, size_t n) {
+    // grid-stride kernels: one workgroup per compute unit at most, so that the tables are loaded once per CU
     size_t wgs = (n + kThreads - 1) / kThreads;
-    size_t cap = (size_t)ctx->num_cu * 4;
+    size_t cap = (size_t)ctx->num_cu;
     return (int)(wgs < 1 ? 1 : (wgs > cap ? cap : wgs));
 }
 
@@ -630,6 +634,7 @@ void llvq_destroy(llvq_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     if (ctx->d_blob) (void)hipFree(ctx->d_blob);
     if (ctx->d_counter) (void)hipFree(ctx->d_counter);
+    if (ctx->blas) (void)rocblas_destroy_handle(ctx->blas);
     delete ctx;
 }
 
@@ -693,6 +698,30 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* 
                                    : launch_matmul<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
     return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
                                : launch_matmul<LLVQ_IDX_U64, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+}
+
+int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
+                   int N, int KB, float* d_y, void* d_ws, size_t ws_bytes, void* stream) {
+    const size_t need = (size_t)N * (size_t)KB * 24 * 2;
+    if (!ctx || !d_ws || ws_bytes < need || M < kGemmMinM)
+        return llvq_matmul(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, N, KB, d_y, stream);
+    if (!d_x || !d_gain || !d_y || M > 1024 || N < 1 || KB < 1) return LLVQ_EINVAL;
+    if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
+    if (!aligned(d_x, 16) || !aligned(d_ws, 16) || !aligned(d_y, 4)) return LLVQ_EALIGN;
+    // step 1: shape-gain reconstruction of the whole matrix into the workspace, in the activation type
+    if (int rc = llvq_decode(ctx, d_idx, fmt, d_gain, (size_t)N * KB, d_ws, x_dtype, stream)) return rc;
+    // step 2: plain dense GEMM y[M][N] = x[M][K] * W[N][K]^T on the matrix cores (library routine), fp32 accumulate
+    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->hip_error = "rocblas_create_handle failed"; return LLVQ_EHIP; }
+    if (rocblas_set_stream(ctx->blas, reinterpret_cast<hipStream_t>(stream)) != rocblas_status_success) { ctx->hip_error = "rocblas_set_stream failed"; return LLVQ_EHIP; }
+    const float alpha = 1.0f, beta = 0.0f;
+    const int K = 24 * KB;
+    const rocblas_datatype ab = x_dtype == LLVQ_F16 ? rocblas_datatype_f16_r : rocblas_datatype_bf16_r;
+    // column-major view: y^T (N x M, ld N) = W^T-as-stored (K x N, ld K) transposed  x  x^T-as-stored (K x M, ld K)
+    const rocblas_status st = rocblas_gemm_ex(ctx->blas, rocblas_operation_transpose, rocblas_operation_none, N, M, K, &alpha,
+                                              d_ws, ab, K, d_x, ab, K, &beta, d_y, rocblas_datatype_f32_r, N,
+                                              d_y, rocblas_datatype_f32_r, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
+    if (st != rocblas_status_success) { ctx->hip_error = std::string("rocblas_gemm_ex: ") + rocblas_status_to_string(st); return LLVQ_EHIP; }
+    return LLVQ_OK;
 }
 
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, uint64_t* h_bad, void* stream) {

@@ -220,3 +220,35 @@ def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
 @pytest.mark.parametrize("N,K,M", [(33, 48, 3), (31, 24, 40), (100, 72, 65), (257, 24 * 7, 130), (64, 24 * 9, 300)])
 def test_mfma_ragged_shapes(gpu, oracle13, N, K, M):
     _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M)
+
+
+@pytest.mark.parametrize("name,M,xd", [("q", 96, "f16"), ("k", 256, "bf16"), ("q", 1024, "bf16"), ("gate", 130, "f16")])
+def test_prefill_with_workspace(gpu, oracle13, name, M, xd):
+    """llvq_matmul_ws: weights dequantised once into the caller's workspace, then a dense GEMM.  The result must
+    agree with the oracle whose dequantised weights are rounded to the activation type (what the workspace holds)
+    and stay inside the 2e-3 bar against the exact oracle."""
+    import torch
+    N, K = synth.LLAMA3_8B[name]
+    x_dtype = "bf16" if xd == "bf16" else np.float16
+    idx, gain, x = synth.layer(4, hash((name, M, "ws")) % 1000, N, K, M, x_dtype=x_dtype)
+    KB = idx.shape[1]
+    tdt = torch.bfloat16 if xd == "bf16" else torch.float16
+    d_x = _dev(x).to(tdt)
+    ws = torch.empty(N * KB * 24, dtype=tdt, device="cuda:0")
+    args = (d_x, _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), N, KB)
+    y = gpu.llvq_matmul(*args, workspace=ws).cpu().numpy().astype(np.float64)
+    rows = np.sort(np.random.default_rng(M + N + 1).choice(N, 48, replace=False))
+    ref = oracle13.matmul(x, idx[rows], gain[rows])
+    W = _round_to(oracle13.dequant(idx[rows], gain[rows]).reshape(rows.size, KB * 24), xd)
+    ref2 = x.astype(np.float64) @ W.T
+    err = np.abs(y[:, rows] - ref).max() / np.abs(ref).max()
+    err2 = np.abs(y[:, rows] - ref2).max() / np.abs(ref2).max()
+    print("prefill+ws %s M=%d %s: err vs exact %.2e, vs rounded-weight oracle %.2e" % (name, M, xd, err, err2))
+    assert err <= TOL and err2 <= 5e-5
+    # the workspace holds the dequantised matrix in the activation type
+    got_w = ws.view(N, KB * 24)[torch.from_numpy(rows).to("cuda:0")].float().cpu().numpy().astype(np.float64)
+    assert np.abs(got_w - W).max() <= 2.0 ** -8 * np.abs(W).max()
+    # too small a workspace or a small M: same result as the fused path
+    y_small = gpu.llvq_matmul(*args, workspace=ws[:1024]).cpu().numpy()
+    y_fused = gpu.llvq_matmul(*args).cpu().numpy()
+    assert np.abs(y_small - y_fused).max() <= 1e-5 * np.abs(y_fused).max()
