@@ -252,3 +252,32 @@ def test_prefill_with_workspace(gpu, oracle13, name, M, xd):
     y_small = gpu.llvq_matmul(*args, workspace=ws[:1024]).cpu().numpy()
     y_fused = gpu.llvq_matmul(*args).cpu().numpy()
     assert np.abs(y_small - y_fused).max() <= 1e-5 * np.abs(y_fused).max()
+
+
+@pytest.mark.parametrize("m_max", [2, 3, 7, 12])
+def test_smaller_ball_cuts(m_max):
+    """contexts for Lambda_24(m_max) with m_max < 13: tables, decode and product against an oracle of the same cut"""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_11021_amd import LLVQ
+    from oracle.llvq_oracle import Oracle
+    o = Oracle(m_max)
+    g = LLVQ(m_max, 0)
+    assert g.num_points == o.num_points and g.num_classes == o.num_classes
+    rng = synth.rng_for(7, m_max)
+    idx = synth.indices(rng, 40000, o.num_points)
+    idx[:3] = (0, o.num_points - 1, o.num_points)          # first, last, one past the end
+    want, bad = o.decode(idx)
+    assert bad == 1
+    got = g.llvq_decode_i8(_dev(synth.pack_u48(idx).reshape(-1))).cpu().numpy()
+    assert np.array_equal(got, want)
+    N, KB, M = 50, 20, 3
+    idx2 = synth.indices(rng, (N, KB), o.num_points)
+    gain = synth.gains(rng, (N, KB))
+    x = synth.activations(rng, M, 24 * KB)
+    for xs in (x[:1], x):
+        y = g.llvq_matmul(_dev(xs).half(), _dev(synth.pack_u48(idx2).reshape(-1)), _dev(gain.reshape(-1)), N, KB).cpu().numpy()
+        ref = o.matmul(xs, idx2, gain)
+        assert np.abs(y - ref).max() / np.abs(ref).max() <= TOL
+    g.close()
