@@ -284,12 +284,15 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
 #pragma unroll
                         for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
                         float p = cur.live[u] ? acc * scale : 0.0f;
-                        if (two_rows) {
+                        if (row_hi == row_lo) {                                  // the whole batch lies in one row
+                            const float s_all = wave_sum(p);
+                            if (lane == 0) atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_all);
+                        } else if (two_rows) {
                             const float p_lo = row == row_lo ? p : 0.0f;
                             const float s_lo = wave_sum(p_lo), s_hi = wave_sum(p - p_lo);
                             if (lane == 0) {
                                 atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_lo);
-                                if (row_hi != row_lo) atomicAdd(&ysum[row_hi * kMaxMChunk + mi], s_hi);
+                                atomicAdd(&ysum[row_hi * kMaxMChunk + mi], s_hi);
                             }
                         } else {
                             // general case: segmented suffix sum over lanes of equal row
