@@ -47,7 +47,9 @@ enum {
 /* index storage formats */
 enum {
     LLVQ_IDX_U48 = 0,    /* 6 bytes per index, little endian, densely packed; 2-byte aligned base        */
-    LLVQ_IDX_U64 = 1     /* one uint64 per index (upper 16 bits ignored); 8-byte aligned base            */
+    LLVQ_IDX_U64 = 1,    /* one uint64 per index (upper 16 bits ignored); 8-byte aligned base            */
+    LLVQ_IDX_U24 = 2     /* 3 bytes per word, little endian, densely packed; no alignment requirement: the
+                            1 bit/weight layout of a single small shell (paper App. C, "single shell")      */
 };
 
 /* element types */
@@ -71,6 +73,10 @@ const char* llvq_last_hip_error(const llvq_ctx* ctx);
 uint64_t llvq_num_points(const llvq_ctx* ctx);
 /* number of classes over all shells (383 for m_max = 13) */
 int llvq_num_classes(const llvq_ctx* ctx);
+
+/* Index of the first point of shell m, i.e. N(m-1) of paper Table 1 (0 for m <= 2, N(m_max) for m > m_max):
+ * the base_index that makes a coded word address shell m alone.                                     */
+uint64_t llvq_shell_offset(const llvq_ctx* ctx, int m);
 
 /* Dequantiser of paper App. A: d_out[k][0..23] = integer coordinates of index k, int8.
  * d_idx: n_blocks indices in format `fmt`.                                                        */
@@ -106,6 +112,26 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                    const void* d_idx, int fmt, const void* d_gain, int N, int KB,
                    float* d_y, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Coded words (paper App. E "Shape-gain": one integer carries the shape index and the gain index; paper
+ * Sec. 4 tables, "1 bit / 2 bit gain"; paper App. C, single-shell variant).  A stored word v of 48 bits
+ * (LLVQ_IDX_U48, LLVQ_IDX_U64) or 24 bits (LLVQ_IDX_U24) is split as
+ *     lattice index I = (v mod 2^shape_bits) + base_index,      gain code c = v >> shape_bits,
+ * 1 <= shape_bits <= word bits, base_index < 2^48.  With d_gain_lut != NULL the gain of the block is
+ * d_gain_lut[c] (DEVICE, fp16, 2^(word bits - shape_bits) <= 4096 entries: the levels of the scalar gain
+ * quantiser) and d_gain is ignored (may be NULL); with d_gain_lut == NULL the bits above shape_bits are
+ * ignored and d_gain holds one fp16 per block as in the plain calls.  base_index = llvq_shell_offset(ctx, m)
+ * with shape_bits = ceil(log2 n(m)) addresses shell m alone.  I >= N(m_max) decodes to the zero block.
+ * Everything else (layouts, M ranges, rounding) is as in llvq_decode_i8 / llvq_decode / llvq_matmul.  */
+int llvq_decode_i8_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index,
+                         size_t n_blocks, int8_t* d_out, void* stream);
+int llvq_decode_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index,
+                      const void* d_gain_lut, const void* d_gain, size_t n_blocks,
+                      void* d_out, int out_dtype, void* stream);
+int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
+                      const void* d_idx, int fmt, int shape_bits, uint64_t base_index,
+                      const void* d_gain_lut, const void* d_gain, int N, int KB,
+                      float* d_y, void* stream);
 
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,

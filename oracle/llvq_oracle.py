@@ -9,6 +9,7 @@ reduces the matrix product to a library routine (numpy's fp64 matmul over the
 oracle-decoded dense matrix) so that the C triple loop has something other
 than itself to be compared with.
 """
+import atexit
 import ctypes
 import os
 import subprocess
@@ -29,9 +30,29 @@ def build(force=False):
     return _LIB
 
 
+_loaded = {}      # m_max -> path of the library image initialised for it
+
+
+def _image_for(m_max):
+    """The C oracle keeps its tables in globals, one ball cut per loaded image: every distinct m_max gets a
+    private copy of the shared object, so that oracles for different cuts can be alive at the same time."""
+    import shutil
+    import tempfile
+    path = build()
+    if m_max not in _loaded:
+        if _loaded:
+            fd, private = tempfile.mkstemp(prefix="liboracle_m%d_" % m_max, suffix=".so")
+            os.close(fd)
+            shutil.copyfile(path, private)
+            atexit.register(lambda f=private: os.path.exists(f) and os.remove(f))
+            path = private
+        _loaded[m_max] = path
+    return _loaded[m_max]
+
+
 class Oracle:
     def __init__(self, m_max=M_MAX_DEFAULT):
-        lib = ctypes.CDLL(build())
+        lib = ctypes.CDLL(_image_for(m_max))
         u64, i32 = ctypes.c_uint64, ctypes.c_int
         p = ctypes.c_void_p
         lib.oracle_init.argtypes = [i32]; lib.oracle_init.restype = i32

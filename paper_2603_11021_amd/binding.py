@@ -7,7 +7,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _CSRC = os.path.join(_HERE, "csrc")
 _LIB = os.path.join(_HERE, "libllvq.so")
 
-LLVQ_IDX_U48, LLVQ_IDX_U64 = 0, 1
+LLVQ_IDX_U48, LLVQ_IDX_U64, LLVQ_IDX_U24 = 0, 1, 2
 LLVQ_F16, LLVQ_BF16, LLVQ_F32 = 0, 1, 2
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -52,6 +52,10 @@ def _load():
     lib.llvq_decode.argtypes = [vp, vp, i32, vp, sz, vp, i32, vp]; lib.llvq_decode.restype = i32
     lib.llvq_matmul.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp]; lib.llvq_matmul.restype = i32
     lib.llvq_matmul_ws.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp, sz, vp]; lib.llvq_matmul_ws.restype = i32
+    lib.llvq_shell_offset.argtypes = [vp, i32]; lib.llvq_shell_offset.restype = u64
+    lib.llvq_decode_i8_coded.argtypes = [vp, vp, i32, i32, u64, sz, vp, vp]; lib.llvq_decode_i8_coded.restype = i32
+    lib.llvq_decode_coded.argtypes = [vp, vp, i32, i32, u64, vp, vp, sz, vp, i32, vp]; lib.llvq_decode_coded.restype = i32
+    lib.llvq_matmul_coded.argtypes = [vp, vp, i32, i32, vp, i32, i32, u64, vp, vp, i32, i32, vp, vp]; lib.llvq_matmul_coded.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     _lib = lib
     return lib
@@ -96,9 +100,16 @@ class LLVQ:
     def num_classes(self):
         return int(self._lib.llvq_num_classes(self._h))
 
+    def llvq_shell_offset(self, m):
+        return int(self._lib.llvq_shell_offset(self._h, m))
+
     @staticmethod
-    def _idx_fmt(idx):
+    def _idx_fmt(idx, fmt=None):
         import torch
+        if fmt == LLVQ_IDX_U24:
+            if idx.dtype != torch.uint8:
+                raise LLVQError("24-bit words are passed as a uint8 tensor, 3 bytes per word")
+            return LLVQ_IDX_U24, idx.numel() // 3
         if idx.dtype == torch.uint8:
             return LLVQ_IDX_U48, idx.numel() // 6
         if idx.dtype in (torch.int64, torch.uint64):
@@ -145,6 +156,60 @@ class LLVQ:
             return out
         self._check(self._lib.llvq_matmul(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, gain.data_ptr(), N, KB,
                                           out.data_ptr(), _stream_handle(stream)), "llvq_matmul")
+        return out
+
+    # ---- coded words: shape index in the low shape_bits (+ base_index), gain code above them ------------------
+    def llvq_decode_i8_coded(self, idx, shape_bits, base_index=0, fmt=None, out=None, stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx, fmt)
+        if out is None:
+            out = torch.empty((n, 24), dtype=torch.int8, device=idx.device)
+        self._check(self._lib.llvq_decode_i8_coded(self._h, idx.data_ptr(), fmt, shape_bits, base_index, n, out.data_ptr(),
+                                                   _stream_handle(stream)), "llvq_decode_i8_coded")
+        return out
+
+    @staticmethod
+    def _gain_args(gain_lut, gain, n):
+        import torch
+        for t, what in ((gain_lut, "gain_lut"), (gain, "gain")):
+            if t is not None and t.dtype != torch.float16:
+                raise LLVQError("%s must be float16" % what)
+        if gain is not None and gain.numel() != n:
+            raise LLVQError("gain must hold one entry per block")
+        return (gain_lut.data_ptr() if gain_lut is not None else None, gain.data_ptr() if gain is not None else None)
+
+    def llvq_decode_coded(self, idx, shape_bits, base_index=0, gain_lut=None, gain=None, fmt=None, out_dtype=None, out=None,
+                          stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx, fmt)
+        out_dtype = out_dtype or torch.float16
+        code = {torch.float16: LLVQ_F16, torch.bfloat16: LLVQ_BF16, torch.float32: LLVQ_F32}[out_dtype]
+        p_lut, p_gain = self._gain_args(gain_lut, gain, n)
+        if gain_lut is not None and gain_lut.numel() != 1 << ((24 if fmt == LLVQ_IDX_U24 else 48) - shape_bits):
+            raise LLVQError("gain_lut must hold 2^(word bits - shape_bits) entries")
+        if out is None:
+            out = torch.empty((n, 24), dtype=out_dtype, device=idx.device)
+        self._check(self._lib.llvq_decode_coded(self._h, idx.data_ptr(), fmt, shape_bits, base_index, p_lut, p_gain, n,
+                                                out.data_ptr(), code, _stream_handle(stream)), "llvq_decode_coded")
+        return out
+
+    def llvq_matmul_coded(self, x, idx, N, KB, shape_bits, base_index=0, gain_lut=None, gain=None, fmt=None, out=None,
+                          stream=None):
+        import torch
+        fmt, n = self._idx_fmt(idx, fmt)
+        if n != N * KB:
+            raise LLVQError("idx must hold N*KB words")
+        p_lut, p_gain = self._gain_args(gain_lut, gain, n)
+        if gain_lut is not None and gain_lut.numel() != 1 << ((24 if fmt == LLVQ_IDX_U24 else 48) - shape_bits):
+            raise LLVQError("gain_lut must hold 2^(word bits - shape_bits) entries")
+        code = {torch.float16: LLVQ_F16, torch.bfloat16: LLVQ_BF16}[x.dtype]
+        x2 = x.reshape(-1, 24 * KB)
+        M = x2.shape[0]
+        if out is None:
+            out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+        self._check(self._lib.llvq_matmul_coded(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, shape_bits, base_index,
+                                                p_lut, p_gain, N, KB, out.data_ptr(), _stream_handle(stream)),
+                    "llvq_matmul_coded")
         return out
 
     def llvq_validate(self, idx, stream=None):

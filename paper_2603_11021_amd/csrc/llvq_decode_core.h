@@ -73,6 +73,7 @@ LLVQ_HD bool wave_any(bool v) {
 struct BlockInfo {
     uint32_t cid;                // class id
     uint32_t m;                  // shell
+    float rnorm;                 // 1/sqrt(16 m): the factor that normalises the block to the unit sphere
     uint32_t vt8_lo, vt8_hi;     // value table of the class, fp8 bytes
     uint32_t vti_lo, vti_hi;     // value table of the class, int8
 };
@@ -177,6 +178,7 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
     for (int u = 0; u < NB; u++) {
         const uint32_t f0 = R[u].f0;
         info[u].cid = cid[u]; info[u].m = (f0 >> F0_M) & 15u;
+        info[u].rnorm = tab_at<float, kOffRnorm>(T, (f0 >> (F0_M - 2)) & 60u);
         info[u].vt8_lo = R[u].vt8_lo; info[u].vt8_hi = R[u].vt8_hi; info[u].vti_lo = R[u].vti_lo; info[u].vti_hi = R[u].vti_hi;
         // planes pre-shifted by two: the deposit keys below are byte offsets into a table of dwords
         const uint32_t a0 = (e0[u] & 0xFFFFu) << 2, b0 = (e0[u] >> 16) << 2, a1 = (e1[u] & 0xFFFFu) << 2, b1 = (e1[u] >> 16) << 2;

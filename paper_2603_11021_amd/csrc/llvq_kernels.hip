@@ -68,25 +68,50 @@ __device__ __forceinline__ float wave_sum(float v) {
            (__builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48)));
 }
 
+
 template <int FMT>
 __device__ __forceinline__ uint64_t load_index(const void* __restrict__ idx, size_t k) {
     if constexpr (FMT == LLVQ_IDX_U64) {
         return reinterpret_cast<const uint64_t*>(idx)[k] & 0xFFFFFFFFFFFFull;
+    } else if constexpr (FMT == LLVQ_IDX_U24) {
+        const uint8_t* p = reinterpret_cast<const uint8_t*>(idx) + 3 * k;
+        return (uint64_t)p[0] | ((uint64_t)p[1] << 8) | ((uint64_t)p[2] << 16);
     } else {
         const uint16_t* p = reinterpret_cast<const uint16_t*>(idx) + 3 * k;
         return (uint64_t)p[0] | ((uint64_t)p[1] << 16) | ((uint64_t)p[2] << 32);
     }
 }
 
+// How a stored code word maps to (lattice index, gain): index = (word & mask) + base; the gain is either the
+// per-block fp16 array or entry (word >> shape_bits) of a small table (gain bits carried inside the word).
+struct Code {
+    uint64_t base;
+    uint64_t mask;
+    const uint16_t* lut;       // nullptr: gains come from the per-block array
+    uint32_t shape_bits;
+    uint32_t lut_last;         // last valid entry of lut
+};
+
+template <int FMT>
+__device__ __forceinline__ void load_block(const void* __restrict__ idx, const uint16_t* __restrict__ gain, const Code& cd,
+                                           size_t k, uint64_t& I, uint16_t& g) {
+    const uint64_t v = load_index<FMT>(idx, k);
+    if (cd.lut) g = cd.lut[min((uint32_t)(v >> cd.shape_bits), cd.lut_last)];
+    else g = gain ? gain[k] : (uint16_t)0;
+    I = (v & cd.mask) + cd.base;
+}
+
 // ---- llvq_decode_i8 ---------------------------------------------------------------------------------
 template <int FMT>
 __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
-                                                             const void* __restrict__ idx, size_t n,
+                                                             const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
-        const uint64_t I = load_index<FMT>(idx, k);
+        uint64_t I;
+        uint16_t gdummy;
+        load_block<FMT>(idx, nullptr, cd, k, I, gdummy);
         const bool ok = I < T.npoints;
         uint32_t w[4], o[6];
         const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
@@ -118,17 +143,19 @@ __device__ __forceinline__ void chunk_fp8(uint32_t w, uint32_t vt_lo, uint32_t v
 template <int FMT, int OUT>
 __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                            const void* __restrict__ idx, const uint16_t* __restrict__ gain,
-                                                           size_t n, void* __restrict__ out) {
+                                                           Code cd, size_t n, void* __restrict__ out) {
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
-        const uint64_t I = load_index<FMT>(idx, k);
+        uint64_t I;
+        uint16_t gb;
+        load_block<FMT>(idx, gain, cd, k, I, gb);
         const bool ok = I < T.npoints;
         uint32_t w[4];
         const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
-        const uint32_t vt_lo = bi.vt8_lo, vt_hi = bi.vt8_hi, m = bi.m;
-        const float g = __half2float(__ushort_as_half(gain[k]));
-        const float scale = ok ? g * lay.rnorm[m] : 0.0f;
+        const uint32_t vt_lo = bi.vt8_lo, vt_hi = bi.vt8_hi;
+        const float g = __half2float(__ushort_as_half(gb));
+        const float scale = ok ? g * bi.rnorm : 0.0f;
         float v[24];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
@@ -183,13 +210,15 @@ template <> struct Dot<bf16x2_t> {
     static __device__ __forceinline__ float dot(bf16x2_t a, bf16x2_t b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
 };
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kNB = 1;              // blocks decoded per lane and pass, interleaved to overlap table reads
 
 template <int FMT, typename X2>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                          uint32_t kb_magic, int rows_per_wg, float* __restrict__ y) {
+                                                          Code cd, uint32_t kb_magic, int rows_per_wg, float* __restrict__ y) {
     const int wg_r0 = blockIdx.x * rows_per_wg;
     const int wg_r1 = min(N, wg_r0 + rows_per_wg);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -197,8 +226,9 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         // touch this thread's first index and gain now: their trip from HBM overlaps the table load below
         const size_t nb = (size_t)(wg_r1 - wg_r0) * KB;
         const size_t k = (size_t)wg_r0 * KB + min((size_t)threadIdx.x, nb - 1);
-        const uint64_t warm_i = load_index<FMT>(idx, k);
-        const uint16_t warm_g = gain[k];
+        uint64_t warm_i;
+        uint16_t warm_g;
+        load_block<FMT>(idx, gain, cd, k, warm_i, warm_g);
         asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
     }
     // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
@@ -227,8 +257,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                     // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
                     f.row[u] = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
                     f.b[u] = fbc - f.row[u] * (uint32_t)KB;
-                    f.I[u] = load_index<FMT>(idx, blk0 + fbc);
-                    f.g[u] = gain[blk0 + fbc];
+                    load_block<FMT>(idx, gain, cd, blk0 + fbc, f.I[u], f.g[u]);
                 }
             };
             const uint32_t stride = kWaves * 64 * kNB;
@@ -237,10 +266,10 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             if (base < nblk) fetch(base, cur);
             for (; base < nblk; base += stride) {
                 if (base + stride < nblk) fetch(base + stride, nxt);
-                uint4 xq[kNB][3];
+                u32x4 xq[kNB][3];
 #pragma unroll
                 for (int u = 0; u < kNB; u++) {
-                    const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)m0 * xpitch + (size_t)cur.b[u] * 12);
+                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)m0 * xpitch + (size_t)cur.b[u] * 12);
                     xq[u][0] = xp[0]; xq[u][1] = xp[1]; xq[u][2] = xp[2];
                 }
                 uint64_t I[kNB];
@@ -256,9 +285,9 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
 #pragma unroll
                 for (int u = 0; u < kNB; u++) {
                     if (base + 64 * u >= nblk) break;                       // wave-uniform: this batch is empty
-                    const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi, m = bi[u].m;
+                    const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi;
                     const float g = __half2float(__ushort_as_half(cur.g[u]));
-                    const float scale = ok[u] ? g * lay.rnorm[m] : 0.0f;
+                    const float scale = ok[u] ? g * bi[u].rnorm : 0.0f;
                     X2 wt[12];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
@@ -274,9 +303,9 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                     const uint32_t row_hi = __builtin_amdgcn_readlane(row, 63);
                     const bool two_rows = row_hi <= row_lo + 1;
                     for (int mi = 0; mi < mc; mi++) {
-                        uint4 x0 = xq[u][0], x1 = xq[u][1], x2 = xq[u][2];
+                        u32x4 x0 = xq[u][0], x1 = xq[u][1], x2 = xq[u][2];
                         if (mi > 0) {
-                            const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b[u] * 12);
+                            const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b[u] * 12);
                             x0 = xp[0]; x1 = xp[1]; x2 = xp[2];
                         }
                         const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
@@ -372,7 +401,7 @@ template <int FMT, typename X2, int THREADS, int kTokTiles>
 __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                         const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                         const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                        uint32_t steps_per_wave, float* __restrict__ y) {
+                                                        Code cd, uint32_t steps_per_wave, float* __restrict__ y) {
     constexpr int kWavesHere = THREADS / 64;
     load_tables<THREADS>(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
@@ -443,13 +472,15 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
             const uint32_t b = 2 * st + half;
             const bool live = row < N && b < (uint32_t)KB;
             const size_t k = (size_t)min(row, N - 1) * KB + min(b, (uint32_t)KB - 1);
-            uint64_t I = load_index<FMT>(idx, k);
-            const float g = __half2float(__ushort_as_half(gain[k]));
+            uint64_t I;
+            uint16_t gb;
+            load_block<FMT>(idx, gain, cd, k, I, gb);
+            const float g = __half2float(__ushort_as_half(gb));
             const bool ok = live && I < T.npoints;
             if (!ok) I = 0;
             uint32_t w[4];
             const llvq::BlockInfo bi = llvq::decode_block(T, I, w);
-            const float scale = ok ? g * lay.rnorm[bi.m] : 0.0f;
+            const float scale = ok ? g * bi.rnorm : 0.0f;
             uint32_t wt[12];
 #pragma unroll
             for (int c = 0; c < 4; c++) {
@@ -497,6 +528,7 @@ struct llvq_ctx {
     int m_max = 0;
     int num_cu = 0;
     llvq::TableLayout lay{};
+    uint64_t shell_off[16] = {};            // first index of each shell
     unsigned char* d_blob = nullptr;
     unsigned long long* d_counter = nullptr;
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
@@ -516,6 +548,7 @@ int check_idx(const void* d_idx, int fmt) {
     if (!d_idx) return LLVQ_EINVAL;
     if (fmt == LLVQ_IDX_U48) return aligned(d_idx, 2) ? LLVQ_OK : LLVQ_EALIGN;
     if (fmt == LLVQ_IDX_U64) return aligned(d_idx, 8) ? LLVQ_OK : LLVQ_EALIGN;
+    if (fmt == LLVQ_IDX_U24) return LLVQ_OK;
     return LLVQ_EINVAL;
 }
 
@@ -535,14 +568,24 @@ int grid_for(const llvq_ctx* ctx, size_t n) {
 }  // namespace
 
 template <int FMT>
-static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, size_t n, void* d_out, int out_dtype, hipStream_t st) {
+static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
+    const size_t lds = ctx->lay.lds_bytes;
+    const int grid = grid_for(ctx, n);
+    if (int rc = set_lds(ctx, decode_i8_kernel<FMT>, lds)) return rc;
+    hipLaunchKernelGGL(decode_i8_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "decode_i8 launch");
+}
+
+template <int FMT>
+static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, const Code& cd, size_t n, void* d_out, int out_dtype, hipStream_t st) {
     const size_t lds = ctx->lay.lds_bytes;
     const int grid = grid_for(ctx, n);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
 #define LLVQ_LAUNCH_DQ(OUT)                                                                                     \
     do {                                                                                                          \
         if (int rc = set_lds(ctx, dequant_kernel<FMT, OUT>, lds)) return rc;                                      \
-        hipLaunchKernelGGL((dequant_kernel<FMT, OUT>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, n, d_out); \
+        hipLaunchKernelGGL((dequant_kernel<FMT, OUT>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, cd, n, d_out); \
     } while (0)
     if (out_dtype == LLVQ_F16) LLVQ_LAUNCH_DQ(LLVQ_F16);
     else if (out_dtype == LLVQ_BF16) LLVQ_LAUNCH_DQ(LLVQ_BF16);
@@ -553,7 +596,7 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
 }
 
 template <int FMT, typename X2>
-static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     // one persistent workgroup per compute unit (the tables fill its LDS), rows split evenly among them
     int grid = ctx->num_cu < N ? ctx->num_cu : N;
     const int rows = (N + grid - 1) / grid;
@@ -562,13 +605,13 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
     if (int rc = set_lds(ctx, matmul_kernel<FMT, X2>, lds)) return rc;
     hipLaunchKernelGGL((matmul_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, kb_magic, rows, d_y);
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }
 
 template <int FMT, typename X2, int THREADS, int TOKTILES>
-static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     const uint32_t total = (uint32_t)((N + 31) / 32) * (uint32_t)((KB + 1) / 2);
     constexpr uint32_t wpg = THREADS / 64;
     const uint32_t waves = (uint32_t)ctx->num_cu * wpg;
@@ -578,18 +621,101 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
     const size_t lds = ctx->lay.lds_bytes;
     if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES>, lds)) return rc;
     hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(grid), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, spw, d_y);
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, spw, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
 }
 
+template <int FMT>
+static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n, hipStream_t st) {
+    hipLaunchKernelGGL(validate_kernel<FMT>, dim3(grid), dim3(256), 0, st, d_idx, n, ctx->lay.npoints, ctx->d_counter);
+    return 0;
+}
+
 template <int FMT, typename X2>
-static int launch_mfma(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
+    if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
-    if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
-    return launch_mfma_cfg<FMT, X2, 512, 8>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+    if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    return launch_mfma_cfg<FMT, X2, 512, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
 }
+
+// evaluates EXPR with the constant F set to the storage format `fmt` (which check_idx has accepted)
+#define LLVQ_BY_FMT(fmt, EXPR)                                                                 \
+    ((fmt) == LLVQ_IDX_U48   ? [&] { constexpr int F = LLVQ_IDX_U48; return (EXPR); }()       \
+     : (fmt) == LLVQ_IDX_U64 ? [&] { constexpr int F = LLVQ_IDX_U64; return (EXPR); }()       \
+                             : [&] { constexpr int F = LLVQ_IDX_U24; return (EXPR); }())
+
+namespace {
+
+int word_bits(int fmt) { return fmt == LLVQ_IDX_U24 ? 24 : 48; }
+
+// the stored word is the index itself, gains come from the per-block array
+Code plain_code(int fmt) {
+    Code cd;
+    cd.base = 0;
+    cd.mask = (1ull << word_bits(fmt)) - 1;
+    cd.lut = nullptr;
+    cd.shape_bits = (uint32_t)word_bits(fmt);
+    cd.lut_last = 0;
+    return cd;
+}
+
+// layout of a coded word (see llvq_*_coded in llvq.h); checks the arguments
+int make_code(int fmt, int shape_bits, uint64_t base_index, const void* d_gain_lut, Code& cd) {
+    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64 && fmt != LLVQ_IDX_U24) return LLVQ_EINVAL;
+    const int wb = word_bits(fmt);
+    if (shape_bits < 1 || shape_bits > wb || base_index >= (1ull << 48)) return LLVQ_EINVAL;
+    if (d_gain_lut && wb - shape_bits > 12) return LLVQ_EINVAL;
+    if (d_gain_lut && !aligned(d_gain_lut, 2)) return LLVQ_EALIGN;
+    cd.base = base_index;
+    cd.mask = (1ull << shape_bits) - 1;
+    cd.lut = reinterpret_cast<const uint16_t*>(d_gain_lut);
+    cd.shape_bits = (uint32_t)shape_bits;
+    cd.lut_last = (1u << (wb - shape_bits)) - 1;
+    return LLVQ_OK;
+}
+
+int decode_i8_impl(llvq_ctx* ctx, const void* d_idx, int fmt, const Code& cd, size_t n_blocks, int8_t* d_out, void* stream) {
+    if (n_blocks == 0) return LLVQ_OK;                                   // nothing to read or write
+    if (!d_out) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_out, 8)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return LLVQ_BY_FMT(fmt, launch_decode_i8<F>(ctx, d_idx, cd, n_blocks, d_out, st));
+}
+
+int decode_impl(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, const Code& cd, size_t n_blocks, void* d_out,
+                int out_dtype, void* stream) {
+    if (out_dtype != LLVQ_F16 && out_dtype != LLVQ_BF16 && out_dtype != LLVQ_F32) return LLVQ_EINVAL;
+    if (n_blocks == 0) return LLVQ_OK;
+    if (!d_out || (!d_gain && !cd.lut)) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_out, 16) || !aligned(d_gain, 2)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return LLVQ_BY_FMT(fmt, launch_dequant<F>(ctx, d_idx, d_gain, cd, n_blocks, d_out, out_dtype, st));
+}
+
+int matmul_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain, const Code& cd,
+                int N, int KB, float* d_y, void* stream) {
+    if (!d_x || (!d_gain && !cd.lut) || !d_y) return LLVQ_EINVAL;
+    if (M < 1 || M > 1024 || N < 1 || KB < 1) return LLVQ_EINVAL;
+    if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
+    if ((size_t)N * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
+    if (M >= kMfmaMinM && ((size_t)((N + 31) / 32) * (size_t)((KB + 1) / 2) >= (1ull << 32) || (size_t)M * (size_t)N >= (1ull << 32) ||
+                           (size_t)M * (size_t)KB * 12 >= (1ull << 32)))
+        return LLVQ_EINVAL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (x_dtype == LLVQ_F16) return LLVQ_BY_FMT(fmt, (launch_any_matmul<F, half2_t>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st)));
+    return LLVQ_BY_FMT(fmt, (launch_any_matmul<F, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st)));
+}
+
+bool plain_fmt(int fmt) { return fmt == LLVQ_IDX_U48 || fmt == LLVQ_IDX_U64 || fmt == LLVQ_IDX_U24; }
+
+}  // namespace
 
 extern "C" {
 
@@ -616,6 +742,7 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     llvq_ctx* ctx = new (std::nothrow) llvq_ctx;
     if (!ctx) return LLVQ_EINVAL;
     ctx->device = device; ctx->m_max = m_max; ctx->lay = tabs.lay;
+    for (int m = 0; m < 16; m++) ctx->shell_off[m] = tabs.shell_off[m];
     hipError_t e;
     if ((e = hipSetDevice(device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     hipDeviceProp_t prop;
@@ -644,63 +771,51 @@ void llvq_destroy(llvq_ctx* ctx) {
 uint64_t llvq_num_points(const llvq_ctx* ctx) { return ctx ? ctx->lay.npoints : 0; }
 int llvq_num_classes(const llvq_ctx* ctx) { return ctx ? (int)ctx->lay.ncls : 0; }
 
+uint64_t llvq_shell_offset(const llvq_ctx* ctx, int m) {
+    if (!ctx || m < 2) return 0;
+    if (m > ctx->m_max) return ctx->lay.npoints;
+    return ctx->shell_off[m];
+}
+
 int llvq_decode_i8(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, int8_t* d_out, void* stream) {
-    if (!ctx) return LLVQ_EINVAL;
-    if (n_blocks == 0) return (fmt == LLVQ_IDX_U48 || fmt == LLVQ_IDX_U64) ? LLVQ_OK : LLVQ_EINVAL;   // nothing to read or write
-    if (!d_out) return LLVQ_EINVAL;
-    if (int rc = check_idx(d_idx, fmt)) return rc;
-    if (!aligned(d_out, 8)) return LLVQ_EALIGN;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const size_t lds = ctx->lay.lds_bytes;
-    const int grid = grid_for(ctx, n_blocks);
-    if (fmt == LLVQ_IDX_U48) {
-        if (int rc = set_lds(ctx, decode_i8_kernel<LLVQ_IDX_U48>, lds)) return rc;
-        hipLaunchKernelGGL(decode_i8_kernel<LLVQ_IDX_U48>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, n_blocks, reinterpret_cast<uint32_t*>(d_out));
-    } else {
-        if (int rc = set_lds(ctx, decode_i8_kernel<LLVQ_IDX_U64>, lds)) return rc;
-        hipLaunchKernelGGL(decode_i8_kernel<LLVQ_IDX_U64>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, n_blocks, reinterpret_cast<uint32_t*>(d_out));
-    }
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "decode_i8 launch");
+    if (!ctx || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    return decode_i8_impl(ctx, d_idx, fmt, plain_code(fmt), n_blocks, d_out, stream);
 }
 
 int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks, void* d_out, int out_dtype, void* stream) {
-    if (!ctx) return LLVQ_EINVAL;
-    if (out_dtype != LLVQ_F16 && out_dtype != LLVQ_BF16 && out_dtype != LLVQ_F32) return LLVQ_EINVAL;
-    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
-    if (n_blocks == 0) return LLVQ_OK;
-    if (!d_out || !d_gain) return LLVQ_EINVAL;
-    if (int rc = check_idx(d_idx, fmt)) return rc;
-    if (!aligned(d_out, 16) || !aligned(d_gain, 2)) return LLVQ_EALIGN;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    return fmt == LLVQ_IDX_U48 ? launch_dequant<LLVQ_IDX_U48>(ctx, d_idx, d_gain, n_blocks, d_out, out_dtype, st)
-                               : launch_dequant<LLVQ_IDX_U64>(ctx, d_idx, d_gain, n_blocks, d_out, out_dtype, st);
+    if (!ctx || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    if (n_blocks && !d_gain) return LLVQ_EINVAL;
+    return decode_impl(ctx, d_idx, fmt, d_gain, plain_code(fmt), n_blocks, d_out, out_dtype, stream);
 }
 
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
                 int N, int KB, float* d_y, void* stream) {
-    if (!ctx || !d_x || !d_gain || !d_y) return LLVQ_EINVAL;
-    if (M < 1 || M > 1024 || N < 1 || KB < 1) return LLVQ_EINVAL;
-    if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
-    if ((size_t)N * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
-    if (int rc = check_idx(d_idx, fmt)) return rc;
-    if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
-    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (M >= kMfmaMinM) {
-        if ((size_t)((N + 31) / 32) * (size_t)((KB + 1) / 2) >= (1ull << 32) || (size_t)M * (size_t)N >= (1ull << 32) ||
-            (size_t)M * (size_t)KB * 12 >= (1ull << 32))
-            return LLVQ_EINVAL;
-        if (x_dtype == LLVQ_F16)
-            return fmt == LLVQ_IDX_U48 ? launch_mfma<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
-                                       : launch_mfma<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
-        return fmt == LLVQ_IDX_U48 ? launch_mfma<LLVQ_IDX_U48, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
-                                   : launch_mfma<LLVQ_IDX_U64, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
-    }
-    if (x_dtype == LLVQ_F16)
-        return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
-                                   : launch_matmul<LLVQ_IDX_U64, half2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
-    return fmt == LLVQ_IDX_U48 ? launch_matmul<LLVQ_IDX_U48, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st)
-                               : launch_matmul<LLVQ_IDX_U64, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, N, KB, d_y, st);
+    if (!ctx || !d_gain || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, plain_code(fmt), N, KB, d_y, stream);
+}
+
+int llvq_decode_i8_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index, size_t n_blocks,
+                         int8_t* d_out, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    Code cd;
+    if (int rc = make_code(fmt, shape_bits, base_index, nullptr, cd)) return rc;
+    return decode_i8_impl(ctx, d_idx, fmt, cd, n_blocks, d_out, stream);
+}
+
+int llvq_decode_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index, const void* d_gain_lut,
+                      const void* d_gain, size_t n_blocks, void* d_out, int out_dtype, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    Code cd;
+    if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
+    return decode_impl(ctx, d_idx, fmt, d_gain, cd, n_blocks, d_out, out_dtype, stream);
+}
+
+int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, int shape_bits,
+                      uint64_t base_index, const void* d_gain_lut, const void* d_gain, int N, int KB, float* d_y, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    Code cd;
+    if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
+    return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, cd, N, KB, d_y, stream);
 }
 
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
@@ -728,8 +843,7 @@ int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const voi
 }
 
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, uint64_t* h_bad, void* stream) {
-    if (!ctx || !h_bad) return LLVQ_EINVAL;
-    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
+    if (!ctx || !h_bad || !plain_fmt(fmt)) return LLVQ_EINVAL;
     if (n_blocks) { if (int rc = check_idx(d_idx, fmt)) return rc; }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     hipError_t e;
@@ -737,8 +851,7 @@ int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, ui
     if ((e = hipMemcpyAsync(ctx->d_counter, &zero, sizeof zero, hipMemcpyHostToDevice, st)) != hipSuccess) return hip_fail(ctx, e, "validate reset");
     if (n_blocks) {
         const int grid = grid_for(ctx, n_blocks);
-        if (fmt == LLVQ_IDX_U48) hipLaunchKernelGGL(validate_kernel<LLVQ_IDX_U48>, dim3(grid), dim3(256), 0, st, d_idx, n_blocks, ctx->lay.npoints, ctx->d_counter);
-        else hipLaunchKernelGGL(validate_kernel<LLVQ_IDX_U64>, dim3(grid), dim3(256), 0, st, d_idx, n_blocks, ctx->lay.npoints, ctx->d_counter);
+        LLVQ_BY_FMT(fmt, launch_validate<F>(ctx, grid, d_idx, n_blocks, st));
         if ((e = hipGetLastError()) != hipSuccess) return hip_fail(ctx, e, "validate launch");
     }
     unsigned long long got = 0;

@@ -130,7 +130,9 @@ bool build_tables(int m_max, Tables& out) {
     // ---- classes ----------------------------------------------------------------------------------
     std::vector<Leader> cls;
     uint64_t running = 0;
+    for (int m = 0; m < 16; m++) out.shell_off[m] = 0;
     for (int m = 2; m <= m_max; m++) {
+        out.shell_off[m] = running;
         std::vector<Leader> shell;
         int vmax = (int)std::floor(std::sqrt(16.0 * m) + 1e-9);
         for (int odd = 0; odd < 2; odd++) {
@@ -166,6 +168,7 @@ bool build_tables(int m_max, Tables& out) {
     }
     const uint32_t ncls = (uint32_t)cls.size();
     if (running >= (1ull << 48)) return false;
+    for (int m = m_max + 1; m < 16; m++) out.shell_off[m] = running;
 
     // ---- lut12: colex rank -> mask, grouped by popcount ---------------------------------------------
     std::vector<uint16_t> lut12;
@@ -383,7 +386,7 @@ bool build_tables(int m_max, Tables& out) {
                                 2576.0, (1.0 / 2576.0) * (1.0 + std::ldexp(1.0, -50)), 4096.0, 1.0 / 4096.0};
     TableLayout lay{};
     const uint32_t inner_end = kOffInner + (uint32_t)(inner.size() * sizeof(uint32_t));
-    if (guess.size() > kOffAtab - kOffGuess || cls_off.size() * 8 > kOffSplit - kOffClsOff ||
+    if (guess.size() > kOffAtab - kOffGuess || cls_off.size() * 8 > kOffRnorm - kOffClsOff ||
         (split.size() + 1) * sizeof(SplitEnt) > kOffCls - kOffSplit || recs.size() * sizeof(ClassRec) > kOffInner - kOffCls ||
         inner_end > kMaxBlob)
         return false;
@@ -397,6 +400,9 @@ bool build_tables(int m_max, Tables& out) {
     put(kOffGuess, guess.data(), guess.size());
     put(kOffAtab, atab.data(), atab.size() * 8);
     put(kOffClsOff, cls_off.data(), cls_off.size() * 8);
+    float rnorm[16];
+    for (int m = 0; m < 16; m++) rnorm[m] = m >= 1 ? (float)(1.0 / std::sqrt(16.0 * m)) : 0.0f;
+    put(kOffRnorm, rnorm, sizeof rnorm);
     put(kOffSplit, split.data(), split.size() * sizeof(SplitEnt));
     put(kOffCls, recs.data(), recs.size() * sizeof(ClassRec));
     put(kOffInner, inner.data(), inner.size() * 4);
@@ -404,7 +410,7 @@ bool build_tables(int m_max, Tables& out) {
     lay.ncls = ncls;
     lay.inner_entries = (uint32_t)inner.size();
     lay.npoints = running;
-    for (int m = 0; m < 16; m++) lay.rnorm[m] = m >= 1 ? (float)(1.0 / std::sqrt(16.0 * m)) : 0.0f;
+    for (int m = 0; m < 16; m++) lay.rnorm[m] = rnorm[m];
     out.lay = lay;
     out.blob.swap(blob);
     return true;

@@ -64,6 +64,7 @@ constexpr uint32_t kOffBucket  = 45056;    // 4096 x u16
 constexpr uint32_t kOffGuess   = 53248;    // up to 48 rows x 64 x u8
 constexpr uint32_t kOffAtab    = 56320;    // 4 x {A, 1/A} doubles
 constexpr uint32_t kOffClsOff  = 56384;    // (ncls + 1) x u64, ncls <= 383
+constexpr uint32_t kOffRnorm   = 59456;    // 16 x float: 1/sqrt(16 m)
 constexpr uint32_t kOffSplit   = 59520;    // up to 352 x SplitEnt
 constexpr uint32_t kOffCls     = 65152;    // ncls x ClassRec
 constexpr uint32_t kOffInner   = 83552;    // inner-word planes, u32
@@ -85,6 +86,7 @@ static constexpr int kNibbleSlot[6] = {0, 2, 1, 3, 4, 6};
 
 struct Tables {
     TableLayout lay;
+    uint64_t shell_off[16];  // index of the first point of shell m (N(m-1)); entries above m_max hold N(m_max)
     std::vector<unsigned char> blob;
 };
 

@@ -52,6 +52,22 @@ def pack_u48(idx):
     return np.ascontiguousarray(b).reshape(idx.shape + (6,))
 
 
+def pack_u24(words):
+    """uint64 words below 2^24 -> uint8 array of 3 little-endian bytes per word."""
+    words = np.ascontiguousarray(words, dtype=np.uint64)
+    b = words.reshape(-1, 1).view(np.uint8).reshape(-1, 8)[:, :3]
+    return np.ascontiguousarray(b).reshape(words.shape + (3,))
+
+
+def chi_gain_levels(bits, dim=24, scale=1.0):
+    """2^bits reconstruction levels for the norm of a `dim`-dimensional standard normal block: the medians of
+    2^bits equiprobable cells of the chi distribution (paper App. I, gain code matched to chi_24), as float16.
+    Input generator only: the levels are passed to both the library and the oracle as data."""
+    from scipy.stats import chi
+    n = 1 << bits
+    return (scale * chi.ppf((np.arange(n) + 0.5) / n, dim) / np.sqrt(dim)).astype(np.float16)
+
+
 def layer(config, ordinal, N, K, M=1, n_points=N_POINTS_M13, x_dtype=np.float16):
     """One synthetic quantised linear layer: (idx uint64 [N,KB], gain float16 [N,KB], x float32 [M,24*KB])."""
     rng = rng_for(config, ordinal)
