@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--layers", type=int, default=96, help="distinct layers in the ring (96 x 5.6 MB = 538 MB)")
+    ap.add_argument("--rows", type=int, default=4096,
+                    help="output rows N of the timed layer; 4096 is the headline workload, larger values amortise the per-launch "
+                         "fixed cost (used for the per-block instruction counts in profiles/)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set, batch 16, prefill and bulk decode (stderr)")
     ap.add_argument("--calib-copy", action="store_true",
@@ -49,7 +52,7 @@ def main():
     dev = torch.device("cuda:0")
     q = LLVQ(13, 0)
 
-    N, K, M = 4096, 4096, 1
+    N, K, M = args.rows, 4096, 1
     KB = synth.blocks_per_row(K)            # 171 blocks, K_pad = 4104
     nblk = N * KB
     # ring of distinct layers: uniform indices over the union of shells 2..13, log-normal gains
@@ -106,7 +109,7 @@ def main():
             reps += 1
         dt = (time.perf_counter() - t) / reps
         cpu = {"value": BYTES_PER_BLOCK * nblk / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "sample": "full 4096x4104 batch-1 layer (700,416 blocks), %d repetitions, single thread" % reps,
+               "sample": "full %dx4104 batch-1 layer (%d blocks), %d repetitions, single thread" % (N, nblk, reps),
                "blocks_per_s": nblk / dt}
 
     if args.extra:
@@ -123,8 +126,8 @@ def main():
         "metric": "LLVQ dequant-GEMV GB/s (packed weights)", "value": gbs, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "dequant-GEMV batch 1, W 4096x4104 (171 blocks of 24 per row), 48-bit indices uniform over "
-                               "Lambda24(13) + fp16 gain per block, x fp16, y fp32; ring of %d distinct layers" % args.layers,
+        "config": {"workload": "dequant-GEMV batch 1, W %dx4104 (171 blocks of 24 per row), 48-bit indices uniform over "
+                               "Lambda24(13) + fp16 gain per block, x fp16, y fp32; ring of %d distinct layers" % (N, args.layers),
                    "N": N, "K_pad": 24 * KB, "M": M, "blocks_per_step": nblk},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
@@ -211,6 +214,27 @@ def extra_shapes(q, synth, torch, dev):
         ob = 24 * out.element_size()
         print("bulk decode -> %-8s %d blocks: %9.2f us  %.2f G blocks/s  read+write %.1f GB/s" %
               (name, n, us, n / us / 1e3, n * (8 + ob) / us / 1e3), file=sys.stderr)
+    # encoder side of the index map on the decoded points, then the coded-word layouts (6 B and 3 B per block)
+    pts = q.llvq_decode_i8(idx)
+    back = torch.empty((n, 6), dtype=torch.uint8, device=dev)
+    us = timeit(lambda: q.llvq_encode(pts, out=back))
+    same = bool(torch.equal(back.reshape(-1), idx))
+    print("encode int8 points -> index %d blocks: %9.2f us  %.2f G blocks/s  read+write %.1f GB/s  round trip %s" %
+          (n, us, n / us / 1e3, n * 30 / us / 1e3, "exact" if same else "MISMATCH"), file=sys.stderr)
+    x = torch.from_numpy(synth.activations(r, 1, K)).to(dev).to(torch.float16)
+    y = torch.empty((1, N), dtype=torch.float32, device=dev)
+    lut = torch.from_numpy(synth.chi_gain_levels(1, scale=0.02)).to(dev)
+    w47 = torch.from_numpy(synth.pack_u48(r.integers(0, 1 << 48, size=n, dtype=np.uint64) % np.uint64(1 << 47) |
+                                          (r.integers(0, 2, size=n, dtype=np.uint64) << np.uint64(47))).reshape(-1)).to(dev)
+    us = timeit(lambda: q.llvq_matmul_coded(x, w47, N, KB, 47, gain_lut=lut, out=y))
+    print("matmul %dx%d M=1 coded 47+1 bits (6 B/block): %9.2f us  %.1f GB/s packed  %.2f G blocks/s" %
+          (N, 24 * KB, us, n * 6 / us / 1e3, n / us / 1e3), file=sys.stderr)
+    from paper_2603_11021_amd import LLVQ_IDX_U24
+    base = q.llvq_shell_offset(3)
+    w24 = torch.from_numpy(synth.pack_u24(r.integers(0, q.llvq_shell_offset(4) - base, size=n, dtype=np.uint64)).reshape(-1)).to(dev)
+    us = timeit(lambda: q.llvq_matmul_coded(x, w24, N, KB, 24, base, gain=gain, fmt=LLVQ_IDX_U24, out=y))
+    print("matmul %dx%d M=1 single shell 3, 24-bit words + fp16 gain (5 B/block): %9.2f us  %.1f GB/s packed  %.2f G blocks/s" %
+          (N, 24 * KB, us, n * 5 / us / 1e3, n / us / 1e3), file=sys.stderr)
 
 
 if __name__ == "__main__":

@@ -133,6 +133,15 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                       const void* d_gain_lut, const void* d_gain, int N, int KB,
                       float* d_y, void* stream);
 
+/* Encoder side of the index map (paper Sec. 3.2, "bijective indexing"; the inverse of the dequantiser of
+ * App. A): d_idx[k] = the index I with llvq_decode_i8(I) = d_x[k][0..23].
+ *   d_x   : [n_blocks][24] int8 coordinates of L_int (sum x^2 = 16 m), 8-byte aligned
+ *   d_idx : n_blocks indices in format `fmt` (LLVQ_IDX_U48 or LLVQ_IDX_U64), written
+ * A vector that is not a point of Lambda_24(m_max) -- mixed parity, (x - parity)/2 mod 2 not a Golay word, wrong
+ * sum modulo 8 (paper Sec. 2.3, conditions (i)-(iii)), or a norm outside shells 2..m_max -- gets the all-ones
+ * code (48 or 64 one bits), which every decoding call treats as out of range.                            */
+int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, int fmt, void* stream);
+
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                   uint64_t* h_bad, void* stream);

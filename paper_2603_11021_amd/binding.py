@@ -56,6 +56,7 @@ def _load():
     lib.llvq_decode_i8_coded.argtypes = [vp, vp, i32, i32, u64, sz, vp, vp]; lib.llvq_decode_i8_coded.restype = i32
     lib.llvq_decode_coded.argtypes = [vp, vp, i32, i32, u64, vp, vp, sz, vp, i32, vp]; lib.llvq_decode_coded.restype = i32
     lib.llvq_matmul_coded.argtypes = [vp, vp, i32, i32, vp, i32, i32, u64, vp, vp, i32, i32, vp, vp]; lib.llvq_matmul_coded.restype = i32
+    lib.llvq_encode.argtypes = [vp, vp, sz, vp, i32, vp]; lib.llvq_encode.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     _lib = lib
     return lib
@@ -210,6 +211,18 @@ class LLVQ:
         self._check(self._lib.llvq_matmul_coded(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, shape_bits, base_index,
                                                 p_lut, p_gain, N, KB, out.data_ptr(), _stream_handle(stream)),
                     "llvq_matmul_coded")
+        return out
+
+    def llvq_encode(self, pts, fmt=LLVQ_IDX_U48, out=None, stream=None):
+        """pts: int8 [n, 24] -> indices, uint8 [n, 6] (LLVQ_IDX_U48) or int64 [n] (LLVQ_IDX_U64); all ones = not a point"""
+        import torch
+        if pts.dtype != torch.int8 or pts.numel() % 24:
+            raise LLVQError("points must be int8 with 24 coordinates each")
+        n = pts.numel() // 24
+        if out is None:
+            out = (torch.empty((n, 6), dtype=torch.uint8, device=pts.device) if fmt == LLVQ_IDX_U48
+                   else torch.empty(n, dtype=torch.int64, device=pts.device))
+        self._check(self._lib.llvq_encode(self._h, pts.data_ptr(), n, out.data_ptr(), fmt, _stream_handle(stream)), "llvq_encode")
         return out
 
     def llvq_validate(self, idx, stream=None):

@@ -17,6 +17,7 @@
 
 #include "../../include/llvq.h"
 #include "llvq_decode_core.h"
+#include "llvq_encode_core.h"
 #include "llvq_tables.h"
 
 namespace {
@@ -510,6 +511,26 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
     }
 }
 
+// ---- llvq_encode --------------------------------------------------------------------------------------
+// One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
+template <int FMT>
+__global__ void __launch_bounds__(kThreads) encode_kernel(const unsigned char* __restrict__ blob, llvq::EncLayout lay,
+                                                          const uint2* __restrict__ pts, size_t n, void* __restrict__ idx) {
+    load_tables(blob, lay.bytes);
+    const llvq::EncPtrs T = llvq::make_enc_ptrs(g_lds, lay);
+    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
+        const uint2 p0 = pts[3 * k], p1 = pts[3 * k + 1], p2 = pts[3 * k + 2];
+        const uint32_t x[6] = {p0.x, p0.y, p1.x, p1.y, p2.x, p2.y};
+        const uint64_t I = llvq::encode_block(T, x);
+        if constexpr (FMT == LLVQ_IDX_U64) {
+            reinterpret_cast<uint64_t*>(idx)[k] = I;
+        } else {
+            uint16_t* o = reinterpret_cast<uint16_t*>(idx) + 3 * k;
+            o[0] = (uint16_t)I; o[1] = (uint16_t)(I >> 16); o[2] = (uint16_t)(I >> 32);
+        }
+    }
+}
+
 // ---- llvq_validate ------------------------------------------------------------------------------------
 template <int FMT>
 __global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
@@ -528,8 +549,10 @@ struct llvq_ctx {
     int m_max = 0;
     int num_cu = 0;
     llvq::TableLayout lay{};
+    llvq::EncLayout enc_lay{};
     uint64_t shell_off[16] = {};            // first index of each shell
     unsigned char* d_blob = nullptr;
+    unsigned char* d_enc_blob = nullptr;
     unsigned long long* d_counter = nullptr;
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     std::string hip_error;
@@ -624,6 +647,17 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, spw, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
+}
+
+template <int FMT>
+static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st) {
+    const size_t lds = ctx->enc_lay.bytes;
+    const int grid = grid_for(ctx, n);
+    if (int rc = set_lds(ctx, encode_kernel<FMT>, lds)) return rc;
+    hipLaunchKernelGGL(encode_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
+                       reinterpret_cast<const uint2*>(d_x), n, d_idx);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "encode launch");
 }
 
 template <int FMT>
@@ -755,6 +789,12 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     if ((e = hipMemcpy(ctx->d_blob, tabs.blob.data(), tabs.blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {
         (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
     }
+    ctx->enc_lay = tabs.enc_lay;
+    if ((e = hipMalloc(&ctx->d_enc_blob, tabs.enc_blob.size())) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_enc_blob, tabs.enc_blob.data(), tabs.enc_blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {
+        if (ctx->d_enc_blob) (void)hipFree(ctx->d_enc_blob);
+        (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
+    }
     *out = ctx;
     return LLVQ_OK;
 }
@@ -764,6 +804,7 @@ void llvq_destroy(llvq_ctx* ctx) {
     (void)hipSetDevice(ctx->device);
     if (ctx->d_blob) (void)hipFree(ctx->d_blob);
     if (ctx->d_counter) (void)hipFree(ctx->d_counter);
+    if (ctx->d_enc_blob) (void)hipFree(ctx->d_enc_blob);
     if (ctx->blas) (void)rocblas_destroy_handle(ctx->blas);
     delete ctx;
 }
@@ -816,6 +857,16 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const 
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
     return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, cd, N, KB, d_y, stream);
+}
+
+int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, int fmt, void* stream) {
+    if (!ctx || (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64)) return LLVQ_EINVAL;
+    if (n_blocks == 0) return LLVQ_OK;
+    if (!d_x) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_x, 8)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    return fmt == LLVQ_IDX_U48 ? launch_encode<LLVQ_IDX_U48>(ctx, d_x, n_blocks, d_idx, st) : launch_encode<LLVQ_IDX_U64>(ctx, d_x, n_blocks, d_idx, st);
 }
 
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,

@@ -271,6 +271,7 @@ bool build_tables(int m_max, Tables& out) {
 
     // ---- class records ---------------------------------------------------------------------------
     std::vector<ClassRec> recs(ncls);
+    std::vector<EncRec> encs(ncls);
     std::vector<uint64_t> cls_off(ncls + 1);
     for (uint32_t ci = 0; ci < ncls; ci++) {
         const Leader& L = cls[ci];
@@ -354,6 +355,53 @@ bool build_tables(int m_max, Tables& out) {
         R.vt8_lo = (uint32_t)v8; R.vt8_hi = (uint32_t)(v8 >> 32);
         R.vti_lo = (uint32_t)vi; R.vti_hi = (uint32_t)(vi >> 32);
         recs[ci] = R;
+
+        // the same class seen from the encoder: key of the leader, code of each absolute value, ranking radices
+        EncRec E{};
+        E.offset = L.offset;
+        uint64_t p1 = 0, p4 = 0;
+        for (size_t i = 0; i < L.val.size(); i++) {
+            uint64_t v = (uint64_t)L.val[i];
+            p1 += v * L.cnt[i];
+            p4 += v * v * v * v * L.cnt[i];
+        }
+        if (p4 >= (1u << 20) || p1 >= (1u << 9)) return false;
+        E.key = (uint32_t)p4 | (uint32_t)p1 << 20 | (uint32_t)(L.odd ? 1 : 0) << 29;
+        E.f0 = R.f0;
+        uint8_t ctab[8];
+        for (int k = 0; k < 8; k++) ctab[k] = 0xFF;
+        auto set_code = [&](int value, int code) { ctab[value >> 1] = (uint8_t)code; };
+        if (outer_all) {
+            set_code(outside, 0);
+            for (size_t i = 0; i < mv.size(); i++) set_code(mv[i], 4 + (int)i);
+        } else {
+            set_code(0, 0);
+            for (size_t i = 0; i < mv.size(); i++) set_code(mv[i], 1 + (int)i);
+            for (size_t i = 0; i < dv.size(); i++) set_code(dv[i], 4 + (int)i);
+        }
+        std::memcpy(&E.ctab_lo, ctab, 4);
+        std::memcpy(&E.ctab_hi, ctab + 4, 4);
+        E.Pin = (uint32_t)Pin;
+        E.P1 = (uint16_t)P1;
+        E.sp = si.sp;
+        auto radices = [&](const std::vector<int>& cnt, uint16_t rad[2]) -> int {
+            int slots = 0;
+            for (int c : cnt) slots += c;
+            rad[0] = rad[1] = 1;
+            for (size_t i = 0; i + 1 < cnt.size(); i++) {
+                if (i < 2) rad[i] = (uint16_t)g_binom[slots][cnt[i]];
+                slots -= cnt[i];
+            }
+            return cnt.empty() ? 0 : (int)cnt.size() - 1;
+        };
+        const int dig0 = radices(mc, E.rad0);
+        int dig1 = 0;
+        E.rad1[0] = E.rad1[1] = 1;
+        if (f1direct) dig1 = radices(dc, E.rad1);
+        if (dig0 > 3 || dig1 > 3) return false;
+        E.e1 = (uint32_t)goff << E1_GOFF | (uint32_t)acode << E1_ACODE | (uint32_t)dig0 << E1_DIG0 |
+               (uint32_t)dig1 << E1_DIG1 | (uint32_t)sym_base0 << E1_SYM0;
+        encs[ci] = E;
     }
     cls_off[ncls] = running;
 
@@ -413,6 +461,79 @@ bool build_tables(int m_max, Tables& out) {
     for (int m = 0; m < 16; m++) lay.rnorm[m] = rnorm[m];
     out.lay = lay;
     out.blob.swap(blob);
+
+    // ---- encoder blob ------------------------------------------------------------------------------
+    // ginv: any 12 cyclically consecutive coordinates of a cyclic code are an information set, so the low 12
+    // bits of a word identify it
+    std::vector<uint16_t> ginv(4096, 0xFFFF);
+    for (uint32_t k = 0; k < 4096; k++) {
+        if (ginv[gs[k] & 0xFFFu] != 0xFFFF) return false;
+        ginv[gs[k] & 0xFFFu] = (uint16_t)k;
+    }
+    std::vector<uint16_t> rank12(4096);
+    for (int pc = 0; pc <= 12; pc++) {
+        uint16_t rk = 0;
+        for (uint32_t mk : masks_in_colex_order(12, pc)) rank12[mk] = rk++;
+    }
+    std::vector<uint8_t> pext6(4096);
+    for (uint32_t F = 0; F < 64; F++)
+        for (uint32_t src = 0; src < 64; src++) {
+            uint32_t o = 0;
+            for (int pos = 0, k = 0; pos < 6; pos++)
+                if ((F >> pos) & 1u) { if ((src >> pos) & 1u) o |= 1u << k; k++; }
+            pext6[F << 6 | (src ^ F)] = (uint8_t)o;            // swizzled like the deposit tables
+        }
+    // g16[H][p]: number of 16-bit masks of popcount p whose bits 12..15, read as a number, are below H
+    std::vector<uint16_t> g16(16 * 17, 0);
+    for (uint32_t H = 0; H < 16; H++)
+        for (int pc = 0; pc <= 16; pc++) {
+            uint64_t c = 0;
+            for (uint32_t h = 0; h < H; h++) {
+                int rest = pc - popcnt(h);
+                if (rest >= 0 && rest <= 12) c += g_binom[12][rest];
+            }
+            if (c > 0xFFFF) return false;
+            g16[H * 17 + pc] = (uint16_t)c;
+        }
+    // cuckoo hash of the class keys: every key sits in one of its two candidate slots
+    const uint32_t hslots = 1u << kEncHashBits;
+    std::vector<HashEnt> htab;
+    uint32_t mult[2] = {0, 0};
+    for (uint32_t attempt = 0; attempt < 64 && !mult[0]; attempt++) {
+        const uint32_t m0 = 0x9E3779B1u + 2u * attempt * 0x632BE5ABu, m1 = 0x85EBCA77u + 2u * attempt * 0xC2B2AE3Du;
+        htab.assign(2 * hslots, HashEnt{0xFFFFFFFFu, 0});
+        bool ok = true;
+        for (uint32_t ci = 0; ci < ncls && ok; ci++) {
+            HashEnt cur{encs[ci].key, ci};
+            int half = 0;
+            ok = false;
+            for (int kick = 0; kick < 200; kick++) {
+                const uint32_t slot = half * hslots + ((cur.key * (half ? m1 : m0)) >> (32 - kEncHashBits));
+                std::swap(cur, htab[slot]);
+                if (cur.key == 0xFFFFFFFFu) { ok = true; break; }
+                half ^= 1;
+            }
+        }
+        if (ok) { mult[0] = m0; mult[1] = m1; }
+    }
+    if (!mult[0]) return false;
+    if (split.size() * sizeof(SplitEnt) > kEncCls - kEncSplit || encs.size() * sizeof(EncRec) > kEncBlob - kEncCls) return false;
+    std::vector<unsigned char> eb(kEncBlob, 0);
+    auto eput = [&](uint32_t off, const void* src, size_t bytes) { std::memcpy(eb.data() + off, src, bytes); };
+    eput(kEncGs, gs.data(), gs.size() * 4);
+    eput(kEncGinv, ginv.data(), ginv.size() * 2);
+    eput(kEncRank12, rank12.data(), rank12.size() * 2);
+    eput(kEncPext6, pext6.data(), pext6.size());
+    eput(kEncHash, htab.data(), htab.size() * sizeof(HashEnt));
+    eput(kEncG16, g16.data(), g16.size() * 2);
+    eput(kEncSplit, split.data(), split.size() * sizeof(SplitEnt));
+    eput(kEncCls, encs.data(), encs.size() * sizeof(EncRec));
+    out.enc_lay.bytes = kEncBlob;
+    out.enc_lay.ncls = ncls;
+    out.enc_lay.hash_mult[0] = mult[0];
+    out.enc_lay.hash_mult[1] = mult[1];
+    out.enc_lay.m_max = (uint32_t)m_max;
+    out.enc_blob.swap(eb);
     return true;
 }
 

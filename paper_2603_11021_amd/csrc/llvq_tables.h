@@ -81,6 +81,51 @@ struct TableLayout {
     float    rnorm[16];      // 1/sqrt(16 m)
 };
 
+// ---- tables of the encoder-side index map (point -> index), a blob of their own ---------------------
+// One record per class, in class order.  The point's class is found by hashing the key below; the code of each
+// coordinate (the same nibble codes the decoder produces) comes from an 8-entry table indexed by |x| >> 1.
+struct alignas(16) EncRec {
+    uint64_t offset;            // index of the first point of the class
+    uint32_t key;               // sum |x|^4  |  (sum |x|) << 20  |  parity << 29: identifies the leader
+    uint32_t f0;                // the bit fields of ClassRec::f0
+    uint32_t ctab_lo, ctab_hi;  // nibble code of the absolute value 2k (even classes) or 2k+1 (odd), k = 0..7
+    uint32_t Pin;               // arrangements of the inner word of the outer domain
+    uint32_t e1;                // bit fields, see E1_* below
+    uint16_t P1;                // arrangements of the direct F1 word
+    uint16_t sp;                // split entry of j is split[sp + j]
+    uint16_t rad0[2];           // radices of the first two digits of the outer domain's inner word
+    uint16_t rad1[2];           // the same for the direct F1 word
+    uint32_t pad;
+};
+static_assert(sizeof(EncRec) == 48, "EncRec layout");
+// e1: [0..11] first Golay word of the class in gs  [12..13] code of A  [14..15] digits of the outer inner word
+//     [16..17] digits of the direct F1 word  [18] first symbol of the outer inner word (0 or 1)
+enum { E1_GOFF = 0, E1_ACODE = 12, E1_DIG0 = 14, E1_DIG1 = 16, E1_SYM0 = 18 };
+
+constexpr uint32_t kEncGs     = 0;        // 4096 x u32, the decoder's sorted Golay words
+constexpr uint32_t kEncGinv   = 16384;    // 4096 x u16: low 12 bits of a word -> its position in gs
+constexpr uint32_t kEncRank12 = 24576;    // 4096 x u16: colex rank of a 12-bit mask among the masks of its popcount
+constexpr uint32_t kEncPext6  = 32768;    // 4096 x u8: extraction of the bits of a 6-bit source under a 6-bit mask
+constexpr uint32_t kEncHash   = 36864;    // 2 x 512 x HashEnt: cuckoo table of the class keys
+constexpr uint32_t kEncG16    = 45056;    // 16 x 17 x u16: masks of popcount p whose bits 12..15 are below H
+constexpr uint32_t kEncSplit  = 46080;    // the decoder's SplitEnt array
+constexpr uint32_t kEncCls    = 51712;    // ncls x EncRec
+constexpr uint32_t kEncBlob   = 70144;    // 68.5 KB
+constexpr uint32_t kEncHashBits = 9;      // slots per half of the cuckoo table
+
+// a key sits in slot (key * mult[h]) >> (32 - kEncHashBits) of half h, for h = 0 or h = 1
+struct HashEnt {
+    uint32_t key;     // 0xFFFFFFFF: empty
+    uint32_t cid;
+};
+
+struct EncLayout {
+    uint32_t bytes;          // bytes of the encoder blob = bytes resident in LDS
+    uint32_t ncls;
+    uint32_t hash_mult[2];   // multipliers of the two halves of the cuckoo table
+    uint32_t m_max;
+};
+
 // nibble slot (0..7) of chunk position 0..5 inside a spread6 entry
 static constexpr int kNibbleSlot[6] = {0, 2, 1, 3, 4, 6};
 
@@ -88,6 +133,8 @@ struct Tables {
     TableLayout lay;
     uint64_t shell_off[16];  // index of the first point of shell m (N(m-1)); entries above m_max hold N(m_max)
     std::vector<unsigned char> blob;
+    EncLayout enc_lay;
+    std::vector<unsigned char> enc_blob;
 };
 
 // Builds every table for Lambda_24(m_max), 2 <= m_max <= 13.  Returns false on an internal inconsistency.

@@ -5,6 +5,7 @@
 #include <cstring>
 
 #include "../../paper_2603_11021_amd/csrc/llvq_decode_core.h"
+#include "../../paper_2603_11021_amd/csrc/llvq_encode_core.h"
 #include "../../paper_2603_11021_amd/csrc/llvq_tables.h"
 
 static llvq::Tables g_tabs;
@@ -32,6 +33,21 @@ uint64_t emul_decode_i8(const uint64_t* idx, uint64_t n, int8_t* out) {
         const llvq::BlockInfo bi = llvq::decode_block(T, idx[k], w);
         llvq::nibbles_to_i8(w, bi.vti_lo, bi.vti_hi, o);
         std::memcpy(out + 24 * k, o, 24);
+    }
+    return bad;
+}
+
+uint32_t emul_enc_bytes() { return g_tabs.enc_lay.bytes; }
+
+// pts: n x 24 int8; idx receives the index or all ones; returns the number of vectors that are not points
+uint64_t emul_encode(const int8_t* pts, uint64_t n, uint64_t* idx) {
+    const llvq::EncPtrs T = llvq::make_enc_ptrs(g_tabs.enc_blob.data(), g_tabs.enc_lay);
+    uint64_t bad = 0;
+    for (uint64_t k = 0; k < n; k++) {
+        uint32_t x[6];
+        std::memcpy(x, pts + 24 * k, 24);
+        idx[k] = llvq::encode_block(T, x);
+        bad += idx[k] == llvq::kInvalidIndex;
     }
     return bad;
 }

@@ -15,7 +15,10 @@ EMUL = os.path.join(ROOT, "tests", "host_emul", "libemul.so")
 
 @pytest.fixture(scope="module")
 def emul():
-    if not os.path.exists(EMUL):
+    srcs = [os.path.join(ROOT, "tests", "host_emul", "emul.cpp")] + [
+        os.path.join(ROOT, "paper_2603_11021_amd", "csrc", f)
+        for f in ("llvq_tables.cpp", "llvq_tables.h", "llvq_decode_core.h", "llvq_encode_core.h")]
+    if not os.path.exists(EMUL) or os.path.getmtime(EMUL) < max(os.path.getmtime(f) for f in srcs):
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", EMUL,
                                os.path.join(ROOT, "tests", "host_emul", "emul.cpp"),
                                os.path.join(ROOT, "paper_2603_11021_amd", "csrc", "llvq_tables.cpp")])
@@ -23,7 +26,15 @@ def emul():
     lib.emul_num_points.restype = ctypes.c_uint64
     lib.emul_decode_i8.restype = ctypes.c_uint64
     lib.emul_decode_i8.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+    lib.emul_encode.restype = ctypes.c_uint64
+    lib.emul_encode.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
     assert lib.emul_init(13) == 0
+
+    def encode(pts):
+        pts = np.ascontiguousarray(pts, dtype=np.int8)
+        out = np.empty(pts.shape[0], dtype=np.uint64)
+        bad = lib.emul_encode(pts.ctypes.data, pts.shape[0], out.ctypes.data)
+        return out, int(bad)
 
     def decode(idx):
         idx = np.ascontiguousarray(idx, dtype=np.uint64)
@@ -32,6 +43,7 @@ def emul():
         return out, int(bad)
 
     decode.lib = lib
+    decode.encode = encode
     return decode
 
 
@@ -101,6 +113,43 @@ def test_host_decode_matches_oracle_on_random_union(emul, oracle13):
 def test_host_decode_out_of_range(emul, oracle13):
     got, bad = emul(np.array([oracle13.num_points, 2 ** 48 - 1, 5], dtype=np.uint64))
     assert bad == 2 and not got[:2].any() and got[2].any()
+
+
+def test_host_encode_inverts_decode_on_every_class(emul, oracle13):
+    rng = np.random.default_rng(23)
+    picks = []
+    for c in oracle13.classes():
+        picks += [c["offset"], c["offset"] + c["size"] - 1]
+        picks += [c["offset"] + int(v) for v in rng.integers(0, c["size"], 100)]
+    I = np.array(picks, dtype=np.uint64)
+    pts, _ = oracle13.decode(I)
+    got, bad = emul.encode(pts)
+    assert bad == 0 and np.array_equal(got, I)
+
+
+def test_host_encode_matches_oracle_on_random_union_and_shell2(emul, oracle13):
+    I = np.concatenate([np.random.default_rng(24).integers(0, oracle13.num_points, 200000, dtype=np.uint64),
+                        np.arange(196560, dtype=np.uint64)])
+    pts, _ = oracle13.decode(I)
+    got, bad = emul.encode(pts)
+    want, wbad = oracle13.encode(pts)
+    assert bad == wbad == 0 and np.array_equal(got, want) and np.array_equal(got, I)
+
+
+def test_host_encode_rejects_what_the_oracle_rejects(emul, oracle13):
+    from point_cases import spoiled_points
+    rng = np.random.default_rng(25)
+    pts, _ = oracle13.decode(rng.integers(0, oracle13.num_points, 20000, dtype=np.uint64))
+    bad_pts = spoiled_points(pts, rng)
+    want, wbad = oracle13.encode(bad_pts)
+    got, bad = emul.encode(bad_pts)
+    assert 0.8 * bad_pts.shape[0] < wbad < bad_pts.shape[0]               # some spoiled vectors are points again
+    assert bad == wbad and np.array_equal(got, want)                        # the oracle marks a non-point with all ones
+
+
+def test_encoder_tables_fit_in_lds(emul):
+    emul.lib.emul_enc_bytes.restype = ctypes.c_uint32
+    assert emul.lib.emul_enc_bytes() <= 80 * 1024
 
 
 def test_synth_pack_u48():
