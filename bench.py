@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
 ALU_PEAK_TLOPS = 39.3          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one vector instruction per lane and cycle
-VALU_PER_BLOCK = 454           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
-TRAFFIC_BYTES_PER_LAUNCH = 11881249  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
+VALU_PER_BLOCK = 439           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
+TRAFFIC_BYTES_PER_LAUNCH = 11968274  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
 
 
 def main():
@@ -37,6 +37,9 @@ def main():
                          "fixed cost (used for the per-block instruction counts in profiles/)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set, batch 16, prefill and bulk decode (stderr)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also run the batch-1 product over a range of sizes, 320 launches each (stderr); under "
+                         "rocprofv3 --kernel-trace the dispatches appear in this order")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy, so that a rocprofv3 --pmc run has a kernel of known HBM traffic")
     args = ap.parse_args()
@@ -115,6 +118,8 @@ def main():
     if args.extra:
         extra_layer_set(q, synth, torch, dev)
         extra_shapes(q, synth, torch, dev)
+    if args.sweep:
+        extra_sweep(q, synth, torch, dev)
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
@@ -174,6 +179,33 @@ def extra_layer_set(q, synth, torch, dev):
     ms = e0.elapsed_time(e1) / reps
     print("llama3-8b layer set x4 (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed" % (tot * 8 / 1e6, ms, tot * 8 / ms / 1e6),
           file=sys.stderr)
+
+
+SWEEP_SHAPES = ((1, 1), (256, 1), (256, 64), (256, 171), (512, 171), (1024, 171), (2048, 171), (4096, 171), (8192, 171),
+                (4096, 342), (4096, 683))
+
+
+def extra_sweep(q, synth, torch, dev):
+    """Batch-1 product on N x 24*KB layers from one block to 2.8 M blocks, same buffers every launch (hot cache): shows
+    the fixed cost of a launch and the slope per block.  HIP-event times of launches this short include the host's
+    launch rate; kernel durations come from a kernel trace of the same run."""
+    import numpy as np
+    rng = synth.rng_for(7, 1)
+    for (N, KB) in SWEEP_SHAPES:
+        idx = torch.from_numpy(synth.pack_u48(synth.indices(rng, (N, KB))).reshape(-1)).to(dev)
+        gain = torch.from_numpy(synth.gains(rng, (N, KB)).reshape(-1)).to(dev)
+        x = torch.from_numpy(synth.activations(rng, 1, 24 * KB).astype(np.float16)).to(dev)
+        y = torch.empty((1, N), dtype=torch.float32, device=dev)
+        for _ in range(20):
+            q.llvq_matmul(x, idx, gain, N, KB, out=y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(300):
+            q.llvq_matmul(x, idx, gain, N, KB, out=y)
+        e1.record()
+        torch.cuda.synchronize()
+        print("sweep N=%5d KB=%4d (%8d blocks): %7.2f us per launch" % (N, KB, N * KB, e0.elapsed_time(e1) / 300 * 1e3), file=sys.stderr)
 
 
 def extra_shapes(q, synth, torch, dev):
