@@ -70,6 +70,7 @@ class Oracle:
         lib.oracle_encode_batch.argtypes = [p, u64, p]; lib.oracle_encode_batch.restype = u64
         lib.oracle_dequant_batch.argtypes = [p, p, u64, p]; lib.oracle_dequant_batch.restype = u64
         lib.oracle_matmul.argtypes = [p, p, i32, i32, p, i32, p]; lib.oracle_matmul.restype = None
+        lib.oracle_nearest_batch.argtypes = [p, u64, i32, p, p]; lib.oracle_nearest_batch.restype = None
         self.lib = lib
         self.m_max = m_max
         n = lib.oracle_init(m_max)
@@ -124,6 +125,17 @@ class Oracle:
     def is_member(self, x):
         x = np.ascontiguousarray(x, dtype=np.int32)
         return bool(self.lib.oracle_is_member(x.ctypes.data))
+
+    # -- nearest point of the ball cut ---------------------------------------------------
+    def nearest(self, w, metric="angular"):
+        """w: [n, 24] floats -> (int8 [n, 24] nearest points, float64 [n] scores).
+        angular: score <w, x>/||x||; euclidean: score <w, x> - ||x||^2 / 2."""
+        w = np.ascontiguousarray(w, dtype=np.float64).reshape(-1, 24)
+        out = np.empty((w.shape[0], 24), dtype=np.int8)
+        score = np.empty(w.shape[0], dtype=np.float64)
+        self.lib.oracle_nearest_batch(w.ctypes.data, w.shape[0], {"angular": 0, "euclidean": 1}[metric],
+                                      out.ctypes.data, score.ctypes.data)
+        return out, score
 
     # -- shape-gain and matrix product --------------------------------------------------
     def dequant(self, idx, gain_f16):
