@@ -52,6 +52,12 @@ enum {
                             1 bit/weight layout of a single small shell (paper App. C, "single shell")      */
 };
 
+/* metrics of llvq_quantize */
+enum {
+    LLVQ_ANGULAR = 0,    /* maximise <w, x> / ||x||  (shape-gain: the code is the set of directions)             */
+    LLVQ_EUCLIDEAN = 1   /* minimise ||w - x||^2     (spherical shaping: the code is the ball cut itself)        */
+};
+
 /* element types */
 enum {
     LLVQ_F16 = 0,
@@ -141,6 +147,20 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
  * sum modulo 8 (paper Sec. 2.3, conditions (i)-(iii)), or a norm outside shells 2..m_max -- gets the all-ones
  * code (48 or 64 one bits), which every decoding call treats as out of range.                            */
 int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, int fmt, void* stream);
+
+/* Quantiser (paper Sec. 3 and 3.1: search over leaders, Golay placements and parity-constrained signs, extended
+ * to the union of shells with angular or Euclidean scoring): for every block of 24 reals the point x of
+ * Lambda_24(m_max) that maximises <w, x> / ||x|| (LLVQ_ANGULAR) or minimises ||w - x|| (LLVQ_EUCLIDEAN), both in
+ * the coordinates of L_int (||x||^2 = 16 m; scale w accordingly for the Euclidean metric).
+ *   d_w      : [n_blocks][24] fp32, finite
+ *   d_points : [n_blocks][24] int8, written: the chosen points (8-byte aligned)
+ *   d_idx    : n_blocks indices in format `fmt`, written through llvq_encode; NULL: not wanted
+ *   d_score  : n_blocks fp32, written: <w, x> / ||x|| (angular; this is also the least-squares gain of the block,
+ *              paper App. E "optimal scales") or <w, x> - ||x||^2 / 2 (Euclidean); NULL: not wanted
+ * Scores are accumulated in fp32: among candidates whose scores differ by less than rounding (about 2e-6
+ * relative) either may be returned; the returned point is always a point of the ball cut.                  */
+int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, int8_t* d_points,
+                  void* d_idx, int fmt, float* d_score, void* stream);
 
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,

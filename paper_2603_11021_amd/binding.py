@@ -9,6 +9,7 @@ _LIB = os.path.join(_HERE, "libllvq.so")
 
 LLVQ_IDX_U48, LLVQ_IDX_U64, LLVQ_IDX_U24 = 0, 1, 2
 LLVQ_F16, LLVQ_BF16, LLVQ_F32 = 0, 1, 2
+LLVQ_ANGULAR, LLVQ_EUCLIDEAN = 0, 1
 
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-std=c++17", "-fPIC", "-shared"]
@@ -57,6 +58,7 @@ def _load():
     lib.llvq_decode_coded.argtypes = [vp, vp, i32, i32, u64, vp, vp, sz, vp, i32, vp]; lib.llvq_decode_coded.restype = i32
     lib.llvq_matmul_coded.argtypes = [vp, vp, i32, i32, vp, i32, i32, u64, vp, vp, i32, i32, vp, vp]; lib.llvq_matmul_coded.restype = i32
     lib.llvq_encode.argtypes = [vp, vp, sz, vp, i32, vp]; lib.llvq_encode.restype = i32
+    lib.llvq_quantize.argtypes = [vp, vp, sz, i32, vp, vp, i32, vp, vp]; lib.llvq_quantize.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     _lib = lib
     return lib
@@ -224,6 +226,23 @@ class LLVQ:
                    else torch.empty(n, dtype=torch.int64, device=pts.device))
         self._check(self._lib.llvq_encode(self._h, pts.data_ptr(), n, out.data_ptr(), fmt, _stream_handle(stream)), "llvq_encode")
         return out
+
+    def llvq_quantize(self, w, metric=LLVQ_ANGULAR, fmt=LLVQ_IDX_U48, want_idx=True, stream=None):
+        """w: float32 [n, 24] -> (points int8 [n, 24], indices or None, scores float32 [n])"""
+        import torch
+        if w.dtype != torch.float32 or w.numel() % 24:
+            raise LLVQError("blocks must be float32 with 24 coordinates each")
+        n = w.numel() // 24
+        pts = torch.empty((n, 24), dtype=torch.int8, device=w.device)
+        score = torch.empty(n, dtype=torch.float32, device=w.device)
+        idx = None
+        if want_idx:
+            idx = (torch.empty((n, 6), dtype=torch.uint8, device=w.device) if fmt == LLVQ_IDX_U48
+                   else torch.empty(n, dtype=torch.int64, device=w.device))
+        self._check(self._lib.llvq_quantize(self._h, w.data_ptr(), n, metric, pts.data_ptr(),
+                                            idx.data_ptr() if idx is not None else None, fmt, score.data_ptr(),
+                                            _stream_handle(stream)), "llvq_quantize")
+        return pts, idx, score
 
     def llvq_validate(self, idx, stream=None):
         fmt, n = self._idx_fmt(idx)

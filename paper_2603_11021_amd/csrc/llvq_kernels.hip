@@ -531,6 +531,12 @@ __global__ void __launch_bounds__(kThreads) encode_kernel(const unsigned char* _
     }
 }
 
+}  // namespace
+
+#include "llvq_search_kernel.h"
+
+namespace {
+
 // ---- llvq_validate ------------------------------------------------------------------------------------
 template <int FMT>
 __global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
@@ -553,6 +559,9 @@ struct llvq_ctx {
     uint64_t shell_off[16] = {};            // first index of each shell
     unsigned char* d_blob = nullptr;
     unsigned char* d_enc_blob = nullptr;
+    llvq::SearchLayout search_lay{};
+    llvq::SearchRec* d_search = nullptr;    // nearest-point search records
+    uint32_t* d_words = nullptr;            // the 4096 Golay words in (weight, message) order
     unsigned long long* d_counter = nullptr;
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     std::string hip_error;
@@ -795,6 +804,14 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
         if (ctx->d_enc_blob) (void)hipFree(ctx->d_enc_blob);
         (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
     }
+    ctx->search_lay = tabs.search_lay;
+    const size_t sbytes = tabs.search_recs.size() * sizeof(llvq::SearchRec), wbytes = tabs.golay_sorted.size() * sizeof(uint32_t);
+    if ((e = hipMalloc(&ctx->d_search, sbytes)) != hipSuccess || (e = hipMalloc(&ctx->d_words, wbytes)) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_search, tabs.search_recs.data(), sbytes, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_words, tabs.golay_sorted.data(), wbytes, hipMemcpyHostToDevice)) != hipSuccess) {
+        llvq_destroy(ctx);
+        return LLVQ_EHIP;
+    }
     *out = ctx;
     return LLVQ_OK;
 }
@@ -805,6 +822,8 @@ void llvq_destroy(llvq_ctx* ctx) {
     if (ctx->d_blob) (void)hipFree(ctx->d_blob);
     if (ctx->d_counter) (void)hipFree(ctx->d_counter);
     if (ctx->d_enc_blob) (void)hipFree(ctx->d_enc_blob);
+    if (ctx->d_search) (void)hipFree(ctx->d_search);
+    if (ctx->d_words) (void)hipFree(ctx->d_words);
     if (ctx->blas) (void)rocblas_destroy_handle(ctx->blas);
     delete ctx;
 }
@@ -867,6 +886,23 @@ int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, 
     if (!aligned(d_x, 8)) return LLVQ_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     return fmt == LLVQ_IDX_U48 ? launch_encode<LLVQ_IDX_U48>(ctx, d_x, n_blocks, d_idx, st) : launch_encode<LLVQ_IDX_U64>(ctx, d_x, n_blocks, d_idx, st);
+}
+
+int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, int8_t* d_points, void* d_idx, int fmt,
+                  float* d_score, void* stream) {
+    if (!ctx || (metric != LLVQ_ANGULAR && metric != LLVQ_EUCLIDEAN)) return LLVQ_EINVAL;
+    if (d_idx && fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
+    if (n_blocks == 0) return LLVQ_OK;
+    if (!d_w || !d_points) return LLVQ_EINVAL;
+    if (!aligned(d_w, 4) || !aligned(d_points, 8) || !aligned(d_score, 4)) return LLVQ_EALIGN;
+    if (d_idx) { if (int rc = check_idx(d_idx, fmt)) return rc; }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const int grid = (int)std::min<size_t>(n_blocks, (size_t)ctx->num_cu);
+    hipLaunchKernelGGL(search_kernel, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay, ctx->d_words, d_w,
+                       n_blocks, metric, d_points, d_score);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(ctx, e, "search launch");
+    return d_idx ? llvq_encode(ctx, d_points, n_blocks, d_idx, fmt, stream) : LLVQ_OK;
 }
 
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,

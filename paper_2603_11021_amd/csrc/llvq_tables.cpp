@@ -534,6 +534,45 @@ bool build_tables(int m_max, Tables& out) {
     out.enc_lay.hash_mult[1] = mult[1];
     out.enc_lay.m_max = (uint32_t)m_max;
     out.enc_blob.swap(eb);
+
+    // ---- nearest-point search records ------------------------------------------------------------------
+    out.search_recs.clear();
+    SearchLayout sl{};
+    auto make_rec = [&](uint32_t ci) {
+        const Leader& L = cls[ci];
+        SearchRec S{};
+        std::vector<float> co;
+        if (L.odd) {
+            for (size_t i = 0; i < L.val.size(); i++)
+                for (int k = 0; k < L.cnt[i]; k++) co.push_back(L.val[i] % 4 == 1 ? (float)L.val[i] : -(float)L.val[i]);
+            std::sort(co.begin(), co.end(), [](float a, float b) { return a > b; });
+        } else {
+            for (int pass = 0; pass < 2; pass++)
+                for (size_t i = 0; i < L.val.size(); i++)
+                    if ((L.val[i] % 4 == 2) == (pass == 0))
+                        for (int k = 0; k < L.cnt[i]; k++) co.push_back((float)L.val[i]);
+            if (L.w > 0) S.amin2 = 2.0f * co[L.w - 1];
+        }
+        for (int k = 0; k < 24; k++) S.coef[k] = co[k];
+        S.rnorm = (float)(1.0 / std::sqrt(16.0 * L.m));
+        S.half_n2 = 8.0f * (float)L.m;
+        S.kappa = (encs[ci].f0 >> F0_KAPPA) & 1u;
+        S.cid = ci;
+        S.w = L.odd ? 0u : (uint32_t)L.w;
+        out.search_recs.push_back(S);
+    };
+    for (uint32_t ci = 0; ci < ncls; ci++) if (cls[ci].odd) make_rec(ci);
+    sl.n_odd = (uint32_t)out.search_recs.size();
+    const int weights[5] = {0, 8, 12, 16, 24};
+    for (int g = 0; g < 5; g++) {
+        sl.even_first[g] = (uint32_t)out.search_recs.size();
+        for (uint32_t ci = 0; ci < ncls; ci++) if (!cls[ci].odd && cls[ci].w == weights[g]) make_rec(ci);
+        sl.even_count[g] = (uint32_t)out.search_recs.size() - sl.even_first[g];
+    }
+    sl.total = (uint32_t)out.search_recs.size();
+    if (sl.total != ncls) return false;
+    out.search_lay = sl;
+    out.golay_sorted = gs;
     return true;
 }
 

@@ -126,6 +126,30 @@ struct EncLayout {
     uint32_t m_max;
 };
 
+// ---- tables of the nearest-point search: one record per class, read with wave-uniform (scalar) loads ----
+// coef: the 24 coefficients the sorted input is multiplied with.  Odd class: +a for a = 1 (mod 4), -a for
+// a = 3 (mod 4), in descending order.  Even class: the 2-mod-4 values in descending order (w of them), then the
+// 0-mod-4 values in descending order.
+struct alignas(128) SearchRec {
+    float    coef[24];
+    float    rnorm;      // 1 / sqrt(16 m)
+    float    half_n2;    // ||x||^2 / 2 = 8 m
+    float    amin2;      // twice the smallest 2-mod-4 value (0 when there is none): cost factor of the parity repair
+    uint32_t kappa;      // parity that the number of negative F1 signs must have
+    uint32_t cid;        // class id
+    uint32_t w;          // Golay weight of the class (odd classes: 0)
+    uint32_t pad[2];
+};
+static_assert(sizeof(SearchRec) == 128, "SearchRec layout");
+
+// records are ordered: all odd classes, then the even classes grouped by weight 0, 8, 12, 16, 24
+struct SearchLayout {
+    uint32_t n_odd;
+    uint32_t even_first[5];
+    uint32_t even_count[5];
+    uint32_t total;
+};
+
 // nibble slot (0..7) of chunk position 0..5 inside a spread6 entry
 static constexpr int kNibbleSlot[6] = {0, 2, 1, 3, 4, 6};
 
@@ -135,6 +159,9 @@ struct Tables {
     std::vector<unsigned char> blob;
     EncLayout enc_lay;
     std::vector<unsigned char> enc_blob;
+    SearchLayout search_lay;
+    std::vector<SearchRec> search_recs;
+    std::vector<uint32_t> golay_sorted;   // the 4096 words in (weight, message) order
 };
 
 // Builds every table for Lambda_24(m_max), 2 <= m_max <= 13.  Returns false on an internal inconsistency.
