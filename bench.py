@@ -253,6 +253,16 @@ def extra_shapes(q, synth, torch, dev):
     same = bool(torch.equal(back.reshape(-1), idx))
     print("encode int8 points -> index %d blocks: %9.2f us  %.2f G blocks/s  read+write %.1f GB/s  round trip %s" %
           (n, us, n / us / 1e3, n * 30 / us / 1e3, "exact" if same else "MISMATCH"), file=sys.stderr)
+    # quantiser: nearest direction of Lambda_24(13) for Gaussian blocks (one 4096 x 384 slice of a layer)
+    from paper_2603_11021_amd import LLVQ_ANGULAR
+    nq = 4096 * 16
+    wq = torch.from_numpy(r.standard_normal((nq, 24)).astype(np.float32)).to(dev)
+    res = []
+    us = timeit(lambda: res.append(q.llvq_quantize(wq, LLVQ_ANGULAR)) or res.clear(), reps=3)
+    qp, qi, qs = q.llvq_quantize(wq, LLVQ_ANGULAR)
+    cosm = float((qs / wq.norm(dim=1)).mean())
+    print("quantize (angular search + encode) %d blocks: %9.1f us  %.3f M blocks/s  mean cosine %.4f" %
+          (nq, us, nq / us, cosm), file=sys.stderr)
     x = torch.from_numpy(synth.activations(r, 1, K)).to(dev).to(torch.float16)
     y = torch.empty((1, N), dtype=torch.float32, device=dev)
     lut = torch.from_numpy(synth.chi_gain_levels(1, scale=0.02)).to(dev)

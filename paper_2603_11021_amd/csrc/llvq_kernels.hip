@@ -898,8 +898,12 @@ int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, 
     if (d_idx) { if (int rc = check_idx(d_idx, fmt)) return rc; }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const int grid = (int)std::min<size_t>(n_blocks, (size_t)ctx->num_cu);
-    hipLaunchKernelGGL(search_kernel, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay, ctx->d_words, d_w,
-                       n_blocks, metric, d_points, d_score);
+    if (metric == LLVQ_ANGULAR)
+        hipLaunchKernelGGL(search_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
+                           ctx->d_words, d_w, n_blocks, d_points, d_score);
+    else
+        hipLaunchKernelGGL(search_kernel<LLVQ_EUCLIDEAN>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
+                           ctx->d_words, d_w, n_blocks, d_points, d_score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "search launch");
     return d_idx ? llvq_encode(ctx, d_points, n_blocks, d_idx, fmt, stream) : LLVQ_OK;

@@ -46,9 +46,10 @@ __device__ __forceinline__ ScoredId better(ScoredId a, ScoredId b) {
 
 constexpr int kSearchThreads = 1024;
 
+template <int METRIC>
 __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
                                                                  const uint32_t* __restrict__ words, const float* __restrict__ w_in,
-                                                                 size_t n, int metric, int8_t* __restrict__ pts,
+                                                                 size_t n, int8_t* __restrict__ pts,
                                                                  float* __restrict__ score_out) {
     __shared__ float s_score[kSearchThreads / 64];
     __shared__ uint32_t s_id[kSearchThreads / 64];
@@ -73,13 +74,15 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
 #pragma unroll
                 for (int i = 0; i < 24; i++) y[i] = __uint_as_float(__float_as_uint(wv[i]) ^ (((c >> i) & 1u) << 31));
                 sort_network<24>(y, [](float& a, float& b) { const float hi = fmaxf(a, b), lo = fminf(a, b); a = hi; b = lo; });
+                // the record of the next class is requested (scalar loads) before the current one is multiplied
+                llvq::SearchRec nxt = recs[0];
                 for (uint32_t j = 0; j < lay.n_odd; j++) {
-                    const llvq::SearchRec& R = recs[j];
+                    const llvq::SearchRec R = nxt;
+                    nxt = recs[min(j + 1, lay.n_odd - 1)];
                     float acc = 0.0f;
 #pragma unroll
                     for (int k = 0; k < 24; k++) acc = fmaf(R.coef[k], y[k], acc);
-                    const float mul = metric == 0 ? R.rnorm : 1.0f, bias = metric == 0 ? 0.0f : -R.half_n2;
-                    const ScoredId cand = {fmaf(acc, mul, bias), j | (u << 9)};
+                    const ScoredId cand = {fmaf(acc, R.mul[METRIC], R.bias[METRIC]), j | (u << 9)};
                     if (cand.score > best.score) best = cand;
                 }
             }
@@ -102,14 +105,16 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
                 for (int g = 0; g < 5; g++) {
                     if (!__builtin_amdgcn_ballot_w64(grp == g)) continue;            // no lane of this wave has that weight
                     const uint32_t j0 = lay.even_first[g], j1 = j0 + lay.even_count[g];
+                    if (j0 == j1) continue;
+                    llvq::SearchRec nxt = recs[j0];
                     for (uint32_t j = j0; j < j1; j++) {
-                        const llvq::SearchRec& R = recs[j];
+                        const llvq::SearchRec R = nxt;
+                        nxt = recs[min(j + 1, j1 - 1)];
                         float acc = 0.0f;
 #pragma unroll
                         for (int k = 0; k < 24; k++) acc = fmaf(R.coef[k], e[k], acc);
                         acc = fmaf(-R.amin2, R.kappa ? pen_k1 : pen_k0, acc);
-                        const float mul = metric == 0 ? R.rnorm : 1.0f, bias = metric == 0 ? 0.0f : -R.half_n2;
-                        const ScoredId cand = {fmaf(acc, mul, bias), j | (u << 9)};
+                        const ScoredId cand = {fmaf(acc, R.mul[METRIC], R.bias[METRIC]), j | (u << 9)};
                         if (grp == g && cand.score > best.score) best = cand;
                     }
                 }

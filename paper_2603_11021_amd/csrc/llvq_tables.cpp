@@ -554,8 +554,10 @@ bool build_tables(int m_max, Tables& out) {
             if (L.w > 0) S.amin2 = 2.0f * co[L.w - 1];
         }
         for (int k = 0; k < 24; k++) S.coef[k] = co[k];
-        S.rnorm = (float)(1.0 / std::sqrt(16.0 * L.m));
-        S.half_n2 = 8.0f * (float)L.m;
+        S.mul[0] = (float)(1.0 / std::sqrt(16.0 * L.m));
+        S.mul[1] = 1.0f;
+        S.bias[0] = 0.0f;
+        S.bias[1] = -8.0f * (float)L.m;
         S.kappa = (encs[ci].f0 >> F0_KAPPA) & 1u;
         S.cid = ci;
         S.w = L.odd ? 0u : (uint32_t)L.w;

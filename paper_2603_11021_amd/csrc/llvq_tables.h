@@ -132,13 +132,12 @@ struct EncLayout {
 // 0-mod-4 values in descending order.
 struct alignas(128) SearchRec {
     float    coef[24];
-    float    rnorm;      // 1 / sqrt(16 m)
-    float    half_n2;    // ||x||^2 / 2 = 8 m
+    float    mul[2];     // score = <w, x> * mul[metric] + bias[metric]: {1 / sqrt(16 m), 1}
+    float    bias[2];    //                                              {0, -||x||^2 / 2 = -8 m}
     float    amin2;      // twice the smallest 2-mod-4 value (0 when there is none): cost factor of the parity repair
     uint32_t kappa;      // parity that the number of negative F1 signs must have
     uint32_t cid;        // class id
     uint32_t w;          // Golay weight of the class (odd classes: 0)
-    uint32_t pad[2];
 };
 static_assert(sizeof(SearchRec) == 128, "SearchRec layout");
 
