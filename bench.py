@@ -263,6 +263,20 @@ def extra_shapes(q, synth, torch, dev):
     cosm = float((qs / wq.norm(dim=1)).mean())
     print("quantize (angular search + encode) %d blocks: %9.1f us  %.3f M blocks/s  mean cosine %.4f" %
           (nq, us, nq / us, cosm), file=sys.stderr)
+    # the same 65,536 blocks as a 4096 x 384 layer through the block-wise loop with Hessian corrections
+    Kq = 384
+    Xc = r.standard_normal((4 * Kq, Kq)) * np.linspace(1.0, 6.0, Kq)[None, :]
+    Hq = Xc.T @ Xc / Xc.shape[0] + 0.01 * np.eye(Kq)
+    Gq = np.linalg.inv(Hq)
+    Uq = torch.from_numpy(np.linalg.cholesky((Gq + Gq.T) / 2).T.astype(np.float32).copy()).to(dev)
+    W0 = wq.reshape(4096, Kq).clone()
+    Wg = W0.clone()
+    def gptq_once():
+        Wg.copy_(W0)
+        q.llvq_gptq_quantize(Wg, Uq)
+    us = timeit(gptq_once, reps=3)
+    print("gptq loop 4096 x %d (16 block columns, search + encode + gain reset + BLAS propagation): %9.1f us  %.3f M blocks/s" %
+          (Kq, us, nq / us), file=sys.stderr)
     x = torch.from_numpy(synth.activations(r, 1, K)).to(dev).to(torch.float16)
     y = torch.empty((1, N), dtype=torch.float32, device=dev)
     lut = torch.from_numpy(synth.chi_gain_levels(1, scale=0.02)).to(dev)

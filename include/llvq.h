@@ -162,6 +162,23 @@ int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, 
 int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, int8_t* d_points,
                   void* d_idx, int fmt, float* d_score, void* stream);
 
+/* Block-wise quantisation of a layer with Hessian corrections (paper App. B, Alg. 1; Sec. 3.3 "Spherical
+ * GPTQ"; App. F "Hessian-based corrections"): input-channel blocks of 24 are processed left to right; for every
+ * row the current block v is replaced by g * x / ||x||, x the nearest direction of Lambda_24(m_max) (the search of
+ * llvq_quantize) and g = ||v|| rounded to fp16 (gain reset onto the sphere of radius ||v||); the error
+ * E = v - g x/||x|| is propagated into the not yet processed columns R: W[:, R] -= (E U_QQ^-1) U_QR.
+ *   d_W   : [N][ldw] fp32 row-major, ldw >= 24*KB; in: the layer's weights, out: the quantised layer
+ *           (exactly what llvq_decode reconstructs from d_idx and d_gain, up to fp32 rounding)
+ *   d_U   : [K][K] fp32 row-major, K = 24*KB: the upper-triangular factor U with H^-1 = U^T U of the layer's
+ *           input second-moment matrix H (the caller's, e.g. damped); only the upper triangle is read
+ *   d_idx : [N][KB] indices in format `fmt` (LLVQ_IDX_U48 or LLVQ_IDX_U64), written;  d_gain: [N][KB] fp16, written
+ *   d_ws  : device workspace of at least llvq_gptq_workspace_bytes(N) bytes, 16-byte aligned
+ * The dense steps (a 24 x 24 triangular solve and an N x 24 x |R| product per block) are library BLAS calls.
+ * K not a multiple of 24: pad W with zero columns and U with an identity block.                         */
+size_t llvq_gptq_workspace_bytes(int N);
+int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U,
+                       void* d_idx, int fmt, void* d_gain, void* d_ws, size_t ws_bytes, void* stream);
+
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                   uint64_t* h_bad, void* stream);

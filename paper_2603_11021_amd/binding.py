@@ -59,6 +59,8 @@ def _load():
     lib.llvq_matmul_coded.argtypes = [vp, vp, i32, i32, vp, i32, i32, u64, vp, vp, i32, i32, vp, vp]; lib.llvq_matmul_coded.restype = i32
     lib.llvq_encode.argtypes = [vp, vp, sz, vp, i32, vp]; lib.llvq_encode.restype = i32
     lib.llvq_quantize.argtypes = [vp, vp, sz, i32, vp, vp, i32, vp, vp]; lib.llvq_quantize.restype = i32
+    lib.llvq_gptq_workspace_bytes.argtypes = [i32]; lib.llvq_gptq_workspace_bytes.restype = sz
+    lib.llvq_gptq_quantize.argtypes = [vp, vp, i32, i32, sz, vp, vp, i32, vp, vp, sz, vp]; lib.llvq_gptq_quantize.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     _lib = lib
     return lib
@@ -243,6 +245,23 @@ class LLVQ:
                                             idx.data_ptr() if idx is not None else None, fmt, score.data_ptr(),
                                             _stream_handle(stream)), "llvq_quantize")
         return pts, idx, score
+
+    def llvq_gptq_quantize(self, W, U, fmt=LLVQ_IDX_U48, stream=None):
+        """W: float32 [N, 24*KB], overwritten with the quantised layer; U: float32 [K, K] upper factor of H^-1.
+        Returns (indices [N, KB(, 6)], gains float16 [N, KB])."""
+        import torch
+        N, K = W.shape
+        if W.dtype != torch.float32 or U.dtype != torch.float32 or K % 24 or tuple(U.shape) != (K, K) or not W.is_contiguous() or not U.is_contiguous():
+            raise LLVQError("W must be contiguous float32 [N, 24*KB] and U float32 [K, K]")
+        KB = K // 24
+        idx = (torch.empty((N, KB, 6), dtype=torch.uint8, device=W.device) if fmt == LLVQ_IDX_U48
+               else torch.empty((N, KB), dtype=torch.int64, device=W.device))
+        gain = torch.empty((N, KB), dtype=torch.float16, device=W.device)
+        ws = torch.empty(int(self._lib.llvq_gptq_workspace_bytes(N)), dtype=torch.uint8, device=W.device)
+        self._check(self._lib.llvq_gptq_quantize(self._h, W.data_ptr(), N, KB, K, U.data_ptr(), idx.data_ptr(), fmt,
+                                                 gain.data_ptr(), ws.data_ptr(), ws.numel(), _stream_handle(stream)),
+                    "llvq_gptq_quantize")
+        return idx, gain
 
     def llvq_validate(self, idx, stream=None):
         fmt, n = self._idx_fmt(idx)

@@ -515,7 +515,8 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
 // One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
 template <int FMT>
 __global__ void __launch_bounds__(kThreads) encode_kernel(const unsigned char* __restrict__ blob, llvq::EncLayout lay,
-                                                          const uint2* __restrict__ pts, size_t n, void* __restrict__ idx) {
+                                                          const uint2* __restrict__ pts, size_t n, void* __restrict__ idx,
+                                                          size_t out_stride) {
     load_tables(blob, lay.bytes);
     const llvq::EncPtrs T = llvq::make_enc_ptrs(g_lds, lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
@@ -523,9 +524,9 @@ __global__ void __launch_bounds__(kThreads) encode_kernel(const unsigned char* _
         const uint32_t x[6] = {p0.x, p0.y, p1.x, p1.y, p2.x, p2.y};
         const uint64_t I = llvq::encode_block(T, x);
         if constexpr (FMT == LLVQ_IDX_U64) {
-            reinterpret_cast<uint64_t*>(idx)[k] = I;
+            reinterpret_cast<uint64_t*>(idx)[k * out_stride] = I;
         } else {
-            uint16_t* o = reinterpret_cast<uint16_t*>(idx) + 3 * k;
+            uint16_t* o = reinterpret_cast<uint16_t*>(idx) + 3 * k * out_stride;
             o[0] = (uint16_t)I; o[1] = (uint16_t)(I >> 16); o[2] = (uint16_t)(I >> 32);
         }
     }
@@ -659,12 +660,12 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
 }
 
 template <int FMT>
-static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st) {
+static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st, size_t out_stride = 1) {
     const size_t lds = ctx->enc_lay.bytes;
     const int grid = grid_for(ctx, n);
     if (int rc = set_lds(ctx, encode_kernel<FMT>, lds)) return rc;
     hipLaunchKernelGGL(encode_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
-                       reinterpret_cast<const uint2*>(d_x), n, d_idx);
+                       reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "encode launch");
 }
@@ -900,13 +901,58 @@ int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, 
     const int grid = (int)std::min<size_t>(n_blocks, (size_t)ctx->num_cu);
     if (metric == LLVQ_ANGULAR)
         hipLaunchKernelGGL(search_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
-                           ctx->d_words, d_w, n_blocks, d_points, d_score);
+                           ctx->d_words, d_w, (size_t)24, n_blocks, d_points, d_score);
     else
         hipLaunchKernelGGL(search_kernel<LLVQ_EUCLIDEAN>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
-                           ctx->d_words, d_w, n_blocks, d_points, d_score);
+                           ctx->d_words, d_w, (size_t)24, n_blocks, d_points, d_score);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(ctx, e, "search launch");
     return d_idx ? llvq_encode(ctx, d_points, n_blocks, d_idx, fmt, stream) : LLVQ_OK;
+}
+
+size_t llvq_gptq_workspace_bytes(int N) { return N < 1 ? 0 : (size_t)N * (24 * sizeof(float) + 24) + 256; }
+
+int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U, void* d_idx, int fmt,
+                       void* d_gain, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx || !d_W || !d_U || !d_gain || !d_ws || N < 1 || KB < 1 || ldw < (size_t)24 * KB) return LLVQ_EINVAL;
+    if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
+    if (ws_bytes < llvq_gptq_workspace_bytes(N)) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_W, 4) || !aligned(d_U, 4) || !aligned(d_gain, 2) || !aligned(d_ws, 16)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->hip_error = "rocblas_create_handle failed"; return LLVQ_EHIP; }
+    if (rocblas_set_stream(ctx->blas, st) != rocblas_status_success) { ctx->hip_error = "rocblas_set_stream failed"; return LLVQ_EHIP; }
+    float* d_E = reinterpret_cast<float*>(d_ws);                                             // [N][24]
+    int8_t* d_pts = reinterpret_cast<int8_t*>(d_ws) + (((size_t)N * 24 * sizeof(float) + 255) & ~(size_t)255);   // [N][24]
+    const size_t K = (size_t)24 * KB;
+    const size_t isz = fmt == LLVQ_IDX_U48 ? 6 : 8;
+    const int grid = std::min(N, ctx->num_cu);
+    const float one = 1.0f, minus_one = -1.0f;
+    for (int t = 0; t < KB; t++) {
+        float* Wq = d_W + (size_t)24 * t;
+        // directions of this block column, their indices (strided into the [N][KB] array), gain reset and error
+        hipLaunchKernelGGL(search_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
+                           ctx->d_words, Wq, ldw, (size_t)N, d_pts, (float*)nullptr);
+        void* idx_t = reinterpret_cast<unsigned char*>(d_idx) + isz * (size_t)t;
+        const int rc = fmt == LLVQ_IDX_U48 ? launch_encode<LLVQ_IDX_U48>(ctx, d_pts, (size_t)N, idx_t, st, (size_t)KB)
+                                           : launch_encode<LLVQ_IDX_U64>(ctx, d_pts, (size_t)N, idx_t, st, (size_t)KB);
+        if (rc) return rc;
+        hipLaunchKernelGGL(retract_kernel, dim3((N + 255) / 256), dim3(256), 0, st, Wq, ldw, d_pts, N, d_E,
+                           reinterpret_cast<uint16_t*>(d_gain) + t, (size_t)KB);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(ctx, e, "gptq step launch");
+        const size_t r0 = (size_t)24 * (t + 1);
+        if (r0 >= K) break;
+        // W[:, R] -= (E U_QQ^-1) U_QR.  Row-major arrays seen column-major: E^T (24 x N), U^T (lower triangular)
+        const float* Uqq = d_U + (size_t)24 * t * K + (size_t)24 * t;
+        rocblas_status bs = rocblas_strsm(ctx->blas, rocblas_side_left, rocblas_fill_lower, rocblas_operation_none,
+                                          rocblas_diagonal_non_unit, 24, N, &one, Uqq, (rocblas_int)K, d_E, 24);
+        if (bs == rocblas_status_success)
+            bs = rocblas_sgemm(ctx->blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)(K - r0), N, 24, &minus_one,
+                               d_U + (size_t)24 * t * K + r0, (rocblas_int)K, d_E, 24, &one, d_W + r0, (rocblas_int)ldw);
+        if (bs != rocblas_status_success) { ctx->hip_error = std::string("rocblas: ") + rocblas_status_to_string(bs); return LLVQ_EHIP; }
+    }
+    return LLVQ_OK;
 }
 
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,

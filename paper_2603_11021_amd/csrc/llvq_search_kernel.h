@@ -49,7 +49,7 @@ constexpr int kSearchThreads = 1024;
 template <int METRIC>
 __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
                                                                  const uint32_t* __restrict__ words, const float* __restrict__ w_in,
-                                                                 size_t n, int8_t* __restrict__ pts,
+                                                                 size_t ldw, size_t n, int8_t* __restrict__ pts,
                                                                  float* __restrict__ score_out) {
     __shared__ float s_score[kSearchThreads / 64];
     __shared__ uint32_t s_id[kSearchThreads / 64];
@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
         uint32_t negmask = 0;
 #pragma unroll
         for (int i = 0; i < 24; i++) {
-            wv[i] = w_in[24 * v + i];
+            wv[i] = w_in[ldw * v + i];
             negmask |= (wv[i] < 0.0f ? 1u : 0u) << i;
         }
         ScoredId best = {-INFINITY, 0u};
@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
             const uint32_t c = words[u];
             const llvq::SearchRec& R = recs[j];
             const int i = lane < 24 ? lane : 23;
-            const float wi = w_in[24 * v + i];
+            const float wi = w_in[ldw * v + i];
             const uint32_t ci = (c >> i) & 1u;
             int x;
             if (j < lay.n_odd) {
@@ -176,6 +176,32 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
         }
         __syncthreads();
     }
+}
+
+// One step of the block-wise loop of paper App. B (Alg. 1): for every row the block v = W[row][0..23] has been
+// given its nearest direction x (pts); the block is replaced by g * x / ||x|| with g = ||v|| rounded to fp16 (the
+// norm-preserving "gain reset" of paper Sec. 3.3), and the error E = v - g x/||x|| is kept for the propagation.
+__global__ void retract_kernel(float* __restrict__ W, size_t ldw, const int8_t* __restrict__ pts, int N,
+                               float* __restrict__ E, uint16_t* __restrict__ gain, size_t gain_stride) {
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= N) return;
+    float v[24], x[24], n2 = 0.0f, x2 = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 24; i++) {
+        v[i] = W[(size_t)row * ldw + i];
+        x[i] = (float)pts[(size_t)row * 24 + i];
+        n2 = fmaf(v[i], v[i], n2);
+        x2 = fmaf(x[i], x[i], x2);
+    }
+    const __half gh = __float2half_rn(sqrtf(n2));
+    const float scale = __half2float(gh) / sqrtf(x2);
+#pragma unroll
+    for (int i = 0; i < 24; i++) {
+        const float q = scale * x[i];
+        W[(size_t)row * ldw + i] = q;
+        E[(size_t)row * 24 + i] = v[i] - q;
+    }
+    gain[(size_t)row * gain_stride] = __half_as_ushort(gh);
 }
 
 }  // namespace
