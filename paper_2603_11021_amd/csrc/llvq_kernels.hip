@@ -563,6 +563,8 @@ struct llvq_ctx {
     llvq::SearchLayout search_lay{};
     llvq::SearchRec* d_search = nullptr;    // nearest-point search records
     uint32_t* d_words = nullptr;            // the 4096 Golay words in (weight, message) order
+    uint4* d_tile_a = nullptr;              // matrix-core operands of the class tiles
+    float* d_tile_scale = nullptr;          // per-class factor and offset in accumulator order
     unsigned long long* d_counter = nullptr;
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     std::string hip_error;
@@ -668,6 +670,19 @@ static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx
                        reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "encode launch");
+}
+
+// nearest-direction search of n blocks whose rows start ldw floats apart
+static int launch_search(llvq_ctx* ctx, int metric, const float* d_w, size_t ldw, size_t n, int8_t* d_points, float* d_score, hipStream_t st) {
+    const int grid = (int)std::min<size_t>(n, (size_t)2 * ctx->num_cu);
+    if (metric == LLVQ_ANGULAR)
+        hipLaunchKernelGGL(search_mfma_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kMfmaSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
+                           ctx->d_tile_a, ctx->d_tile_scale, ctx->d_words, d_w, ldw, n, d_points, d_score);
+    else
+        hipLaunchKernelGGL(search_mfma_kernel<LLVQ_EUCLIDEAN>, dim3(grid), dim3(kMfmaSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
+                           ctx->d_tile_a, ctx->d_tile_scale, ctx->d_words, d_w, ldw, n, d_points, d_score);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "search launch");
 }
 
 template <int FMT>
@@ -813,6 +828,13 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
         llvq_destroy(ctx);
         return LLVQ_EHIP;
     }
+    const size_t abytes = tabs.search_tile_a.size() * sizeof(uint16_t), scbytes = tabs.search_tile_scale.size() * sizeof(float);
+    if ((e = hipMalloc(&ctx->d_tile_a, abytes)) != hipSuccess || (e = hipMalloc(&ctx->d_tile_scale, scbytes)) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_tile_a, tabs.search_tile_a.data(), abytes, hipMemcpyHostToDevice)) != hipSuccess ||
+        (e = hipMemcpy(ctx->d_tile_scale, tabs.search_tile_scale.data(), scbytes, hipMemcpyHostToDevice)) != hipSuccess) {
+        llvq_destroy(ctx);
+        return LLVQ_EHIP;
+    }
     *out = ctx;
     return LLVQ_OK;
 }
@@ -825,6 +847,8 @@ void llvq_destroy(llvq_ctx* ctx) {
     if (ctx->d_enc_blob) (void)hipFree(ctx->d_enc_blob);
     if (ctx->d_search) (void)hipFree(ctx->d_search);
     if (ctx->d_words) (void)hipFree(ctx->d_words);
+    if (ctx->d_tile_a) (void)hipFree(ctx->d_tile_a);
+    if (ctx->d_tile_scale) (void)hipFree(ctx->d_tile_scale);
     if (ctx->blas) (void)rocblas_destroy_handle(ctx->blas);
     delete ctx;
 }
@@ -898,15 +922,7 @@ int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, 
     if (!aligned(d_w, 4) || !aligned(d_points, 8) || !aligned(d_score, 4)) return LLVQ_EALIGN;
     if (d_idx) { if (int rc = check_idx(d_idx, fmt)) return rc; }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const int grid = (int)std::min<size_t>(n_blocks, (size_t)ctx->num_cu);
-    if (metric == LLVQ_ANGULAR)
-        hipLaunchKernelGGL(search_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
-                           ctx->d_words, d_w, (size_t)24, n_blocks, d_points, d_score);
-    else
-        hipLaunchKernelGGL(search_kernel<LLVQ_EUCLIDEAN>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
-                           ctx->d_words, d_w, (size_t)24, n_blocks, d_points, d_score);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(ctx, e, "search launch");
+    if (int rc = launch_search(ctx, metric, d_w, 24, n_blocks, d_points, d_score, st)) return rc;
     return d_idx ? llvq_encode(ctx, d_points, n_blocks, d_idx, fmt, stream) : LLVQ_OK;
 }
 
@@ -926,13 +942,11 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
     int8_t* d_pts = reinterpret_cast<int8_t*>(d_ws) + (((size_t)N * 24 * sizeof(float) + 255) & ~(size_t)255);   // [N][24]
     const size_t K = (size_t)24 * KB;
     const size_t isz = fmt == LLVQ_IDX_U48 ? 6 : 8;
-    const int grid = std::min(N, ctx->num_cu);
     const float one = 1.0f, minus_one = -1.0f;
     for (int t = 0; t < KB; t++) {
         float* Wq = d_W + (size_t)24 * t;
         // directions of this block column, their indices (strided into the [N][KB] array), gain reset and error
-        hipLaunchKernelGGL(search_kernel<LLVQ_ANGULAR>, dim3(grid), dim3(kSearchThreads), 0, st, ctx->d_search, ctx->search_lay,
-                           ctx->d_words, Wq, ldw, (size_t)N, d_pts, (float*)nullptr);
+        if (int rc = launch_search(ctx, LLVQ_ANGULAR, Wq, ldw, (size_t)N, d_pts, nullptr, st)) return rc;
         void* idx_t = reinterpret_cast<unsigned char*>(d_idx) + isz * (size_t)t;
         const int rc = fmt == LLVQ_IDX_U48 ? launch_encode<LLVQ_IDX_U48>(ctx, d_pts, (size_t)N, idx_t, st, (size_t)KB)
                                            : launch_encode<LLVQ_IDX_U64>(ctx, d_pts, (size_t)N, idx_t, st, (size_t)KB);

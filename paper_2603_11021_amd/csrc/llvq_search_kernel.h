@@ -178,6 +178,256 @@ __global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::Sear
     }
 }
 
+// ---- the same search with the class scores on the matrix cores --------------------------------------------
+// Scoring all classes against all Golay words is a dense contraction: scores[class][word] = sum_k C[class][k] Z[k][word],
+// Z the sorted inputs of a word.  The class values are small integers, exact in bf16; the inputs are split exactly
+// into three bf16 terms (8 + 8 + 8 mantissa bits), so three bf16 MFMA passes accumulate in fp32 what an fp32
+// product would.  A wave takes 64 words (one per lane): each lane sorts for its word, the operands of the two
+// 32-word column tiles are formed by swapping registers between the lane halves (v_permlane32_swap), and every
+// tile of 32 classes costs six v_mfma_f32_32x32x16_bf16 per column tile.  Only the best score per lane and the
+// tile it came from are tracked; the class inside the winning tile is found afterwards by scoring that one tile
+// for the winning word in fp32 on the vector ALUs, which also yields the reported score.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+constexpr int kMfmaSearchThreads = 512;
+
+// the 24 sorted inputs of the odd classes for word c
+__device__ __forceinline__ void arrange_odd(const float (&wv)[24], uint32_t c, float (&y)[24]) {
+#pragma unroll
+    for (int i = 0; i < 24; i++) y[i] = __uint_as_float(__float_as_uint(wv[i]) ^ (((c >> i) & 1u) << 31));
+    sort_network<24>(y, [](float& a, float& b) { const float hi = fmaxf(a, b), lo = fminf(a, b); a = hi; b = lo; });
+}
+
+// the 24 sorted magnitudes of the even classes for word c (support first), and the two parity-repair costs
+__device__ __forceinline__ void arrange_even(const float (&wv)[24], uint32_t negmask, uint32_t c, float (&e)[24], float& pen_k0,
+                                             float& pen_k1, int& grp) {
+    uint32_t key[24];
+#pragma unroll
+    for (int i = 0; i < 24; i++) key[i] = (__float_as_uint(wv[i]) & 0x7FFFFFFFu) | (((c >> i) & 1u) << 31);
+    sort_network<24>(key, [](uint32_t& a, uint32_t& b) { const uint32_t hi = max(a, b), lo = min(a, b); a = hi; b = lo; });
+#pragma unroll
+    for (int i = 0; i < 24; i++) e[i] = __uint_as_float(key[i] & 0x7FFFFFFFu);
+    const uint32_t wt = (uint32_t)__popc(c);
+    grp = wt == 0 ? 0 : (wt == 8 ? 1 : (wt == 12 ? 2 : (wt == 16 ? 3 : 4)));
+    const float xmin1 = wt == 0 ? 0.0f : (wt == 8 ? e[7] : (wt == 12 ? e[11] : (wt == 16 ? e[15] : e[23])));
+    const uint32_t negpar = (uint32_t)__popc(c & negmask) & 1u;
+    pen_k0 = negpar ? xmin1 : 0.0f;      // cost when the class wants an even number of negative signs on the support
+    pen_k1 = negpar ? 0.0f : xmin1;      // ... an odd number
+}
+
+// exact three-way split of fp32 values into bf16 terms, packed two per dword: out[t][d] holds elements 2d, 2d+1 of term t
+template <int NPAIR>
+__device__ __forceinline__ void split_bf16(const float* v, uint32_t (&out)[3][NPAIR]) {
+#pragma unroll
+    for (int d = 0; d < NPAIR; d++) {
+        uint32_t t0[3], t1[3];
+        float a = v[2 * d], b = v[2 * d + 1];
+#pragma unroll
+        for (int t = 0; t < 3; t++) {
+            t0[t] = __float_as_uint(a) & 0xFFFF0000u;
+            t1[t] = __float_as_uint(b) & 0xFFFF0000u;
+            a -= __uint_as_float(t0[t]);
+            b -= __uint_as_float(t1[t]);
+            out[t][d] = (t0[t] >> 16) | t1[t];
+        }
+    }
+}
+
+struct ColumnOperands {      // B operands of one 32-word column tile: [term][k block] as four dwords
+    uint4 b[3][2];
+};
+
+// v[0..23] (+ two extra values at k = 24, 25) of this lane's word -> operands of the column tiles of the lower and upper lane half
+__device__ __forceinline__ void make_operands(const float (&v)[24], float x24, float x25, ColumnOperands& lo, ColumnOperands& hi) {
+    uint32_t p[3][12], q[3][1];
+    split_bf16<12>(v, p);
+    const float extra[2] = {x24, x25};
+    split_bf16<1>(extra, q);
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+        uint32_t x[4], z[4], x2[4], z2[4];
+#pragma unroll
+        for (int d = 0; d < 4; d++) {
+            // k block 0: k 0..7 from the lower half, 8..15 from the upper half; k block 1: 16..23 and 24..31
+            const auto s0 = __builtin_amdgcn_permlane32_swap(p[t][d], p[t][4 + d], false, false);
+            const auto s1 = __builtin_amdgcn_permlane32_swap(p[t][8 + d], d == 0 ? q[t][0] : 0u, false, false);
+            x[d] = s0[0]; z[d] = s0[1]; x2[d] = s1[0]; z2[d] = s1[1];
+        }
+        lo.b[t][0] = make_uint4(x[0], x[1], x[2], x[3]);
+        lo.b[t][1] = make_uint4(x2[0], x2[1], x2[2], x2[3]);
+        hi.b[t][0] = make_uint4(z[0], z[1], z[2], z[3]);
+        hi.b[t][1] = make_uint4(z2[0], z2[1], z2[2], z2[3]);
+    }
+}
+
+// best score of one class tile against one column tile, per lane (the lane's 16 accumulator rows)
+__device__ __forceinline__ float tile_best(const uint4 (&A)[2], const ColumnOperands& B, const float (&mul)[16], const float (&bias)[16]) {
+    f32x16_t acc;
+#pragma unroll
+    for (int r = 0; r < 16; r++) acc[r] = 0.0f;
+#pragma unroll
+    for (int t = 0; t < 3; t++) {
+#pragma unroll
+        for (int kb = 0; kb < 2; kb++)
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, A[kb]), __builtin_bit_cast(bf16x8_t, B.b[t][kb]), acc, 0, 0, 0);
+    }
+    float best = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; r++) best = fmaxf(best, fmaf(acc[r], mul[r], bias[r]));
+    return best;
+}
+
+template <int METRIC>
+__global__ void __launch_bounds__(kMfmaSearchThreads) search_mfma_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
+                                                                          const uint4* __restrict__ tile_a, const float* __restrict__ tile_scale,
+                                                                          const uint32_t* __restrict__ words, const float* __restrict__ w_in,
+                                                                          size_t ldw, size_t n, int8_t* __restrict__ pts,
+                                                                          float* __restrict__ score_out) {
+    constexpr int kWavesHere = kMfmaSearchThreads / 64;
+    __shared__ uint4 s_a[llvq::kMaxSearchTiles * 2 * 64];
+    __shared__ float s_scale[llvq::kMaxSearchTiles * 64];          // [tile][mul, bias][half][16] of this metric
+    __shared__ float s_score[kWavesHere];
+    __shared__ uint32_t s_id[kWavesHere];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
+    for (uint32_t i = threadIdx.x; i < lay.n_tiles * 128u; i += kMfmaSearchThreads) s_a[i] = tile_a[i];
+    for (uint32_t i = threadIdx.x; i < lay.n_tiles * 64u; i += kMfmaSearchThreads)
+        s_scale[i] = tile_scale[(i >> 6) * llvq::kSearchTileScaleFloats + METRIC * 64 + (i & 63u)];
+    __syncthreads();
+
+    for (size_t v = blockIdx.x; v < n; v += gridDim.x) {
+        float wv[24];
+        uint32_t negmask = 0;
+#pragma unroll
+        for (int i = 0; i < 24; i++) {
+            wv[i] = w_in[ldw * v + i];
+            negmask |= (wv[i] < 0.0f ? 1u : 0u) << i;
+        }
+        ScoredId best = {-INFINITY, 0u};          // id = tile << 16 | word index
+        for (int r = 0; r < 4096 / kMfmaSearchThreads; r++) {
+            const uint32_t ubase = (uint32_t)(kMfmaSearchThreads * r + 64 * wave);
+            const uint32_t c = words[ubase + lane];
+            // word index of this lane's column in the two column tiles
+            const uint32_t u_lo = ubase + (lane & 31), u_hi = u_lo + 32;
+            auto score_tiles = [&](const ColumnOperands& lo, const ColumnOperands& hi, uint32_t t0, uint32_t t1, bool ok_lo, bool ok_hi) {
+                for (uint32_t ct = t0; ct < t1; ct++) {
+                    uint4 A[2];
+                    A[0] = s_a[(ct * 2 + 0) * 64 + lane];
+                    A[1] = s_a[(ct * 2 + 1) * 64 + lane];
+                    float mul[16], bias[16];
+#pragma unroll
+                    for (int k = 0; k < 16; k++) {
+                        mul[k] = s_scale[ct * 64 + half * 16 + k];
+                        bias[k] = s_scale[ct * 64 + 32 + half * 16 + k];
+                    }
+                    const float b_lo = tile_best(A, lo, mul, bias), b_hi = tile_best(A, hi, mul, bias);
+                    if (ok_lo && b_lo > best.score) best = {b_lo, (ct << 16) | u_lo};
+                    if (ok_hi && b_hi > best.score) best = {b_hi, (ct << 16) | u_hi};
+                }
+            };
+            {
+                float y[24];
+                arrange_odd(wv, c, y);
+                ColumnOperands lo, hi;
+                make_operands(y, 0.0f, 0.0f, lo, hi);
+                score_tiles(lo, hi, lay.grp_tile_first[0], lay.grp_tile_first[0] + lay.grp_tile_count[0], true, true);
+            }
+            {
+                float e[24], pen_k0, pen_k1;
+                int grp;
+                arrange_even(wv, negmask, c, e, pen_k0, pen_k1, grp);
+                ColumnOperands lo, hi;
+                make_operands(e, pen_k0, pen_k1, lo, hi);
+                // weight group of the words of the two column tiles, as seen from this lane
+                const auto gs = __builtin_amdgcn_permlane32_swap((uint32_t)grp, (uint32_t)grp, false, false);
+                const int g_lo = (int)gs[0], g_hi = (int)gs[1];
+                for (int g = 0; g < 5; g++) {
+                    if (!__builtin_amdgcn_ballot_w64(grp == g)) continue;
+                    score_tiles(lo, hi, lay.grp_tile_first[1 + g], lay.grp_tile_first[1 + g] + lay.grp_tile_count[1 + g], g_lo == g, g_hi == g);
+                }
+            }
+        }
+        // ---- best of the workgroup: (score, tile, word) -------------------------------------------------------
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            ScoredId o;
+            o.score = __shfl_xor(best.score, off);
+            o.id = __shfl_xor(best.id, off);
+            best = better(best, o);
+        }
+        if (lane == 0) { s_score[wave] = best.score; s_id[wave] = best.id; }
+        __syncthreads();
+        if (wave == 0) {
+            ScoredId b = {lane < kWavesHere ? s_score[lane] : -INFINITY, lane < kWavesHere ? s_id[lane] : 0xFFFFFFFFu};
+#pragma unroll
+            for (int off = 4; off > 0; off >>= 1) {
+                ScoredId o;
+                o.score = __shfl_xor(b.score, off);
+                o.id = __shfl_xor(b.id, off);
+                b = better(b, o);
+            }
+            const uint32_t win = __shfl(b.id, 0);
+            const uint32_t ct = win >> 16, u = win & 0xFFFFu;
+            const uint32_t c = words[u];
+            // ---- the class inside the winning tile: lane = row of the tile, fp32 on the vector ALUs ----------
+            const bool odd_tile = ct < lay.grp_tile_first[1];
+            float z[24], pen_k0 = 0.0f, pen_k1 = 0.0f;
+            int grp = 0;
+            if (odd_tile) arrange_odd(wv, c, z);
+            else arrange_even(wv, negmask, c, z, pen_k0, pen_k1, grp);
+            const uint32_t row = lane & 31;
+            const bool valid = row < lay.tile_rows[ct];
+            const uint32_t j = lay.tile_first_rec[ct] + (valid ? row : 0u);
+            const llvq::SearchRec& S = recs[j];
+            float acc = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 24; k++) acc = fmaf(S.coef[k], z[k], acc);
+            acc = fmaf(-S.amin2, S.kappa ? pen_k1 : pen_k0, acc);
+            ScoredId cand = {valid ? fmaf(acc, S.mul[METRIC], S.bias[METRIC]) : -INFINITY, j};
+#pragma unroll
+            for (int off = 16; off > 0; off >>= 1) {
+                ScoredId o;
+                o.score = __shfl_xor(cand.score, off);
+                o.id = __shfl_xor(cand.id, off);
+                cand = better(cand, o);
+            }
+            cand.score = __shfl(cand.score, 0);
+            cand.id = __shfl(cand.id, 0);
+            // ---- the winner's coordinates: lane i = position i ------------------------------------------------
+            const llvq::SearchRec& R = recs[cand.id];
+            const int i = lane < 24 ? lane : 23;
+            const float wi = w_in[ldw * v + i];
+            const uint32_t ci = (c >> i) & 1u;
+            int x;
+            if (odd_tile) {
+                const float yi = __uint_as_float(__float_as_uint(wi) ^ (ci << 31));
+                int rank = 0;
+                for (int k = 0; k < 24; k++) {
+                    const float yk = __shfl(yi, k);
+                    rank += (yk > yi || (yk == yi && k < i)) ? 1 : 0;
+                }
+                const int a = (int)R.coef[rank];
+                x = ci ? -a : a;
+            } else {
+                const uint32_t keyi = (__float_as_uint(wi) & 0x7FFFFFFFu) | (ci << 31);
+                int rank = 0;
+                for (int k = 0; k < 24; k++) {
+                    const uint32_t kk = __shfl(keyi, k);
+                    rank += (kk > keyi || (kk == keyi && k < i)) ? 1 : 0;
+                }
+                const int a = (int)R.coef[rank];
+                x = wi < 0.0f ? -a : a;
+                const uint32_t wt = (uint32_t)__popc(c);
+                const uint32_t negpar = (uint32_t)__popc(c & negmask) & 1u;
+                if (wt > 0 && negpar != R.kappa && rank == (int)wt - 1) x = -x;
+            }
+            if (lane < 24) pts[24 * v + lane] = (int8_t)x;
+            if (lane == 0 && score_out) score_out[v] = cand.score;
+        }
+        __syncthreads();
+    }
+}
+
 // One step of the block-wise loop of paper App. B (Alg. 1): for every row the block v = W[row][0..23] has been
 // given its nearest direction x (pts); the block is replaced by g * x / ||x|| with g = ||v|| rounded to fp16 (the
 // norm-preserving "gain reset" of paper Sec. 3.3), and the error E = v - g x/||x|| is kept for the propagation.

@@ -573,6 +573,55 @@ bool build_tables(int m_max, Tables& out) {
     }
     sl.total = (uint32_t)out.search_recs.size();
     if (sl.total != ncls) return false;
+    // tiles of 32 classes, never across a group
+    sl.n_tiles = 0;
+    for (int g = 0; g < 6; g++) {
+        const uint32_t first = g == 0 ? 0 : sl.even_first[g - 1], count = g == 0 ? sl.n_odd : sl.even_count[g - 1];
+        sl.grp_tile_first[g] = sl.n_tiles;
+        sl.grp_tile_count[g] = (count + 31) / 32;
+        for (uint32_t t = 0; t < sl.grp_tile_count[g]; t++) {
+            if (sl.n_tiles >= (uint32_t)kMaxSearchTiles) return false;
+            sl.tile_first_rec[sl.n_tiles] = first + 32 * t;
+            sl.tile_rows[sl.n_tiles] = std::min<uint32_t>(32, count - 32 * t);
+            sl.n_tiles++;
+        }
+    }
+    auto bf16_of = [](float v) -> uint16_t {          // exact for the small integers stored here
+        uint32_t u;
+        std::memcpy(&u, &v, 4);
+        return (uint16_t)(u >> 16);
+    };
+    out.search_tile_a.assign((size_t)sl.n_tiles * 2 * 64 * 8, 0);
+    out.search_tile_scale.assign((size_t)sl.n_tiles * kSearchTileScaleFloats, 0.0f);
+    for (uint32_t tl = 0; tl < sl.n_tiles; tl++) {
+        for (uint32_t row = 0; row < 32; row++) {
+            const bool valid = row < sl.tile_rows[tl];
+            const SearchRec* S = valid ? &out.search_recs[sl.tile_first_rec[tl] + row] : nullptr;
+            float kvec[32];
+            for (int k = 0; k < 32; k++) kvec[k] = 0.0f;
+            if (valid) {
+                for (int k = 0; k < 24; k++) kvec[k] = S->coef[k];
+                kvec[S->kappa ? 25 : 24] = -S->amin2;
+                for (int k = 0; k < 32; k++) {
+                    float back;
+                    uint32_t u = (uint32_t)bf16_of(kvec[k]) << 16;
+                    std::memcpy(&back, &u, 4);
+                    if (back != kvec[k]) return false;
+                }
+            }
+            for (int kb = 0; kb < 2; kb++)
+                for (int h = 0; h < 2; h++)
+                    for (int t = 0; t < 8; t++)
+                        out.search_tile_a[(((size_t)tl * 2 + kb) * 64 + (32 * h + row)) * 8 + t] = bf16_of(kvec[16 * kb + 8 * h + t]);
+            // accumulator slot of this row: row = 8 (r / 4) + 4 h + r % 4
+            const uint32_t h = (row >> 2) & 1u, r = 4 * (row >> 3) + (row & 3u);
+            for (int metric = 0; metric < 2; metric++) {
+                float* sc = &out.search_tile_scale[(size_t)tl * kSearchTileScaleFloats + metric * 64];
+                sc[0 * 32 + h * 16 + r] = valid ? S->mul[metric] : 0.0f;
+                sc[1 * 32 + h * 16 + r] = valid ? S->bias[metric] : -INFINITY;
+            }
+        }
+    }
     out.search_lay = sl;
     out.golay_sorted = gs;
     return true;

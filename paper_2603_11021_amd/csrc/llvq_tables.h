@@ -142,12 +142,25 @@ struct alignas(128) SearchRec {
 static_assert(sizeof(SearchRec) == 128, "SearchRec layout");
 
 // records are ordered: all odd classes, then the even classes grouped by weight 0, 8, 12, 16, 24
+constexpr int kMaxSearchTiles = 16;
 struct SearchLayout {
     uint32_t n_odd;
     uint32_t even_first[5];
     uint32_t even_count[5];
     uint32_t total;
+    // the same records cut into tiles of 32 classes for the matrix cores; group 0 = odd, 1..5 = even weights 0, 8, 12, 16, 24
+    uint32_t n_tiles;
+    uint32_t grp_tile_first[6];
+    uint32_t grp_tile_count[6];
+    uint32_t tile_first_rec[kMaxSearchTiles];
+    uint32_t tile_rows[kMaxSearchTiles];      // valid classes in the tile (the rest is padding)
 };
+// Matrix-core operands of a tile: A[tile][kb][lane] = eight bf16 values, class row lane % 32, k = 16 kb + 8 (lane / 32) + t.
+// k = 0..23: the record's coef; even classes: k = 24 holds -amin2 when kappa = 0, k = 25 holds -amin2 when kappa = 1.
+// Scale[tile][metric][0 = mul, 1 = bias][lane / 32][r]: factor and offset of the class in accumulator slot r
+// (row 8 (r / 4) + 4 (lane / 32) + r % 4); padding rows have mul 0 and bias -inf.
+constexpr uint32_t kSearchTileABytes = 2 * 64 * 16;
+constexpr uint32_t kSearchTileScaleFloats = 2 * 2 * 2 * 16;
 
 // nibble slot (0..7) of chunk position 0..5 inside a spread6 entry
 static constexpr int kNibbleSlot[6] = {0, 2, 1, 3, 4, 6};
@@ -160,6 +173,8 @@ struct Tables {
     std::vector<unsigned char> enc_blob;
     SearchLayout search_lay;
     std::vector<SearchRec> search_recs;
+    std::vector<uint16_t> search_tile_a;      // n_tiles x 2 x 64 x 8 bf16
+    std::vector<float> search_tile_scale;     // n_tiles x kSearchTileScaleFloats
     std::vector<uint32_t> golay_sorted;   // the 4096 words in (weight, message) order
 };
 
