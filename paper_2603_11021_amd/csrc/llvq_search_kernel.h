@@ -9,10 +9,10 @@
 //               by descending |w_i|, signs those of w_i; if the number of negative signs on supp(c) has the wrong
 //               parity for condition (iii) of Sec. 2.3, the position of supp(c) with the smallest |w_i| (it holds
 //               the smallest value) changes sign, which costs 2 * a_min * |w|_min.
-// One workgroup handles one input vector at a time: a thread takes one Golay word, sorts once for the odd classes
-// and once for the even classes of the word's weight, and then every class costs 24 multiply-adds whose class
-// coefficients arrive in scalar registers (wave-uniform loads).  The workgroup's best (score, class, word) is
-// then turned back into coordinates by the first 24 lanes.
+// One workgroup handles one input vector at a time: a thread takes one Golay word and sorts once for the odd classes
+// and once for the even classes of the word's weight; the scores of all classes against the sorted inputs are a
+// dense contraction and run on the matrix cores (see below).  The workgroup's best candidate is then turned back
+// into coordinates by the first 24 lanes.
 #pragma once
 
 namespace {
@@ -44,141 +44,7 @@ __device__ __forceinline__ ScoredId better(ScoredId a, ScoredId b) {
     return (b.score > a.score || (b.score == a.score && b.id < a.id)) ? b : a;
 }
 
-constexpr int kSearchThreads = 1024;
-
-template <int METRIC>
-__global__ void __launch_bounds__(kSearchThreads) search_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
-                                                                 const uint32_t* __restrict__ words, const float* __restrict__ w_in,
-                                                                 size_t ldw, size_t n, int8_t* __restrict__ pts,
-                                                                 float* __restrict__ score_out) {
-    __shared__ float s_score[kSearchThreads / 64];
-    __shared__ uint32_t s_id[kSearchThreads / 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-
-    for (size_t v = blockIdx.x; v < n; v += gridDim.x) {
-        // the input vector is the same for every thread: it lives in scalar registers
-        float wv[24];
-        uint32_t negmask = 0;
-#pragma unroll
-        for (int i = 0; i < 24; i++) {
-            wv[i] = w_in[ldw * v + i];
-            negmask |= (wv[i] < 0.0f ? 1u : 0u) << i;
-        }
-        ScoredId best = {-INFINITY, 0u};
-        for (int r = 0; r < 4096 / kSearchThreads; r++) {
-            const uint32_t u = threadIdx.x + kSearchThreads * r;
-            const uint32_t c = words[u];
-            // ---- odd classes: every Golay word ------------------------------------------------------------
-            {
-                float y[24];
-#pragma unroll
-                for (int i = 0; i < 24; i++) y[i] = __uint_as_float(__float_as_uint(wv[i]) ^ (((c >> i) & 1u) << 31));
-                sort_network<24>(y, [](float& a, float& b) { const float hi = fmaxf(a, b), lo = fminf(a, b); a = hi; b = lo; });
-                // the record of the next class is requested (scalar loads) before the current one is multiplied
-                llvq::SearchRec nxt = recs[0];
-                for (uint32_t j = 0; j < lay.n_odd; j++) {
-                    const llvq::SearchRec R = nxt;
-                    nxt = recs[min(j + 1, lay.n_odd - 1)];
-                    float acc = 0.0f;
-#pragma unroll
-                    for (int k = 0; k < 24; k++) acc = fmaf(R.coef[k], y[k], acc);
-                    const ScoredId cand = {fmaf(acc, R.mul[METRIC], R.bias[METRIC]), j | (u << 9)};
-                    if (cand.score > best.score) best = cand;
-                }
-            }
-            // ---- even classes of the word's weight ----------------------------------------------------------
-            {
-                uint32_t key[24];
-#pragma unroll
-                for (int i = 0; i < 24; i++) key[i] = (__float_as_uint(wv[i]) & 0x7FFFFFFFu) | (((c >> i) & 1u) << 31);
-                // as unsigned integers: positions of the word first, each part by descending |w|
-                sort_network<24>(key, [](uint32_t& a, uint32_t& b) { const uint32_t hi = max(a, b), lo = min(a, b); a = hi; b = lo; });
-                float e[24];
-#pragma unroll
-                for (int i = 0; i < 24; i++) e[i] = __uint_as_float(key[i] & 0x7FFFFFFFu);
-                const uint32_t wt = (uint32_t)__popc(c);
-                const int grp = wt == 0 ? 0 : (wt == 8 ? 1 : (wt == 12 ? 2 : (wt == 16 ? 3 : 4)));
-                const float xmin1 = wt == 0 ? 0.0f : (wt == 8 ? e[7] : (wt == 12 ? e[11] : (wt == 16 ? e[15] : e[23])));
-                const uint32_t negpar = (uint32_t)__popc(c & negmask) & 1u;
-                // the repair applies when negpar != kappa: two per-thread values, the class picks one
-                const float pen_k0 = negpar ? xmin1 : 0.0f, pen_k1 = negpar ? 0.0f : xmin1;
-                for (int g = 0; g < 5; g++) {
-                    if (!__builtin_amdgcn_ballot_w64(grp == g)) continue;            // no lane of this wave has that weight
-                    const uint32_t j0 = lay.even_first[g], j1 = j0 + lay.even_count[g];
-                    if (j0 == j1) continue;
-                    llvq::SearchRec nxt = recs[j0];
-                    for (uint32_t j = j0; j < j1; j++) {
-                        const llvq::SearchRec R = nxt;
-                        nxt = recs[min(j + 1, j1 - 1)];
-                        float acc = 0.0f;
-#pragma unroll
-                        for (int k = 0; k < 24; k++) acc = fmaf(R.coef[k], e[k], acc);
-                        acc = fmaf(-R.amin2, R.kappa ? pen_k1 : pen_k0, acc);
-                        const ScoredId cand = {fmaf(acc, R.mul[METRIC], R.bias[METRIC]), j | (u << 9)};
-                        if (grp == g && cand.score > best.score) best = cand;
-                    }
-                }
-            }
-        }
-        // ---- best of the workgroup ---------------------------------------------------------------------------
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) {
-            ScoredId o;
-            o.score = __shfl_xor(best.score, off);
-            o.id = __shfl_xor(best.id, off);
-            best = better(best, o);
-        }
-        if (lane == 0) { s_score[wave] = best.score; s_id[wave] = best.id; }
-        __syncthreads();
-        if (wave == 0) {
-            ScoredId b = {lane < kSearchThreads / 64 ? s_score[lane] : -INFINITY, lane < kSearchThreads / 64 ? s_id[lane] : 0xFFFFFFFFu};
-#pragma unroll
-            for (int off = 8; off > 0; off >>= 1) {
-                ScoredId o;
-                o.score = __shfl_xor(b.score, off);
-                o.id = __shfl_xor(b.id, off);
-                b = better(b, o);
-            }
-            b.score = __shfl(b.score, 0);
-            b.id = __shfl(b.id, 0);
-            // ---- the winner's coordinates: lane i = position i ------------------------------------------------
-            const uint32_t j = b.id & 511u, u = b.id >> 9;
-            const uint32_t c = words[u];
-            const llvq::SearchRec& R = recs[j];
-            const int i = lane < 24 ? lane : 23;
-            const float wi = w_in[ldw * v + i];
-            const uint32_t ci = (c >> i) & 1u;
-            int x;
-            if (j < lay.n_odd) {
-                const float yi = __uint_as_float(__float_as_uint(wi) ^ (ci << 31));
-                int rank = 0;
-                for (int k = 0; k < 24; k++) {
-                    const float yk = __shfl(yi, k);
-                    rank += (yk > yi || (yk == yi && k < i)) ? 1 : 0;
-                }
-                const int a = (int)R.coef[rank];
-                x = ci ? -a : a;
-            } else {
-                const uint32_t keyi = (__float_as_uint(wi) & 0x7FFFFFFFu) | (ci << 31);
-                int rank = 0;
-                for (int k = 0; k < 24; k++) {
-                    const uint32_t kk = __shfl(keyi, k);
-                    rank += (kk > keyi || (kk == keyi && k < i)) ? 1 : 0;
-                }
-                const int a = (int)R.coef[rank];
-                x = wi < 0.0f ? -a : a;
-                const uint32_t wt = (uint32_t)__popc(c);
-                const uint32_t negpar = (uint32_t)__popc(c & negmask) & 1u;
-                if (wt > 0 && negpar != R.kappa && rank == (int)wt - 1) x = -x;
-            }
-            if (lane < 24) pts[24 * v + lane] = (int8_t)x;
-            if (lane == 0 && score_out) score_out[v] = b.score;
-        }
-        __syncthreads();
-    }
-}
-
-// ---- the same search with the class scores on the matrix cores --------------------------------------------
+// ---- the class scores on the matrix cores -------------------------------------------------------------------
 // Scoring all classes against all Golay words is a dense contraction: scores[class][word] = sum_k C[class][k] Z[k][word],
 // Z the sorted inputs of a word.  The class values are small integers, exact in bf16; the inputs are split exactly
 // into three bf16 terms (8 + 8 + 8 mantissa bits), so three bf16 MFMA passes accumulate in fp32 what an fp32
@@ -262,7 +128,8 @@ __device__ __forceinline__ void make_operands(const float (&v)[24], float x24, f
 }
 
 // best score of one class tile against one column tile, per lane (the lane's 16 accumulator rows)
-__device__ __forceinline__ float tile_best(const uint4 (&A)[2], const ColumnOperands& B, const float (&mul)[16], const float (&bias)[16]) {
+template <int METRIC>
+__device__ __forceinline__ float tile_best(const uint4 (&A)[2], const ColumnOperands& B, const float (&scale)[16]) {
     f32x16_t acc;
 #pragma unroll
     for (int r = 0; r < 16; r++) acc[r] = 0.0f;
@@ -274,25 +141,25 @@ __device__ __forceinline__ float tile_best(const uint4 (&A)[2], const ColumnOper
     }
     float best = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; r++) best = fmaxf(best, fmaf(acc[r], mul[r], bias[r]));
+    for (int r = 0; r < 16; r++) best = fmaxf(best, METRIC == 0 ? acc[r] * scale[r] : acc[r] + scale[r]);
     return best;
 }
 
 template <int METRIC>
-__global__ void __launch_bounds__(kMfmaSearchThreads) search_mfma_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
+__global__ void __launch_bounds__(kMfmaSearchThreads, 4) search_mfma_kernel(const llvq::SearchRec* __restrict__ recs, llvq::SearchLayout lay,
                                                                           const uint4* __restrict__ tile_a, const float* __restrict__ tile_scale,
                                                                           const uint32_t* __restrict__ words, const float* __restrict__ w_in,
                                                                           size_t ldw, size_t n, int8_t* __restrict__ pts,
                                                                           float* __restrict__ score_out) {
     constexpr int kWavesHere = kMfmaSearchThreads / 64;
     __shared__ uint4 s_a[llvq::kMaxSearchTiles * 2 * 64];
-    __shared__ float s_scale[llvq::kMaxSearchTiles * 64];          // [tile][mul, bias][half][16] of this metric
+    __shared__ float s_scale[llvq::kMaxSearchTiles * 32];          // [tile][half][16] of this metric
     __shared__ float s_score[kWavesHere];
     __shared__ uint32_t s_id[kWavesHere];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
     for (uint32_t i = threadIdx.x; i < lay.n_tiles * 128u; i += kMfmaSearchThreads) s_a[i] = tile_a[i];
-    for (uint32_t i = threadIdx.x; i < lay.n_tiles * 64u; i += kMfmaSearchThreads)
-        s_scale[i] = tile_scale[(i >> 6) * llvq::kSearchTileScaleFloats + METRIC * 64 + (i & 63u)];
+    for (uint32_t i = threadIdx.x; i < lay.n_tiles * 32u; i += kMfmaSearchThreads)
+        s_scale[i] = tile_scale[(i >> 5) * llvq::kSearchTileScaleFloats + METRIC * 32 + (i & 31u)];
     __syncthreads();
 
     for (size_t v = blockIdx.x; v < n; v += gridDim.x) {
@@ -314,13 +181,10 @@ __global__ void __launch_bounds__(kMfmaSearchThreads) search_mfma_kernel(const l
                     uint4 A[2];
                     A[0] = s_a[(ct * 2 + 0) * 64 + lane];
                     A[1] = s_a[(ct * 2 + 1) * 64 + lane];
-                    float mul[16], bias[16];
+                    float scale[16];
 #pragma unroll
-                    for (int k = 0; k < 16; k++) {
-                        mul[k] = s_scale[ct * 64 + half * 16 + k];
-                        bias[k] = s_scale[ct * 64 + 32 + half * 16 + k];
-                    }
-                    const float b_lo = tile_best(A, lo, mul, bias), b_hi = tile_best(A, hi, mul, bias);
+                    for (int k = 0; k < 16; k++) scale[k] = s_scale[ct * 32 + half * 16 + k];
+                    const float b_lo = tile_best<METRIC>(A, lo, scale), b_hi = tile_best<METRIC>(A, hi, scale);
                     if (ok_lo && b_lo > best.score) best = {b_lo, (ct << 16) | u_lo};
                     if (ok_hi && b_hi > best.score) best = {b_hi, (ct << 16) | u_hi};
                 }

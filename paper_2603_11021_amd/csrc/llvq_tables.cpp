@@ -595,11 +595,11 @@ bool build_tables(int m_max, Tables& out) {
     out.search_tile_scale.assign((size_t)sl.n_tiles * kSearchTileScaleFloats, 0.0f);
     for (uint32_t tl = 0; tl < sl.n_tiles; tl++) {
         for (uint32_t row = 0; row < 32; row++) {
-            const bool valid = row < sl.tile_rows[tl];
-            const SearchRec* S = valid ? &out.search_recs[sl.tile_first_rec[tl] + row] : nullptr;
+            // padding rows repeat the first class of the tile: they can tie with it but never win alone
+            const SearchRec* S = &out.search_recs[sl.tile_first_rec[tl] + (row < sl.tile_rows[tl] ? row : 0)];
             float kvec[32];
             for (int k = 0; k < 32; k++) kvec[k] = 0.0f;
-            if (valid) {
+            {
                 for (int k = 0; k < 24; k++) kvec[k] = S->coef[k];
                 kvec[S->kappa ? 25 : 24] = -S->amin2;
                 for (int k = 0; k < 32; k++) {
@@ -615,11 +615,9 @@ bool build_tables(int m_max, Tables& out) {
                         out.search_tile_a[(((size_t)tl * 2 + kb) * 64 + (32 * h + row)) * 8 + t] = bf16_of(kvec[16 * kb + 8 * h + t]);
             // accumulator slot of this row: row = 8 (r / 4) + 4 h + r % 4
             const uint32_t h = (row >> 2) & 1u, r = 4 * (row >> 3) + (row & 3u);
-            for (int metric = 0; metric < 2; metric++) {
-                float* sc = &out.search_tile_scale[(size_t)tl * kSearchTileScaleFloats + metric * 64];
-                sc[0 * 32 + h * 16 + r] = valid ? S->mul[metric] : 0.0f;
-                sc[1 * 32 + h * 16 + r] = valid ? S->bias[metric] : -INFINITY;
-            }
+            float* sc = &out.search_tile_scale[(size_t)tl * kSearchTileScaleFloats];
+            sc[0 * 32 + h * 16 + r] = S->mul[0];       // angular: score = <w, x> * mul
+            sc[1 * 32 + h * 16 + r] = S->bias[1];      // Euclidean: score = <w, x> + bias
         }
     }
     out.search_lay = sl;

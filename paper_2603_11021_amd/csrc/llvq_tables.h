@@ -157,10 +157,10 @@ struct SearchLayout {
 };
 // Matrix-core operands of a tile: A[tile][kb][lane] = eight bf16 values, class row lane % 32, k = 16 kb + 8 (lane / 32) + t.
 // k = 0..23: the record's coef; even classes: k = 24 holds -amin2 when kappa = 0, k = 25 holds -amin2 when kappa = 1.
-// Scale[tile][metric][0 = mul, 1 = bias][lane / 32][r]: factor and offset of the class in accumulator slot r
-// (row 8 (r / 4) + 4 (lane / 32) + r % 4); padding rows have mul 0 and bias -inf.
+// Scale[tile][metric][lane / 32][r]: the factor (angular metric) or the offset (Euclidean metric) of the class in
+// accumulator slot r (row 8 (r / 4) + 4 (lane / 32) + r % 4).  Padding rows repeat the first class of the tile.
 constexpr uint32_t kSearchTileABytes = 2 * 64 * 16;
-constexpr uint32_t kSearchTileScaleFloats = 2 * 2 * 2 * 16;
+constexpr uint32_t kSearchTileScaleFloats = 2 * 2 * 16;
 
 // nibble slot (0..7) of chunk position 0..5 inside a spread6 entry
 static constexpr int kNibbleSlot[6] = {0, 2, 1, 3, 4, 6};
