@@ -36,24 +36,17 @@ extern __shared__ __align__(16) unsigned char g_lds[];
 
 template <int THREADS = kThreads>
 __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ blob, uint32_t bytes) {
-    // global loads are issued ten at a time before their LDS stores, so their latencies overlap
-    const uint4* src = reinterpret_cast<const uint4*>(blob);
-    uint4* dst = reinterpret_cast<uint4*>(g_lds);
+    // global -> LDS without staging in registers: one wave instruction moves 64 x 16 B to 1 KB of consecutive LDS
+    // addresses (base in M0, wave-uniform); chunks of 1 KB are dealt round-robin to the waves
     const uint32_t n16 = bytes / 16;
-    constexpr int kPer = 10;                                    // 10 x 16 B x 1024 threads = 160 KB
-    for (uint32_t base = 0; base < n16; base += kPer * THREADS) {
-        uint4 v[kPer];
-#pragma unroll
-        for (int i = 0; i < kPer; i++) {
-            const uint32_t k = base + threadIdx.x + i * THREADS;
-            v[i] = k < n16 ? src[k] : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < kPer; i++) {
-            const uint32_t k = base + threadIdx.x + i * THREADS;
-            if (k < n16) dst[k] = v[i];
-        }
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (uint32_t c = wave; c * 64 < n16; c += THREADS / 64) {
+        const uint32_t k = c * 64 + lane;
+        if (k < n16)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blob + (size_t)k * 16),
+                                             (__attribute__((address_space(3))) void*)(g_lds + c * 1024), 16, 0, 0);
     }
+    __builtin_amdgcn_s_waitcnt(0);          // vmcnt(0): the wave's copies have landed
     __syncthreads();
 }
 
