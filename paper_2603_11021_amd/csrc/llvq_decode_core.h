@@ -70,6 +70,15 @@ LLVQ_HD bool wave_any(bool v) {
 #endif
 }
 
+// loop condition shared by the lanes of a wavefront: true while any lane still has work (the host has one lane)
+LLVQ_HD bool wave_or(bool v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_ballot_w64(v) != 0;
+#else
+    return v;
+#endif
+}
+
 struct BlockInfo {
     uint32_t cid;                // class id
     uint32_t m;                  // shell
@@ -78,39 +87,45 @@ struct BlockInfo {
     uint32_t vti_lo, vti_hi;     // value table of the class, int8
 };
 
-// Decodes NB indices per lane (each must be < npoints), stage by stage so that the table reads of the NB
+// App. A steps 1-2: shell and class of an index (< npoints) in one search over the global class offsets
+struct ClassHit {
+    uint32_t cid;     // class id
+    uint64_t Ic;      // index inside the class
+};
+
+LLVQ_HD ClassHit find_class(const TabPtrs& T, uint64_t I) {
+    uint32_t cid = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I >> kBucketShift) * 2u);
+    uint64_t off = tab_at<uint64_t, kOffClsOff>(T, cid * 8u);
+    uint64_t nxt = tab_at<uint64_t, kOffClsOff + 8>(T, cid * 8u);
+    for (;;) {
+        const bool more = I >= nxt && cid + 1 < T.ncls;
+        if (more) {
+            cid++;
+            off = nxt;
+            nxt = tab_at<uint64_t, kOffClsOff + 8>(T, cid * 8u);
+        }
+        if (!wave_or(more)) break;
+    }
+    ClassHit h;
+    h.cid = cid;
+    h.Ic = I - off;
+    return h;
+}
+
+// App. A steps 3-4 for NB blocks per lane whose classes are known, stage by stage so that the table reads of the NB
 // blocks are independent and overlap.  w[u][0..3] receive the nibble words of block u.
 template <int NB>
-LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
+LLVQ_HD void decode_blocks_from(const TabPtrs& T, const ClassHit (&hit)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
     uint32_t cid[NB];
-    // App. A steps 1-2: shell and class in one search over the global class offsets
-    uint64_t off[NB], nxt[NB];
 #pragma unroll
-    for (int u = 0; u < NB; u++) {
-        cid[u] = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I[u] >> kBucketShift) * 2u);
-        off[u] = tab_at<uint64_t, kOffClsOff>(T, cid[u] * 8u);
-        nxt[u] = tab_at<uint64_t, kOffClsOff + 8>(T, cid[u] * 8u);
-    }
-    for (;;) {
-        bool more = false;
-#pragma unroll
-        for (int u = 0; u < NB; u++) {
-            if (I[u] >= nxt[u] && cid[u] + 1 < T.ncls) {
-                cid[u]++;
-                off[u] = nxt[u];
-                nxt[u] = tab_at<uint64_t, kOffClsOff + 8>(T, cid[u] * 8u);
-                more = true;
-            }
-        }
-        if (!more) break;
-    }
+    for (int u = 0; u < NB; u++) cid[u] = hit[u].cid;
 
     ClassRec R[NB];
     uint32_t c[NB], U[NB], e0[NB], e1[NB], s[NB], d[NB], j[NB];
 #pragma unroll
     for (int u = 0; u < NB; u++) {
         R[u] = tab_at<ClassRec, kOffCls>(T, cid[u] * (uint32_t)sizeof(ClassRec));
-        const uint64_t Ic = I[u] - off[u];
+        const uint64_t Ic = hit[u].Ic;
         const uint32_t f0 = R[u].f0, f1 = R[u].f1;
         // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
         // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
@@ -222,6 +237,15 @@ LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (
                       (gA1 & 0x04044444u) | (gA0 & dkeep);
         }
     }
+}
+
+// Decodes NB indices per lane (each must be < npoints)
+template <int NB>
+LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
+    ClassHit hit[NB];
+#pragma unroll
+    for (int u = 0; u < NB; u++) hit[u] = find_class(T, I[u]);
+    decode_blocks_from<NB>(T, hit, w, info);
 }
 
 // Decodes one index I (must be < npoints); w[0..3] receive the nibble words.

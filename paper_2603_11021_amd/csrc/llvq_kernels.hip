@@ -206,8 +206,6 @@ template <> struct Dot<bf16x2_t> {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kNB = 1;              // blocks decoded per lane and pass, interleaved to overlap table reads
-
 template <int FMT, typename X2>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
@@ -239,49 +237,50 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             const int mc = min(kMaxMChunk, M - m0);
             for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
             __syncthreads();
-            // a wave takes kNB consecutive batches of 64 blocks per pass; the indices and gains of the next
-            // pass and the first activation row of this pass are requested before this pass is decoded
-            struct Fetch { uint64_t I[kNB]; uint32_t row[kNB], b[kNB]; uint16_t g[kNB]; bool live[kNB]; };
+            // a wave takes every 16th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
+            // the next batch are requested before this one is decoded, and the next batch's class search (a chain of
+            // dependent table reads) is started before this batch's products, which hide its latency
+            struct Fetch { uint64_t I; uint32_t row, b; uint16_t g; bool live; };
             auto fetch = [&](uint32_t base, Fetch& f) {
-#pragma unroll
-                for (int u = 0; u < kNB; u++) {
-                    const uint32_t fb = base + 64 * u + lane;
-                    f.live[u] = fb < nblk;
-                    const uint32_t fbc = f.live[u] ? fb : nblk - 1;
-                    // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
-                    f.row[u] = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
-                    f.b[u] = fbc - f.row[u] * (uint32_t)KB;
-                    load_block<FMT>(idx, gain, cd, blk0 + fbc, f.I[u], f.g[u]);
-                }
+                const uint32_t fb = base + lane;
+                f.live = fb < nblk;
+                const uint32_t fbc = f.live ? fb : nblk - 1;
+                // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
+                f.row = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
+                f.b = fbc - f.row * (uint32_t)KB;
+                load_block<FMT>(idx, gain, cd, blk0 + fbc, f.I, f.g);
             };
-            const uint32_t stride = kWaves * 64 * kNB;
-            uint32_t base = (uint32_t)wave * (64 * kNB);
+            auto classify = [&](const Fetch& f, bool& ok) {
+                ok = f.live && f.I < T.npoints;
+                return llvq::find_class(T, ok ? f.I : 0);
+            };
+            const uint32_t stride = kWaves * 64;
+            uint32_t base = (uint32_t)wave * 64;
             Fetch cur, nxt;
-            if (base < nblk) fetch(base, cur);
+            llvq::ClassHit hit_cur, hit_nxt;
+            bool ok_cur = false, ok_nxt = false;
+            if (base < nblk) {
+                fetch(base, cur);
+                hit_cur = classify(cur, ok_cur);
+            }
             for (; base < nblk; base += stride) {
-                if (base + stride < nblk) fetch(base + stride, nxt);
-                u32x4 xq[kNB][3];
-#pragma unroll
-                for (int u = 0; u < kNB; u++) {
-                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)m0 * xpitch + (size_t)cur.b[u] * 12);
-                    xq[u][0] = xp[0]; xq[u][1] = xp[1]; xq[u][2] = xp[2];
+                const bool more = base + stride < nblk;
+                if (more) fetch(base + stride, nxt);
+                u32x4 xq[1][3];
+                {
+                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)m0 * xpitch + (size_t)cur.b * 12);
+                    xq[0][0] = xp[0]; xq[0][1] = xp[1]; xq[0][2] = xp[2];
                 }
-                uint64_t I[kNB];
-                bool ok[kNB];
-#pragma unroll
-                for (int u = 0; u < kNB; u++) {
-                    ok[u] = cur.live[u] && cur.I[u] < T.npoints;
-                    I[u] = ok[u] ? cur.I[u] : 0;
-                }
-                uint32_t w[kNB][4];
-                llvq::BlockInfo bi[kNB];
-                llvq::decode_blocks<kNB>(T, I, w, bi);
-#pragma unroll
-                for (int u = 0; u < kNB; u++) {
-                    if (base + 64 * u >= nblk) break;                       // wave-uniform: this batch is empty
+                uint32_t w[1][4];
+                llvq::BlockInfo bi[1];
+                const llvq::ClassHit hits[1] = {hit_cur};
+                llvq::decode_blocks_from<1>(T, hits, w, bi);
+                if (more) hit_nxt = classify(nxt, ok_nxt);
+                {
+                    constexpr int u = 0;
                     const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi;
-                    const float g = __half2float(__ushort_as_half(cur.g[u]));
-                    const float scale = ok[u] ? g * bi[u].rnorm : 0.0f;
+                    const float g = __half2float(__ushort_as_half(cur.g));
+                    const float scale = ok_cur ? g * bi[u].rnorm : 0.0f;
                     X2 wt[12];
 #pragma unroll
                     for (int c = 0; c < 4; c++) {
@@ -292,21 +291,21 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                         wt[3 * c + 2] = Dot<X2>::cvt(fe, true);    // positions 6c+4, 6c+5
                     }
                     // rows are contiguous runs of lanes; with KB >= 64 a batch touches at most two rows
-                    const uint32_t row = cur.row[u];
+                    const uint32_t row = cur.row;
                     const uint32_t row_lo = __builtin_amdgcn_readfirstlane(row);
                     const uint32_t row_hi = __builtin_amdgcn_readlane(row, 63);
                     const bool two_rows = row_hi <= row_lo + 1;
                     for (int mi = 0; mi < mc; mi++) {
                         u32x4 x0 = xq[u][0], x1 = xq[u][1], x2 = xq[u][2];
                         if (mi > 0) {
-                            const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b[u] * 12);
+                            const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b * 12);
                             x0 = xp[0]; x1 = xp[1]; x2 = xp[2];
                         }
                         const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
                         float acc = 0.0f;
 #pragma unroll
                         for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
-                        float p = cur.live[u] ? acc * scale : 0.0f;
+                        float p = cur.live ? acc * scale : 0.0f;
                         if (row_hi == row_lo) {                                  // the whole batch lies in one row
                             const float s_all = wave_sum(p);
                             if (lane == 0) atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_all);
@@ -327,11 +326,13 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                                 const uint32_t rv = __shfl_down(row, off);
                                 if (lane + off < 64 && rv == row) p += pv;
                             }
-                            if (head && cur.live[u]) atomicAdd(&ysum[row * kMaxMChunk + mi], p);
+                            if (head && cur.live) atomicAdd(&ysum[row * kMaxMChunk + mi], p);
                         }
                     }
                 }
                 cur = nxt;
+                hit_cur = hit_nxt;
+                ok_cur = ok_nxt;
             }
             __syncthreads();
             for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
