@@ -112,102 +112,93 @@ LLVQ_HD ClassHit find_class(const TabPtrs& T, uint64_t I) {
     return h;
 }
 
-// App. A steps 3-4 for NB blocks per lane whose classes are known, stage by stage so that the table reads of the NB
-// blocks are independent and overlap.  w[u][0..3] receive the nibble words of block u.
-template <int NB>
-LLVQ_HD void decode_blocks_from(const TabPtrs& T, const ClassHit (&hit)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
-    uint32_t cid[NB];
-#pragma unroll
-    for (int u = 0; u < NB; u++) cid[u] = hit[u].cid;
+// App. A step 3 for a block whose class is known: the digits r, s, I'' = (d, rin, rho1) and the first table
+// reads that depend on them.  Everything the placement needs later is carried in a Front.
+struct Front {
+    uint32_t cid, f0, f1;
+    uint32_t c;                  // the Golay word selected by r
+    uint32_t e0, e1;             // symbol planes over the slots of U and over the F1 slots
+    uint32_t s, d;               // sign bits, rank of the subset U
+    uint32_t sp_j;               // split entry guessed for d (index into the split table)
+    uint32_t vt8_lo, vt8_hi, vti_lo, vti_hi;
+    float rnorm;
+};
 
-    ClassRec R[NB];
-    uint32_t c[NB], U[NB], e0[NB], e1[NB], s[NB], d[NB], j[NB];
-#pragma unroll
-    for (int u = 0; u < NB; u++) {
-        R[u] = tab_at<ClassRec, kOffCls>(T, cid[u] * (uint32_t)sizeof(ClassRec));
-        const uint64_t Ic = hit[u].Ic;
-        const uint32_t f0 = R[u].f0, f1 = R[u].f1;
-        // App. A step 3: r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are
-        // exact: the operands are integers below 2^48 held in doubles and the reciprocals are nudged upwards.
-        const uint32_t acode = (f1 >> F1_ACODE) & 3u;
-        const double A = tab_at<double, kOffAtab>(T, acode * 16u);
-        const double invA = tab_at<double, kOffAtab + 8>(T, acode * 16u);
-        const double x = (double)Ic;
-        const double q1 = floor(x * invA);
-        const uint32_t r = (uint32_t)fma(-q1, A, x);
-        const int B = (int)((f0 >> F0_B) & 31u);
-        const double ipp = floor(ldexp(q1, -B));
-        s[u] = (uint32_t)fma(-ipp, ldexp(1.0, B), q1);
-        // I'' = (d * Pin + rin) * P1 + rho1
-        const double dd = floor(ipp * R[u].invPP);
-        const uint32_t rem = (uint32_t)fma(-dd, (double)R[u].PP, ipp);
-        d[u] = (uint32_t)dd;
-        const uint32_t rin = (uint32_t)((double)rem * (double)R[u].invP1);
-        const uint32_t rho1 = rem - rin * R[u].P1;
-        // the Golay word selected by r, the symbol planes over the slots of U (e0) and over the F1 slots (e1)
-        c[u] = tab_at<uint32_t, kOffGs>(T, (((f1 >> F1_GOFF) & 4095u) + r) * 4u);
-        e0[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb0 + rin) * 4u);
-        e1[u] = tab_at<uint32_t, kOffInner>(T, (R[u].tb1 + rho1) * 4u);
-        j[u] = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * kGuessBuckets + (d[u] >> ((f1 >> F1_GSHIFT) & 31u)));
-    }
+LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
+    Front F;
+    const ClassRec R = tab_at<ClassRec, kOffCls>(T, hit.cid * (uint32_t)sizeof(ClassRec));
+    const uint32_t f0 = R.f0, f1 = R.f1;
+    // r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are exact: the operands are
+    // integers below 2^48 held in doubles and the reciprocals are nudged upwards.
+    const uint32_t acode = (f1 >> F1_ACODE) & 3u;
+    const double A = tab_at<double, kOffAtab>(T, acode * 16u);
+    const double invA = tab_at<double, kOffAtab + 8>(T, acode * 16u);
+    const double x = (double)hit.Ic;
+    const double q1 = floor(x * invA);
+    const uint32_t r = (uint32_t)fma(-q1, A, x);
+    const int B = (int)((f0 >> F0_B) & 31u);
+    const double ipp = floor(ldexp(q1, -B));
+    F.s = (uint32_t)fma(-ipp, ldexp(1.0, B), q1);
+    // I'' = (d * Pin + rin) * P1 + rho1
+    const double dd = floor(ipp * R.invPP);
+    const uint32_t rem = (uint32_t)fma(-dd, (double)R.PP, ipp);
+    F.d = (uint32_t)dd;
+    const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
+    const uint32_t rho1 = rem - rin * R.P1;
+    F.c = tab_at<uint32_t, kOffGs>(T, (((f1 >> F1_GOFF) & 4095u) + r) * 4u);
+    F.e0 = tab_at<uint32_t, kOffInner>(T, (R.tb0 + rin) * 4u);
+    F.e1 = tab_at<uint32_t, kOffInner>(T, (R.tb1 + rho1) * 4u);
+    const uint32_t j = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * kGuessBuckets + (F.d >> ((f1 >> F1_GSHIFT) & 31u)));
+    F.sp_j = (uint32_t)(uint16_t)(R.sp + j) | (j << 16);
+    F.cid = hit.cid; F.f0 = f0; F.f1 = f1;
+    F.vt8_lo = R.vt8_lo; F.vt8_hi = R.vt8_hi; F.vti_lo = R.vti_lo; F.vti_hi = R.vti_hi;
+    F.rnorm = tab_at<float, kOffRnorm>(T, (f0 >> (F0_M - 2)) & 60u);
+    return F;
+}
 
-    // App. A step 4, placement: the q-subset U of the outer domain's n slots with rank d
-    SplitEnt e[NB];
-    uint32_t nbase[NB];
-#pragma unroll
-    for (int u = 0; u < NB; u++) {
-        const uint32_t eo = (uint32_t)(uint16_t)(R[u].sp + j[u]) * (uint32_t)sizeof(SplitEnt);
-        e[u] = tab_at<SplitEnt, kOffSplit>(T, eo);
-        nbase[u] = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);   // one past the last entry is never used
-    }
+// App. A step 4: placement and signs.  w[0..3] receive the nibble words of the block.
+LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]) {
+    // the q-subset U of the outer domain's n slots with rank d
+    uint32_t j = F.sp_j >> 16, eo = (F.sp_j & 0xFFFFu) * (uint32_t)sizeof(SplitEnt);
+    SplitEnt e = tab_at<SplitEnt, kOffSplit>(T, eo);
+    uint32_t nbase = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);   // one past the last entry is never used
+    const uint32_t jmax = (F.f1 >> F1_JMAX) & 15u;
     for (;;) {
-        bool more = false;
-#pragma unroll
-        for (int u = 0; u < NB; u++) {
-            const uint32_t jmax = (R[u].f1 >> F1_JMAX) & 15u;
-            if (j[u] < jmax && d[u] >= nbase[u]) {
-                j[u]++;
-                const uint32_t eo = (uint32_t)(uint16_t)(R[u].sp + j[u]) * (uint32_t)sizeof(SplitEnt);
-                e[u] = tab_at<SplitEnt, kOffSplit>(T, eo);
-                nbase[u] = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);
-                more = true;
-            }
+        const bool more = j < jmax && F.d >= nbase;
+        if (more) {
+            j++;
+            eo += (uint32_t)sizeof(SplitEnt);
+            e = tab_at<SplitEnt, kOffSplit>(T, eo);
+            nbase = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);
         }
-        if (!more) break;
+        if (!wave_or(more)) break;
     }
-#pragma unroll
-    for (int u = 0; u < NB; u++) {
-        const uint32_t dl = d[u] - e[u].base;
-        const uint32_t rk_hi = (uint32_t)((double)dl * (double)e[u].inv);
-        const uint32_t rk_lo = dl - rk_hi * e[u].div;
-        U[u] = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e[u].b12lo + rk_lo) * 2u) |
-               ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e[u].b12hi + rk_hi) * 2u) << 12);
-    }
+    const uint32_t dl = F.d - e.base;
+    const uint32_t rk_hi = (uint32_t)((double)dl * (double)e.inv);
+    const uint32_t rk_lo = dl - rk_hi * e.div;
+    const uint32_t U = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12lo + rk_lo) * 2u) |
+                       ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12hi + rk_hi) * 2u) << 12);
+    const bool any_b1 = wave_any((F.e1 >> 16) != 0);                      // a third F1 value (10) is rare
 
-    bool any_b1 = false;
-#pragma unroll
-    for (int u = 0; u < NB; u++) any_b1 |= (e1[u] >> 16) != 0;
-    any_b1 = wave_any(any_b1);                                           // a third F1 value (10) is rare
-
-#pragma unroll
-    for (int u = 0; u < NB; u++) {
-        const uint32_t f0 = R[u].f0;
-        info[u].cid = cid[u]; info[u].m = (f0 >> F0_M) & 15u;
-        info[u].rnorm = tab_at<float, kOffRnorm>(T, (f0 >> (F0_M - 2)) & 60u);
-        info[u].vt8_lo = R[u].vt8_lo; info[u].vt8_hi = R[u].vt8_hi; info[u].vti_lo = R[u].vti_lo; info[u].vti_hi = R[u].vti_hi;
+    BlockInfo info;
+    const uint32_t f0 = F.f0;
+    info.cid = F.cid; info.m = (f0 >> F0_M) & 15u;
+    info.rnorm = F.rnorm;
+    info.vt8_lo = F.vt8_lo; info.vt8_hi = F.vt8_hi; info.vti_lo = F.vti_lo; info.vti_hi = F.vti_hi;
+    {
         // planes pre-shifted by two: the deposit keys below are byte offsets into a table of dwords
-        const uint32_t a0 = (e0[u] & 0xFFFFu) << 2, b0 = (e0[u] >> 16) << 2, a1 = (e1[u] & 0xFFFFu) << 2, b1 = (e1[u] >> 16) << 2;
+        const uint32_t a0 = (F.e0 & 0xFFFFu) << 2, b0 = (F.e0 >> 16) << 2, a1 = (F.e1 & 0xFFFFu) << 2, b1 = (F.e1 >> 16) << 2;
         // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so
         // that the number of negative F1 coordinates has the parity condition (iii) asks for
         const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
-        uint32_t s1 = s[u] & ((1u << wm1) - 1u);
+        uint32_t s1 = F.s & ((1u << wm1) - 1u);
         const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
         s1 |= forced << wm1;
-        const uint32_t s0 = (s[u] >> wm1) << 2;
+        const uint32_t s0 = (F.s >> wm1) << 2;
 
         const bool odd = (f0 >> F0_ODD) & 1u;
         const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
-        const uint32_t cw = c[u];
+        const uint32_t cw = F.c;
         const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? cw : 0u;           // slots of the direct F1 word
         const uint32_t om = outer_all ? 0xFFFFFFu : (~cw & 0xFFFFFFu);      // positions of the outer domain
         const uint32_t sm = odd ? 0xFFFFFFu : cw;                           // positions taking a bit of sb
@@ -218,7 +209,7 @@ LLVQ_HD void decode_blocks_from(const TabPtrs& T, const ClassHit (&hit)[NB], uin
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
-            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, (omk << 6) | (bfe6(U[u], ou) ^ omk));   // U in absolute positions
+            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, (omk << 6) | (bfe6(U, ou) ^ omk));   // U in absolute positions
             ou += popc32(omk);
             const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
             const uint32_t cx = cmk * 0x104u, ux = uk * 0x104u, sx = smk * 0x104u;
@@ -233,29 +224,16 @@ LLVQ_HD void decode_blocks_from(const TabPtrs& T, const ClassHit (&hit)[NB], uin
             const uint32_t gS1 = spread6_at(T, sx, sb, os);
             os += popc32(smk);
             const uint32_t ones = 0x01011111u;
-            w[u][k] = ((gA1 | gA0) & ones) | ((gB & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
+            w[k] = ((gA1 | gA0) & ones) | ((gB & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
                       (gA1 & 0x04044444u) | (gA0 & dkeep);
         }
     }
-}
-
-// Decodes NB indices per lane (each must be < npoints)
-template <int NB>
-LLVQ_HD void decode_blocks(const TabPtrs& T, const uint64_t (&I)[NB], uint32_t (&w)[NB][4], BlockInfo (&info)[NB]) {
-    ClassHit hit[NB];
-#pragma unroll
-    for (int u = 0; u < NB; u++) hit[u] = find_class(T, I[u]);
-    decode_blocks_from<NB>(T, hit, w, info);
+    return info;
 }
 
 // Decodes one index I (must be < npoints); w[0..3] receive the nibble words.
-LLVQ_HD BlockInfo decode_block(const TabPtrs& T, uint64_t I, uint32_t w[4]) {
-    const uint64_t Iv[1] = {I};
-    uint32_t wv[1][4];
-    BlockInfo bi[1];
-    decode_blocks<1>(T, Iv, wv, bi);
-    w[0] = wv[0][0]; w[1] = wv[0][1]; w[2] = wv[0][2]; w[3] = wv[0][3];
-    return bi[0];
+LLVQ_HD BlockInfo decode_block(const TabPtrs& T, uint64_t I, uint32_t (&w)[4]) {
+    return decode_back(T, decode_front(T, find_class(T, I)), w);
 }
 
 // v_perm_b32-style byte select restricted to selector values 0..7: byte k of the result is byte sel_k of hi:lo

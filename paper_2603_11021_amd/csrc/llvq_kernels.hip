@@ -238,8 +238,8 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
             __syncthreads();
             // a wave takes every 16th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
-            // the next batch are requested before this one is decoded, and the next batch's class search (a chain of
-            // dependent table reads) is started before this batch's products, which hide its latency
+            // the next batch are requested before this one is decoded, and the next batch's class search and digit
+            // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
             struct Fetch { uint64_t I; uint32_t row, b; uint16_t g; bool live; };
             auto fetch = [&](uint32_t base, Fetch& f) {
                 const uint32_t fb = base + lane;
@@ -250,18 +250,18 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 f.b = fbc - f.row * (uint32_t)KB;
                 load_block<FMT>(idx, gain, cd, blk0 + fbc, f.I, f.g);
             };
-            auto classify = [&](const Fetch& f, bool& ok) {
+            auto front_of = [&](const Fetch& f, bool& ok) {
                 ok = f.live && f.I < T.npoints;
-                return llvq::find_class(T, ok ? f.I : 0);
+                return llvq::decode_front(T, llvq::find_class(T, ok ? f.I : 0));
             };
             const uint32_t stride = kWaves * 64;
             uint32_t base = (uint32_t)wave * 64;
             Fetch cur, nxt;
-            llvq::ClassHit hit_cur, hit_nxt;
+            llvq::Front front_cur, front_nxt;
             bool ok_cur = false, ok_nxt = false;
             if (base < nblk) {
                 fetch(base, cur);
-                hit_cur = classify(cur, ok_cur);
+                front_cur = front_of(cur, ok_cur);
             }
             for (; base < nblk; base += stride) {
                 const bool more = base + stride < nblk;
@@ -273,9 +273,8 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 }
                 uint32_t w[1][4];
                 llvq::BlockInfo bi[1];
-                const llvq::ClassHit hits[1] = {hit_cur};
-                llvq::decode_blocks_from<1>(T, hits, w, bi);
-                if (more) hit_nxt = classify(nxt, ok_nxt);
+                bi[0] = llvq::decode_back(T, front_cur, w[0]);
+                if (more) front_nxt = front_of(nxt, ok_nxt);
                 {
                     constexpr int u = 0;
                     const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi;
@@ -331,7 +330,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                     }
                 }
                 cur = nxt;
-                hit_cur = hit_nxt;
+                front_cur = front_nxt;
                 ok_cur = ok_nxt;
             }
             __syncthreads();
