@@ -67,7 +67,9 @@ enum {
 
 /* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 13, on HIP device `device`.
  * Builds the constant tables (Golay words, class records, ranking tables) on the host and copies
- * them to the device.  The context is immutable afterwards and may be shared by threads.         */
+ * them to the device.  The tables are immutable afterwards; llvq_decode*, llvq_matmul, llvq_matmul_coded, llvq_encode,
+ * llvq_quantize and llvq_shell_offset may be called on one context from several threads.  llvq_matmul_ws,
+ * llvq_gptq_quantize (they share the context's BLAS handle) and llvq_validate (its counter) may not.   */
 int llvq_create(llvq_ctx** out, int m_max, int device);
 void llvq_destroy(llvq_ctx* ctx);
 

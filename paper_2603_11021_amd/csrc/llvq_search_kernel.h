@@ -87,15 +87,15 @@ template <int NPAIR>
 __device__ __forceinline__ void split_bf16(const float* v, uint32_t (&out)[3][NPAIR]) {
 #pragma unroll
     for (int d = 0; d < NPAIR; d++) {
-        uint32_t t0[3], t1[3];
         float a = v[2 * d], b = v[2 * d + 1];
 #pragma unroll
         for (int t = 0; t < 3; t++) {
-            t0[t] = __float_as_uint(a) & 0xFFFF0000u;
-            t1[t] = __float_as_uint(b) & 0xFFFF0000u;
-            a -= __uint_as_float(t0[t]);
-            b -= __uint_as_float(t1[t]);
-            out[t][d] = (t0[t] >> 16) | t1[t];
+            // the upper halves of a and b side by side (a in the low half): one byte permute, which also truncates
+            out[t][d] = __builtin_amdgcn_perm(__float_as_uint(b), __float_as_uint(a), 0x07060302u);
+            if (t < 2) {
+                a -= __uint_as_float(__float_as_uint(a) & 0xFFFF0000u);
+                b -= __uint_as_float(__float_as_uint(b) & 0xFFFF0000u);
+            }
         }
     }
 }

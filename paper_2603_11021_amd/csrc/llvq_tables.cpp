@@ -458,7 +458,6 @@ bool build_tables(int m_max, Tables& out) {
     lay.ncls = ncls;
     lay.inner_entries = (uint32_t)inner.size();
     lay.npoints = running;
-    for (int m = 0; m < 16; m++) lay.rnorm[m] = rnorm[m];
     out.lay = lay;
     out.blob.swap(blob);
 

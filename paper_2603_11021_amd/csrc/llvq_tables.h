@@ -78,7 +78,6 @@ struct TableLayout {
     uint32_t inner_entries;
     uint32_t pad;
     uint64_t npoints;        // N(m_max)
-    float    rnorm[16];      // 1/sqrt(16 m)
 };
 
 // ---- tables of the encoder-side index map (point -> index), a blob of their own ---------------------
