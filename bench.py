@@ -165,35 +165,53 @@ def main():
 
 
 def extra_layer_set(q, synth, torch, dev):
-    """One pass over the seven linear layers of a Llama-3-8B-shaped block, distinct buffers, batch 1 (stderr)."""
+    """One pass over the seven linear layers of a Llama-3-8B-shaped block (four distinct copies) and of a
+    Llama-3-70B-shaped block, distinct buffers, batch 1; then the bulk decode of the 70B-shaped block to bf16 (stderr)."""
     import numpy as np
-    layers = []
-    tot = 0
-    for rep in range(4):
-        for i, (name, (N, K)) in enumerate(synth.LLAMA3_8B.items()):
-            KB = synth.blocks_per_row(K)
-            r = synth.rng_for(3, 10 * rep + i)
-            idx = torch.from_numpy(synth.pack_u48(synth.indices(r, (N, KB))).reshape(-1)).to(dev)
-            gain = torch.from_numpy(synth.gains(r, (N, KB)).reshape(-1)).to(dev)
-            x = torch.from_numpy(synth.activations(r, 1, K).astype(np.float16)).to(dev)
-            y = torch.empty((1, N), dtype=torch.float32, device=dev)
-            layers.append((name, x, idx, gain, N, KB, y))
-            tot += N * KB
-    for _ in range(2):
-        for (_, x, idx, gain, N, KB, y) in layers:
-            q.llvq_matmul(x, idx, gain, N, KB, out=y)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 5
-    e0.record()
-    for _ in range(reps):
-        for (_, x, idx, gain, N, KB, y) in layers:
-            q.llvq_matmul(x, idx, gain, N, KB, out=y)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / reps
-    print("llama3-8b layer set x4 (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed" % (tot * 8 / 1e6, ms, tot * 8 / ms / 1e6),
-          file=sys.stderr)
+    for label, shapes, copies in (("llama3-8b", synth.LLAMA3_8B, 4), ("llama3-70b", synth.LLAMA3_70B, 1)):
+        layers = []
+        tot = 0
+        for rep in range(copies):
+            for i, (name, (N, K)) in enumerate(shapes.items()):
+                KB = synth.blocks_per_row(K)
+                r = synth.rng_for(3 if copies > 1 else 5, 10 * rep + i)
+                idx = torch.from_numpy(synth.pack_u48(synth.indices(r, (N, KB))).reshape(-1)).to(dev)
+                gain = torch.from_numpy(synth.gains(r, (N, KB)).reshape(-1)).to(dev)
+                x = torch.from_numpy(synth.activations(r, 1, K).astype(np.float16)).to(dev)
+                y = torch.empty((1, N), dtype=torch.float32, device=dev)
+                layers.append((name, x, idx, gain, N, KB, y))
+                tot += N * KB
+        for _ in range(2):
+            for (_, x, idx, gain, N, KB, y) in layers:
+                q.llvq_matmul(x, idx, gain, N, KB, out=y)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 5
+        e0.record()
+        for _ in range(reps):
+            for (_, x, idx, gain, N, KB, y) in layers:
+                q.llvq_matmul(x, idx, gain, N, KB, out=y)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        print("%s layer set x%d (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed, %.2f G blocks/s" %
+              (label, copies, tot * 8 / 1e6, ms, tot * 8 / ms / 1e6, tot / ms / 1e6), file=sys.stderr)
+        if copies == 1:
+            outs = [torch.empty((N * KB, 24), dtype=torch.bfloat16, device=dev) for (_, _, _, _, N, KB, _) in layers]
+            for (_, _, idx, gain, N, KB, _), o in zip(layers, outs):
+                q.llvq_decode(idx, gain, out_dtype=torch.bfloat16, out=o)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                for (_, _, idx, gain, N, KB, _), o in zip(layers, outs):
+                    q.llvq_decode(idx, gain, out_dtype=torch.bfloat16, out=o)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            print("%s bulk decode of the block to bf16 (%d blocks): %.3f ms, %.2f G blocks/s, read+write %.1f GB/s" %
+                  (label, tot, ms, tot / ms / 1e6, tot * 56 / ms / 1e6), file=sys.stderr)
+            del outs
+        del layers
 
 
 SWEEP_SHAPES = ((1, 1), (256, 1), (256, 64), (256, 171), (512, 171), (1024, 171), (2048, 171), (4096, 171), (8192, 171),
