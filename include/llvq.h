@@ -102,7 +102,8 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
  *   d_y   : [M][N] row-major fp32, overwritten
  * 1 <= M <= 1024.  M = 1 is the decode (matrix-vector) case the paper times.
  * M <= 2: products activation * integer coordinate are exact in fp32, accumulated in fp32 and scaled by
- *   gain / sqrt(16 m) per block (v_dot2 kernel).
+ *   gain / sqrt(16 m) per block (v_dot2 kernel); the partial sums of a row are combined with fp32 atomic adds in
+ *   LDS, so the last bits of y can differ between calls (about 1e-7 relative).
  * M >= 3 (batched decode, prefill): the weights gain * x / sqrt(16 m) are rounded to the activation type
  *   (fp16: relative 2^-10, bf16: 2^-9) and contracted on the matrix cores with fp32 accumulation; partial sums
  *   of different K ranges are combined with fp32 atomic adds, so the last bits of y can differ between calls.

@@ -288,3 +288,41 @@ def test_smaller_ball_cuts(m_max):
         ref = o.matmul(xs, idx2, gain)
         assert np.abs(y - ref).max() / np.abs(ref).max() <= TOL
     g.close()
+
+
+def test_matmul_calls_can_be_captured_in_a_graph(gpu, oracle13):
+    """several llvq_matmul calls (both kernels) recorded into a HIP graph: every replay, with eager work and
+    synchronisations in between, reproduces the eager result up to the order of the fp32 atomic adds"""
+    import torch
+    cases = []
+    for i, (N, K, M) in enumerate([(512, 4096, 1), (300, 1000, 2), (256, 960, 16)]):
+        idx, gain, x = synth.layer(6, 2000 + i, N, K, M)
+        KB = idx.shape[1]
+        cases.append((_dev(x).half(), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), N, KB,
+                      torch.empty((M, N), dtype=torch.float32, device="cuda:0"), oracle13.matmul(x, idx, gain)))
+
+    def run():
+        for (x, idx, gain, N, KB, y, _) in cases:
+            gpu.llvq_matmul(x, idx, gain, N, KB, out=y)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [c[5].clone() for c in cases]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(4):
+        for c in cases:
+            c[5].fill_(float(rep))                      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for want, c in zip(eager, cases):
+            got = c[5]
+            assert float((got - want).abs().max()) <= 2e-6 * float(want.abs().max())
+            assert np.abs(got.cpu().numpy() - c[6]).max() / np.abs(c[6]).max() <= TOL
