@@ -24,14 +24,16 @@ namespace llvq {
 // The tables are addressed as `base + constant offset + key`; on the device `base` is the start of LDS and
 // the constant folds into the offset field of the LDS instruction.
 struct TabPtrs {
-    const unsigned char* base;
+    const unsigned char* base;     // LDS-resident part of the blob
+    const unsigned char* gbase;    // the whole blob in global memory (for kernels that keep only its first part in LDS)
     uint32_t ncls;
     uint64_t npoints;
 };
 
-LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const TableLayout& L) {
+LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const unsigned char* gbase, const TableLayout& L) {
     TabPtrs T;
     T.base = base;
+    T.gbase = gbase;
     T.ncls = L.ncls;
     T.npoints = L.npoints;
     return T;
@@ -41,6 +43,12 @@ LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const TableLayout& L) {
 template <typename V, uint32_t OFF>
 LLVQ_HD V tab_at(const TabPtrs& T, uint32_t byte_off) {
     return *reinterpret_cast<const V*>(T.base + OFF + byte_off);
+}
+
+// the same for the tables that stay in global memory
+template <typename V, uint32_t OFF>
+LLVQ_HD V gtab_at(const TabPtrs& T, uint32_t byte_off) {
+    return *reinterpret_cast<const V*>(T.gbase + OFF + byte_off);
 }
 
 LLVQ_HD uint32_t popc32(uint32_t v) {
@@ -124,6 +132,8 @@ struct Front {
     float rnorm;
 };
 
+// BIG_GLOBAL: the Golay words and the inner-word planes are read from global memory instead of LDS
+template <bool BIG_GLOBAL = false>
 LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     Front F;
     const ClassRec R = tab_at<ClassRec, kOffCls>(T, hit.cid * (uint32_t)sizeof(ClassRec));
@@ -145,9 +155,10 @@ LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     F.d = (uint32_t)dd;
     const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
     const uint32_t rho1 = rem - rin * R.P1;
-    F.c = tab_at<uint32_t, kOffGs>(T, (((f1 >> F1_GOFF) & 4095u) + r) * 4u);
-    F.e0 = tab_at<uint32_t, kOffInner>(T, (R.tb0 + rin) * 4u);
-    F.e1 = tab_at<uint32_t, kOffInner>(T, (R.tb1 + rho1) * 4u);
+    const uint32_t oc = (((f1 >> F1_GOFF) & 4095u) + r) * 4u, o0 = (R.tb0 + rin) * 4u, o1 = (R.tb1 + rho1) * 4u;
+    F.c = BIG_GLOBAL ? gtab_at<uint32_t, kOffGs>(T, oc) : tab_at<uint32_t, kOffGs>(T, oc);
+    F.e0 = BIG_GLOBAL ? gtab_at<uint32_t, kOffInner>(T, o0) : tab_at<uint32_t, kOffInner>(T, o0);
+    F.e1 = BIG_GLOBAL ? gtab_at<uint32_t, kOffInner>(T, o1) : tab_at<uint32_t, kOffInner>(T, o1);
     const uint32_t j = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * kGuessBuckets + (F.d >> ((f1 >> F1_GSHIFT) & 31u)));
     F.sp_j = (uint32_t)(uint16_t)(R.sp + j) | (j << 16);
     F.cid = hit.cid; F.f0 = f0; F.f1 = f1;

@@ -100,8 +100,8 @@ template <int FMT>
 __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                              const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
-    load_tables(blob, lay.lds_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    load_tables(blob, lay.blob_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
         uint64_t I;
         uint16_t gdummy;
@@ -138,8 +138,8 @@ template <int FMT, int OUT>
 __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                            const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                            Code cd, size_t n, void* __restrict__ out) {
-    load_tables(blob, lay.lds_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    load_tables(blob, lay.blob_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
         uint64_t I;
         uint16_t gb;
@@ -224,8 +224,8 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
     }
     // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
-    load_tables(blob, lay.lds_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    load_tables(blob, lay.lds_bytes);      // the Golay words and inner-word planes are read from global memory
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kRowsPerPass][kMaxMChunk]
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
@@ -252,7 +252,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             };
             auto front_of = [&](const Fetch& f, bool& ok) {
                 ok = f.live && f.I < T.npoints;
-                return llvq::decode_front(T, llvq::find_class(T, ok ? f.I : 0));
+                return llvq::decode_front<true>(T, llvq::find_class(T, ok ? f.I : 0));
             };
             const uint32_t stride = kWaves * 64;
             uint32_t base = (uint32_t)wave * 64;
@@ -397,8 +397,8 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
                                                         const uint32_t* __restrict__ x, int M, int N, int KB,
                                                         Code cd, uint32_t steps_per_wave, float* __restrict__ y) {
     constexpr int kWavesHere = THREADS / 64;
-    load_tables<THREADS>(blob, lay.lds_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, lay);
+    load_tables<THREADS>(blob, lay.blob_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
     // steps (row tile, block pair) are numbered row tile major and dealt to the waves of the grid as contiguous ranges
@@ -597,7 +597,7 @@ int grid_for(const llvq_ctx* ctx, size_t n) {
 
 template <int FMT>
 static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
-    const size_t lds = ctx->lay.lds_bytes;
+    const size_t lds = ctx->lay.blob_bytes;
     const int grid = grid_for(ctx, n);
     if (int rc = set_lds(ctx, decode_i8_kernel<FMT>, lds)) return rc;
     hipLaunchKernelGGL(decode_i8_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
@@ -607,7 +607,7 @@ static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, si
 
 template <int FMT>
 static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, const Code& cd, size_t n, void* d_out, int out_dtype, hipStream_t st) {
-    const size_t lds = ctx->lay.lds_bytes;
+    const size_t lds = ctx->lay.blob_bytes;
     const int grid = grid_for(ctx, n);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
 #define LLVQ_LAUNCH_DQ(OUT)                                                                                     \
@@ -646,7 +646,7 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
     uint32_t spw = (total + waves - 1) / waves;
     if (spw < 2) spw = 2;                                               // amortise the write-back of a partial tile
     const int grid = (int)((total + spw * wpg - 1) / (spw * wpg));
-    const size_t lds = ctx->lay.lds_bytes;
+    const size_t lds = ctx->lay.blob_bytes;
     if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES>, lds)) return rc;
     hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(grid), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, spw, d_y);
@@ -801,7 +801,7 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     ctx->num_cu = prop.multiProcessorCount;
     constexpr size_t kScratch = (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);    // the largest kernel scratch beside the tables
-    if (tabs.lay.lds_bytes + kScratch > prop.sharedMemPerBlock && tabs.lay.lds_bytes + kScratch > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
+    if (tabs.lay.blob_bytes + kScratch > prop.sharedMemPerBlock && tabs.lay.blob_bytes + kScratch > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
     if ((e = hipMalloc(&ctx->d_blob, tabs.blob.size())) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     if ((e = hipMalloc(&ctx->d_counter, sizeof(unsigned long long))) != hipSuccess) { (void)hipFree(ctx->d_blob); delete ctx; return LLVQ_EHIP; }
     if ((e = hipMemcpy(ctx->d_blob, tabs.blob.data(), tabs.blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {

@@ -435,7 +435,7 @@ bool build_tables(int m_max, Tables& out) {
     TableLayout lay{};
     const uint32_t inner_end = kOffInner + (uint32_t)(inner.size() * sizeof(uint32_t));
     if (guess.size() > kOffAtab - kOffGuess || cls_off.size() * 8 > kOffRnorm - kOffClsOff ||
-        (split.size() + 1) * sizeof(SplitEnt) > kOffCls - kOffSplit || recs.size() * sizeof(ClassRec) > kOffInner - kOffCls ||
+        (split.size() + 1) * sizeof(SplitEnt) > kOffCls - kOffSplit || recs.size() * sizeof(ClassRec) > kLdsBytes - kOffCls ||
         inner_end > kMaxBlob)
         return false;
     std::vector<unsigned char> blob((inner_end + 15u) & ~15u, 0);
@@ -454,7 +454,8 @@ bool build_tables(int m_max, Tables& out) {
     put(kOffSplit, split.data(), split.size() * sizeof(SplitEnt));
     put(kOffCls, recs.data(), recs.size() * sizeof(ClassRec));
     put(kOffInner, inner.data(), inner.size() * 4);
-    lay.lds_bytes = (uint32_t)blob.size();
+    lay.lds_bytes = kLdsBytes;
+    lay.blob_bytes = (uint32_t)blob.size();
     lay.ncls = ncls;
     lay.inner_entries = (uint32_t)inner.size();
     lay.npoints = running;

@@ -53,30 +53,34 @@ struct alignas(16) SplitEnt {
 };
 static_assert(sizeof(SplitEnt) == 16, "SplitEnt layout");
 
-// Fixed byte offsets of the tables inside the blob (and inside LDS, where kernels copy the blob verbatim).
-// They are compile-time constants so that the kernels can fold them into the offset field of the LDS
-// instructions; the small, frequently read tables sit below 64 KB, the reach of that field.
-constexpr uint32_t kOffGs      = 0;        // 4096 x u32
-constexpr uint32_t kOffSpread6 = 16384;    // 4096 x u32
-constexpr uint32_t kOffPdep6   = 32768;    // 4096 x u8
-constexpr uint32_t kOffLut12   = 36864;    // 4096 x u16
-constexpr uint32_t kOffBucket  = 45056;    // 4096 x u16
-constexpr uint32_t kOffGuess   = 53248;    // up to 48 rows x 64 x u8
-constexpr uint32_t kOffAtab    = 56320;    // 4 x {A, 1/A} doubles
-constexpr uint32_t kOffClsOff  = 56384;    // (ncls + 1) x u64, ncls <= 383
-constexpr uint32_t kOffRnorm   = 59456;    // 16 x float: 1/sqrt(16 m)
-constexpr uint32_t kOffSplit   = 59520;    // up to 352 x SplitEnt
-constexpr uint32_t kOffCls     = 65152;    // ncls x ClassRec
-constexpr uint32_t kOffInner   = 83552;    // inner-word planes, u32
-constexpr uint32_t kMaxBlob    = 162816;   // 159 KB; the last KB of the 160 KB of LDS is kernel scratch
+// Fixed byte offsets of the tables inside the blob.  The first kLdsBytes of the blob are copied verbatim into LDS
+// by every kernel; the offsets are compile-time constants so that the kernels can fold them into the offset field
+// of the LDS instructions.  The two large tables that are read once or twice per block (the sorted Golay words and
+// the inner-word planes) come last: a kernel either copies the whole blob into LDS or only the first kLdsBytes and
+// reads those two through the vector L1/L2 (a shorter table copy per launch, at the price of three global gathers
+// per block).
+constexpr uint32_t kOffSpread6 = 0;        // 4096 x u32
+constexpr uint32_t kOffPdep6   = 16384;    // 4096 x u8
+constexpr uint32_t kOffLut12   = 20480;    // 4096 x u16
+constexpr uint32_t kOffBucket  = 28672;    // 4096 x u16
+constexpr uint32_t kOffGuess   = 36864;    // up to 48 rows x 64 x u8
+constexpr uint32_t kOffAtab    = 39936;    // 4 x {A, 1/A} doubles
+constexpr uint32_t kOffClsOff  = 40000;    // (ncls + 1) x u64, ncls <= 383
+constexpr uint32_t kOffRnorm   = 43072;    // 16 x float: 1/sqrt(16 m)
+constexpr uint32_t kOffSplit   = 43136;    // up to 352 x SplitEnt
+constexpr uint32_t kOffCls     = 48768;    // ncls x ClassRec
+constexpr uint32_t kLdsBytes   = 67168;    // end of the LDS-resident part
+constexpr uint32_t kOffGs      = 67168;    // 4096 x u32 (global memory)
+constexpr uint32_t kOffInner   = 83552;    // inner-word planes, u32 (global memory)
+constexpr uint32_t kMaxBlob    = 83552 + 4 * 65536;   // the inner-word table bases are 16-bit entry numbers
 constexpr uint32_t kBucketShift = 36;      // bucket index = I >> 36 (4096 buckets cover 48 bits)
 constexpr uint32_t kGuessBuckets = 64;     // buckets of the subset-split guess table per (n, q)
 
 struct TableLayout {
-    uint32_t lds_bytes;      // bytes of the blob = bytes resident in LDS
+    uint32_t lds_bytes;      // first part of the blob: the tables every kernel keeps in LDS
+    uint32_t blob_bytes;     // the whole blob (kernels that want all tables in LDS copy this many bytes)
     uint32_t ncls;
     uint32_t inner_entries;
-    uint32_t pad;
     uint64_t npoints;        // N(m_max)
 };
 

@@ -18,14 +18,14 @@ int emul_init(int m_max) {
     return g_ok ? 0 : -1;
 }
 
-uint32_t emul_lds_bytes() { return g_tabs.lay.lds_bytes; }
+uint32_t emul_lds_bytes() { return g_tabs.lay.blob_bytes; }     // the most any kernel copies into LDS
 uint32_t emul_num_classes() { return g_tabs.lay.ncls; }
 uint64_t emul_num_points() { return g_tabs.lay.npoints; }
 uint32_t emul_inner_entries() { return g_tabs.lay.inner_entries; }
 
 // returns the number of out-of-range indices (decoded to zero)
 uint64_t emul_decode_i8(const uint64_t* idx, uint64_t n, int8_t* out) {
-    const llvq::TabPtrs T = llvq::make_tab_ptrs(g_tabs.blob.data(), g_tabs.lay);
+    const llvq::TabPtrs T = llvq::make_tab_ptrs(g_tabs.blob.data(), g_tabs.blob.data(), g_tabs.lay);
     uint64_t bad = 0;
     for (uint64_t k = 0; k < n; k++) {
         if (idx[k] >= T.npoints) { bad++; std::memset(out + 24 * k, 0, 24); continue; }
