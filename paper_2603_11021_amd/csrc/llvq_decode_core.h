@@ -102,17 +102,21 @@ struct ClassHit {
 };
 
 LLVQ_HD ClassHit find_class(const TabPtrs& T, uint64_t I) {
+    // the bucket of the top bits names the class of the bucket's first index; the class of I is that one or one of
+    // the next few.  Three candidates are tested per round (their offsets are read together), so that the rare lane
+    // whose bucket spans several small classes does not make its whole wavefront wait for one table read per class.
     uint32_t cid = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I >> kBucketShift) * 2u);
     uint64_t off = tab_at<uint64_t, kOffClsOff>(T, cid * 8u);
-    uint64_t nxt = tab_at<uint64_t, kOffClsOff + 8>(T, cid * 8u);
     for (;;) {
-        const bool more = I >= nxt && cid + 1 < T.ncls;
-        if (more) {
-            cid++;
-            off = nxt;
-            nxt = tab_at<uint64_t, kOffClsOff + 8>(T, cid * 8u);
-        }
-        if (!wave_or(more)) break;
+        const uint32_t last = T.ncls;                       // offset[ncls] = npoints > I: never passed
+        const uint32_t c1 = cid + 1 < last ? cid + 1 : last, c2 = cid + 2 < last ? cid + 2 : last, c3 = cid + 3 < last ? cid + 3 : last;
+        const uint64_t o1 = tab_at<uint64_t, kOffClsOff>(T, c1 * 8u);
+        const uint64_t o2 = tab_at<uint64_t, kOffClsOff>(T, c2 * 8u);
+        const uint64_t o3 = tab_at<uint64_t, kOffClsOff>(T, c3 * 8u);
+        const bool p1 = I >= o1, p2 = I >= o2, p3 = I >= o3;     // monotone: p3 implies p2 implies p1
+        off = p3 ? o3 : (p2 ? o2 : (p1 ? o1 : off));
+        cid = p3 ? c3 : (p2 ? c2 : (p1 ? c1 : cid));
+        if (!wave_or(p3)) break;
     }
     ClassHit h;
     h.cid = cid;
