@@ -95,6 +95,43 @@ __device__ __forceinline__ void load_block(const void* __restrict__ idx, const u
     I = (v & cd.mask) + cd.base;
 }
 
+// The same in two steps for software-pipelined loops: load_raw only issues the loads (nothing in it depends on a
+// loaded value, so no wait is placed there), finish_block turns the loaded pieces into (index, gain) where they are used.
+struct RawBlock {
+    uint32_t a, b, c;          // pieces of the stored word as loaded
+    uint16_t g;                // per-block gain as loaded
+};
+
+template <int FMT>
+__device__ __forceinline__ void load_raw(const void* __restrict__ idx, const uint16_t* __restrict__ gain, bool gain_array, size_t k,
+                                         RawBlock& r) {
+    r.a = r.b = r.c = 0;
+    if constexpr (FMT == LLVQ_IDX_U64) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(idx) + 2 * k;
+        r.a = p[0]; r.b = p[1];
+    } else if constexpr (FMT == LLVQ_IDX_U24) {
+        const uint8_t* p = reinterpret_cast<const uint8_t*>(idx) + 3 * k;
+        r.a = p[0]; r.b = p[1]; r.c = p[2];
+    } else {
+        // one 4-byte load (2-byte aligned) and one 2-byte load: the pieces stay as loaded until finish_block
+        typedef uint32_t u32_align2 __attribute__((aligned(2)));
+        const unsigned char* p = reinterpret_cast<const unsigned char*>(idx) + 6 * k;
+        r.a = *reinterpret_cast<const u32_align2*>(p);
+        r.c = *reinterpret_cast<const uint16_t*>(p + 4);
+    }
+    r.g = gain_array ? gain[k] : (uint16_t)0;
+}
+
+template <int FMT>
+__device__ __forceinline__ void finish_block(const RawBlock& r, const Code& cd, uint64_t& I, uint16_t& g) {
+    uint64_t v;
+    if constexpr (FMT == LLVQ_IDX_U64) v = ((uint64_t)r.a | ((uint64_t)r.b << 32)) & 0xFFFFFFFFFFFFull;
+    else if constexpr (FMT == LLVQ_IDX_U24) v = (uint64_t)(r.a | (r.b << 8) | (r.c << 16));
+    else v = (uint64_t)r.a | ((uint64_t)r.c << 32);
+    g = cd.lut ? cd.lut[min((uint32_t)(v >> cd.shape_bits), cd.lut_last)] : r.g;
+    I = (v & cd.mask) + cd.base;
+}
+
 // ---- llvq_decode_i8 ---------------------------------------------------------------------------------
 template <int FMT>
 __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
@@ -240,7 +277,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             // a wave takes every 16th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
             // the next batch are requested before this one is decoded, and the next batch's class search and digit
             // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
-            struct Fetch { uint64_t I; uint32_t row, b; uint16_t g; bool live; };
+            struct Fetch { RawBlock raw; uint32_t row, b; uint16_t g; bool live; };
             auto fetch = [&](uint32_t base, Fetch& f) {
                 const uint32_t fb = base + lane;
                 f.live = fb < nblk;
@@ -248,11 +285,13 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
                 f.row = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
                 f.b = fbc - f.row * (uint32_t)KB;
-                load_block<FMT>(idx, gain, cd, blk0 + fbc, f.I, f.g);
+                load_raw<FMT>(idx, gain, cd.lut == nullptr, blk0 + fbc, f.raw);
             };
-            auto front_of = [&](const Fetch& f, bool& ok) {
-                ok = f.live && f.I < T.npoints;
-                return llvq::decode_front<true>(T, llvq::find_class(T, ok ? f.I : 0));
+            auto front_of = [&](Fetch& f, bool& ok) {
+                uint64_t I;
+                finish_block<FMT>(f.raw, cd, I, f.g);
+                ok = f.live && I < T.npoints;
+                return llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
             };
             const uint32_t stride = kWaves * 64;
             uint32_t base = (uint32_t)wave * 64;
