@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <rocblas/rocblas.h>
+#include <type_traits>
 
 #include <cstdio>
 #include <algorithm>
@@ -302,9 +303,12 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 fetch(base, cur);
                 front_cur = front_of(cur, ok_cur);
             }
-            for (; base < nblk; base += stride) {
-                const bool more = base + stride < nblk;
-                if (more) fetch(base + stride, nxt);
+            // one batch: kMore says whether another batch follows.  The two cases are separate copies of the code so that
+            // each is straight-line with respect to its memory operations: a load inside a branch would make every later
+            // wait count as if it had not been issued, i.e. wait for newer loads than it needs
+            auto batch = [&](auto more_tag) {
+                constexpr bool kMore = decltype(more_tag)::value;
+                if constexpr (kMore) fetch(base + stride, nxt);
                 u32x4 xq[1][3];
                 {
                     const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)m0 * xpitch + (size_t)cur.b * 12);
@@ -313,7 +317,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 uint32_t w[1][4];
                 llvq::BlockInfo bi[1];
                 bi[0] = llvq::decode_back(T, front_cur, w[0]);
-                if (more) front_nxt = front_of(nxt, ok_nxt);
+                if constexpr (kMore) front_nxt = front_of(nxt, ok_nxt);
                 {
                     constexpr int u = 0;
                     const uint32_t vt_lo = bi[u].vt8_lo, vt_hi = bi[u].vt8_hi;
@@ -368,10 +372,14 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                         }
                     }
                 }
+            };
+            for (; base + stride < nblk; base += stride) {
+                batch(std::true_type{});
                 cur = nxt;
                 front_cur = front_nxt;
                 ok_cur = ok_nxt;
             }
+            if (base < nblk) batch(std::false_type{});
             __syncthreads();
             for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
                 const int rr = i / mc, mi = i - rr * mc;
