@@ -193,7 +193,6 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
     const uint32_t rk_lo = dl - rk_hi * e.div;
     const uint32_t U = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12lo + rk_lo) * 2u) |
                        ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12hi + rk_hi) * 2u) << 12);
-    const bool any_b1 = wave_any((F.e1 >> 16) != 0);                      // a third F1 value (10) is rare
 
     BlockInfo info;
     const uint32_t f0 = F.f0;
@@ -229,8 +228,7 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
             const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
             const uint32_t cx = cmk * 0x104u, ux = uk * 0x104u, sx = smk * 0x104u;
             const uint32_t gA1 = spread6_at(T, cx, a1, o1);
-            uint32_t gB = 0;
-            if (any_b1) gB = spread6_at(T, cx, b1, o1);
+            uint32_t gB = spread6_at(T, cx, b1, o1);
             o1 += popc32(cmk);
             const uint32_t gA0 = spread6_at(T, ux, a0, o0);
             gB |= spread6_at(T, ux, b0, o0);

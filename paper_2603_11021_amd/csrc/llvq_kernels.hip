@@ -120,7 +120,10 @@ __device__ __forceinline__ void load_raw(const void* __restrict__ idx, const uin
         r.a = *reinterpret_cast<const u32_align2*>(p);
         r.c = *reinterpret_cast<const uint16_t*>(p + 4);
     }
-    r.g = gain_array ? gain[k] : (uint16_t)0;
+    // always a load (from the index array itself when gains come from a table; the value is then ignored): a load under
+    // a condition would make later waits in a pipelined loop conservative
+    const uint16_t* gp = gain_array ? gain : reinterpret_cast<const uint16_t*>(idx);
+    r.g = gp[k];
 }
 
 template <int FMT>
