@@ -247,7 +247,9 @@ template <> struct Dot<bf16x2_t> {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int FMT, typename X2>
+// BIG_GLOBAL: only the small tables are copied into LDS and the Golay words and inner-word planes are read from global
+// memory (short launches, where the table copy is a visible share); otherwise the whole blob is copied (long launches).
+template <int FMT, typename X2, bool BIG_GLOBAL>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
@@ -265,9 +267,10 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
     }
     // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
-    load_tables(blob, lay.lds_bytes);      // the Golay words and inner-word planes are read from global memory
+    const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
+    load_tables(blob, table_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
-    float* ysum = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kRowsPerPass][kMaxMChunk]
+    float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     for (int r0 = wg_r0; r0 < wg_r1; r0 += kRowsPerPass) {
@@ -295,7 +298,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 uint64_t I;
                 finish_block<FMT>(f.raw, cd, I, f.g);
                 ok = f.live && I < T.npoints;
-                return llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
+                return llvq::decode_front<BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
             };
             const uint32_t stride = kWaves * 64;
             uint32_t base = (uint32_t)wave * 64;
@@ -679,11 +682,19 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     int grid = ctx->num_cu < N ? ctx->num_cu : N;
     const int rows = (N + grid - 1) / grid;
     grid = (N + rows - 1) / rows;
-    const size_t lds = ctx->lay.lds_bytes + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
     const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
-    if (int rc = set_lds(ctx, matmul_kernel<FMT, X2>, lds)) return rc;
-    hipLaunchKernelGGL((matmul_kernel<FMT, X2>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
+    // from about 256 batches of 64 blocks per compute unit on, copying all tables into LDS pays (measured on Llama-3-70B shapes)
+    const bool big_global = (size_t)N * (size_t)KB < (size_t)ctx->num_cu * 64 * 256;
+    const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
+    if (big_global) {
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true>, lds)) return rc;
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
+    } else {
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, false>, lds)) return rc;
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }
