@@ -143,10 +143,16 @@ __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char
                                                              uint32_t* __restrict__ out) {
     load_tables(blob, lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
-    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
+    // the next word is requested (always: past the end the last one is read again) before this block is decoded
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    RawBlock raw, raw_next;
+    if (k < n) load_raw<FMT>(idx, nullptr, false, k, raw);
+    for (; k < n; k += stride, raw = raw_next) {
+        load_raw<FMT>(idx, nullptr, false, min(k + stride, n - 1), raw_next);
         uint64_t I;
         uint16_t gdummy;
-        load_block<FMT>(idx, nullptr, cd, k, I, gdummy);
+        finish_block<FMT>(raw, cd, I, gdummy);
         const bool ok = I < T.npoints;
         uint32_t w[4], o[6];
         const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
@@ -181,10 +187,16 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
                                                            Code cd, size_t n, void* __restrict__ out) {
     load_tables(blob, lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
-    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
+    // the next word and gain are requested (always: past the end the last ones are read again) before this block is decoded
+    const size_t stride = (size_t)gridDim.x * kThreads;
+    size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    RawBlock raw, raw_next;
+    if (k < n) load_raw<FMT>(idx, gain, cd.lut == nullptr, k, raw);
+    for (; k < n; k += stride, raw = raw_next) {
+        load_raw<FMT>(idx, gain, cd.lut == nullptr, min(k + stride, n - 1), raw_next);
         uint64_t I;
         uint16_t gb;
-        load_block<FMT>(idx, gain, cd, k, I, gb);
+        finish_block<FMT>(raw, cd, I, gb);
         const bool ok = I < T.npoints;
         uint32_t w[4];
         const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
