@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
 ALU_PEAK_TLOPS = 39.3          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one vector instruction per lane and cycle
-VALU_PER_BLOCK = 478           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
-TRAFFIC_BYTES_PER_LAUNCH = 7141171  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
+VALU_PER_BLOCK = 455           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
+TRAFFIC_BYTES_PER_LAUNCH = 7202431  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
 
 
 def main():
@@ -153,7 +153,7 @@ def main():
         "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
         "max_rel_err_vs_oracle": err,
         "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "kernel": "matmul_kernel<U48,f16>", "kernel_ms": kern_ms,
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "kernel": "matmul_kernel<U48,f16,BIG_GLOBAL>", "kernel_ms": kern_ms,
                      "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk,
                      # the kernel is bound by the vector ALU work of the index decode, not by HBM: second roofline
                      "alu": {"achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
