@@ -1,8 +1,8 @@
 // gfx950 kernels and the C ABI of the LLVQ library (see include/llvq.h for the contract).
 //
-// Work decomposition: one lane decodes one 24-block.  All constant tables live in LDS (about 150 KB, one
-// 1024-thread workgroup per compute unit); every table access is an LDS gather, every other step is VALU
-// work on registers.  The fused product streams 8 bytes per block from HBM (6-byte index + fp16 gain),
+// Work decomposition: one lane decodes one 24-block.  The constant tables live in LDS (66 to 157 KB, one
+// 1024-thread workgroup per compute unit); a table access is an LDS gather (short launches of the batch-1 product
+// read the two largest tables from global memory instead), every other step is VALU work on registers.  The fused product streams 8 bytes per block from HBM (6-byte index + fp16 gain),
 // decodes the block into fp8-coded weights in registers, converts them pairwise to fp16 and feeds
 // v_dot2_f32_f16 against activations that consecutive lanes read as consecutive 48-byte runs.
 #include <hip/hip_runtime.h>
@@ -278,7 +278,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         load_block<FMT>(idx, gain, cd, k, warm_i, warm_g);
         asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
     }
-    // one workgroup per compute unit: the 150 KB of tables are loaded once per launch and workgroup
+    // one workgroup per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
     load_tables(blob, table_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
