@@ -326,3 +326,19 @@ def test_matmul_calls_can_be_captured_in_a_graph(gpu, oracle13):
             got = c[5]
             assert float((got - want).abs().max()) <= 2e-6 * float(want.abs().max())
             assert np.abs(got.cpu().numpy() - c[6]).max() / np.abs(c[6]).max() <= TOL
+
+
+@pytest.mark.parametrize("N,K,M", [(20000, 48, 1), (17000, 24, 2), (33000, 72, 1), (70, 24 * 300, 2), (16385, 96, 1)])
+def test_matmul_many_rows_per_workgroup(gpu, oracle13, N, K, M):
+    """more than 64 rows per workgroup (several passes over the LDS accumulators) and many rows per wave batch
+    (the segmented row reduction), and the opposite: a few very long rows"""
+    _matmul_case(gpu, oracle13, 6, 3000 + N % 97 + M, N, K, M)
+
+
+def test_matmul_random_small_shapes(gpu, oracle13):
+    rng = np.random.default_rng(77)
+    for case in range(24):
+        N = int(rng.integers(1, 400))
+        KB = int(rng.integers(1, 40))
+        M = int(rng.choice([1, 1, 2, 3, 5, 16, 33]))
+        _matmul_case(gpu, oracle13, 6, 4000 + case, N, 24 * KB - int(rng.integers(0, 24)) if KB > 1 else 24, M)
