@@ -324,6 +324,20 @@ def extra_shapes(q, synth, torch, dev):
     us = timeit(lambda: q.llvq_matmul_coded(x, w24, N, KB, 24, base, gain=gain, fmt=LLVQ_IDX_U24, out=y))
     print("matmul %dx%d M=1 single shell 3, 24-bit words + fp16 gain (5 B/block): %9.2f us  %.1f GB/s packed  %.2f G blocks/s" %
           (N, 24 * KB, us, n * 5 / us / 1e3, n / us / 1e3), file=sys.stderr)
+    # the configuration of the paper's own timing table (App. C): 4096 x 4104, single shell, 24-bit words, constant norm
+    Np, KBp = 4096, 171
+    one = torch.ones(1, dtype=torch.float16, device=dev)
+    ring = [torch.from_numpy(synth.pack_u24(r.integers(0, q.llvq_shell_offset(4) - base, size=Np * KBp, dtype=np.uint64)).reshape(-1)).to(dev)
+            for _ in range(64)]
+    xp = torch.from_numpy(synth.activations(r, 1, 4096)).to(dev).to(torch.float16)
+    yp = torch.empty((1, Np), dtype=torch.float32, device=dev)
+    turn = [0]
+    def paper_cfg():
+        turn[0] += 1
+        q.llvq_matmul_coded(xp, ring[turn[0] % 64], Np, KBp, 24, base, gain_lut=one, fmt=LLVQ_IDX_U24, out=yp)
+    us = timeit(paper_cfg, reps=256)
+    print("matmul 4096x4104 M=1 single shell 3, 24-bit words, one gain level (3 B/block, ring of 64 layers): %9.2f us "
+          "(the paper's App. C prints 11.94 us for this configuration on an unnamed NVIDIA GPU)" % us, file=sys.stderr)
 
 
 if __name__ == "__main__":

@@ -101,6 +101,11 @@ def test_single_shell_24bit_words(gpu, oracle13):
         x = synth.activations(rng, M, 24 * KB)
         y = gpu.llvq_matmul_coded(_dev(x).half(), d24, N, KB, 24, base, gain=_dev(gain.reshape(-1)), fmt=LLVQ_IDX_U24).cpu().numpy()
         assert _rel(y, oracle13.matmul(x, idx, gain)) <= (1e-5 if M <= 2 else TOL)
+    # no gain bits at all: a gain table with one level (constant-norm code, 3 bytes per block: the paper's App. C setting)
+    one = np.array([0.0123], dtype=np.float16)
+    x = synth.activations(rng, 1, 24 * KB)
+    y = gpu.llvq_matmul_coded(_dev(x).half(), d24, N, KB, 24, base, gain_lut=_dev(one), fmt=LLVQ_IDX_U24).cpu().numpy()
+    assert _rel(y, oracle13.matmul(x, idx, np.full(idx.shape, one[0], dtype=np.float16))) <= 1e-5
     # 23 shape bits + 1 gain bit inside the 24-bit word, over the first 2^23 points of the shell
     shape = synth.indices(rng, (N, KB), 1 << 23)
     code = rng.integers(0, 2, size=(N, KB), dtype=np.uint64)
