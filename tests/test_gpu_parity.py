@@ -342,3 +342,23 @@ def test_matmul_random_small_shapes(gpu, oracle13):
         KB = int(rng.integers(1, 40))
         M = int(rng.choice([1, 1, 2, 3, 5, 16, 33]))
         _matmul_case(gpu, oracle13, 6, 4000 + case, N, 24 * KB - int(rng.integers(0, 24)) if KB > 1 else 24, M)
+
+
+def test_calls_run_on_the_callers_stream(gpu, oracle13):
+    """work is enqueued on the stream that is passed in: results are ready after that stream is synchronised"""
+    import torch
+    idx, gain, x = synth.layer(6, 5000, 300, 960, 1)
+    KB = idx.shape[1]
+    d_x, d_idx, d_gain = _dev(x).half(), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    y = torch.zeros((1, 300), dtype=torch.float32, device="cuda:0")
+    out = torch.zeros((idx.size, 24), dtype=torch.int8, device="cuda:0")
+    torch.cuda.synchronize()
+    gpu.llvq_matmul(d_x, d_idx, d_gain, 300, KB, out=y, stream=side)
+    gpu.llvq_decode_i8(d_idx, out=out, stream=side)
+    side.synchronize()
+    ref = oracle13.matmul(x, idx, gain)
+    assert np.abs(y.cpu().numpy() - ref).max() / np.abs(ref).max() <= TOL
+    want, _ = oracle13.decode(idx.reshape(-1))
+    assert np.array_equal(out.cpu().numpy(), want)
