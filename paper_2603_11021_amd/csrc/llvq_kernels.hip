@@ -572,7 +572,7 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
 // ---- llvq_encode --------------------------------------------------------------------------------------
 // One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
 template <int FMT>
-__global__ void __launch_bounds__(kThreads) encode_kernel(const unsigned char* __restrict__ blob, llvq::EncLayout lay,
+__global__ void __launch_bounds__(kThreads, 8) encode_kernel(const unsigned char* __restrict__ blob, llvq::EncLayout lay,
                                                           const uint2* __restrict__ pts, size_t n, void* __restrict__ idx,
                                                           size_t out_stride) {
     load_tables(blob, lay.bytes);
@@ -730,7 +730,9 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
 template <int FMT>
 static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st, size_t out_stride = 1) {
     const size_t lds = ctx->enc_lay.bytes;
-    const int grid = grid_for(ctx, n);
+    // the encoder's tables take 68.5 KB: two workgroups share a compute unit (64 vector registers per lane)
+    const size_t wgs = (n + kThreads - 1) / kThreads;
+    const int grid = (int)std::max<size_t>(1, std::min<size_t>(wgs, (size_t)2 * ctx->num_cu));
     if (int rc = set_lds(ctx, encode_kernel<FMT>, lds)) return rc;
     hipLaunchKernelGGL(encode_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
                        reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
