@@ -137,11 +137,14 @@ __device__ __forceinline__ void finish_block(const RawBlock& r, const Code& cd, 
 }
 
 // ---- llvq_decode_i8 ---------------------------------------------------------------------------------
-template <int FMT>
-__global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+// BIG_GLOBAL as in matmul_kernel below: with the two big tables in global memory the LDS part is 66 KB and two
+// workgroups share a compute unit (eight waves per SIMD, 64 registers per lane), which wins on launches that are not
+// dominated by their HBM traffic
+template <int FMT, bool BIG_GLOBAL>
+__global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                              const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
-    load_tables(blob, lay.blob_bytes);
+    load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     // the next word is requested (always: past the end the last one is read again) before this block is decoded
     const size_t stride = (size_t)gridDim.x * kThreads;
@@ -155,7 +158,7 @@ __global__ void __launch_bounds__(kThreads) decode_i8_kernel(const unsigned char
         finish_block<FMT>(raw, cd, I, gdummy);
         const bool ok = I < T.npoints;
         uint32_t w[4], o[6];
-        const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
+        const llvq::BlockInfo bi = llvq::decode_back(T, llvq::decode_front<BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0)), w);
         llvq::nibbles_to_i8(w, bi.vti_lo, bi.vti_hi, o);
         uint2* dst = reinterpret_cast<uint2*>(out + 6 * k);
         dst[0] = ok ? make_uint2(o[0], o[1]) : make_uint2(0, 0);
@@ -181,11 +184,11 @@ __device__ __forceinline__ void chunk_fp8(uint32_t w, uint32_t vt_lo, uint32_t v
 }
 
 // ---- llvq_decode (shape-gain reconstruction) ------------------------------------------------------------
-template <int FMT, int OUT>
-__global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+template <int FMT, int OUT, bool BIG_GLOBAL>
+__global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                            const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                            Code cd, size_t n, void* __restrict__ out) {
-    load_tables(blob, lay.blob_bytes);
+    load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     // the next word and gain are requested (always: past the end the last ones are read again) before this block is decoded
     const size_t stride = (size_t)gridDim.x * kThreads;
@@ -199,7 +202,7 @@ __global__ void __launch_bounds__(kThreads) dequant_kernel(const unsigned char* 
         finish_block<FMT>(raw, cd, I, gb);
         const bool ok = I < T.npoints;
         uint32_t w[4];
-        const llvq::BlockInfo bi = llvq::decode_block(T, ok ? I : 0, w);
+        const llvq::BlockInfo bi = llvq::decode_back(T, llvq::decode_front<BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0)), w);
         const uint32_t vt_lo = bi.vt8_lo, vt_hi = bi.vt8_hi;
         const float g = __half2float(__ushort_as_half(gb));
         const float scale = ok ? g * bi.rnorm : 0.0f;
@@ -651,38 +654,49 @@ int set_lds(llvq_ctx* ctx, K kernel, size_t bytes) {
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "hipFuncSetAttribute");
 }
 
-int grid_for(const llvq_ctx* ctx, size_t n) {
-    // grid-stride kernels: one workgroup per compute unit at most, so that the tables are loaded once per CU
+int grid_for(const llvq_ctx* ctx, size_t n, int per_cu = 1) {
+    // grid-stride kernels: no more workgroups than fit the compute units at once, so that each copies the tables once
     size_t wgs = (n + kThreads - 1) / kThreads;
-    size_t cap = (size_t)ctx->num_cu;
+    size_t cap = (size_t)ctx->num_cu * per_cu;
     return (int)(wgs < 1 ? 1 : (wgs > cap ? cap : wgs));
 }
 
 }  // namespace
 
+// short launches keep only the small tables in LDS and run two workgroups per compute unit (see the kernels)
+static bool small_launch(const llvq_ctx* ctx, size_t n) { return n < (size_t)ctx->num_cu * 64 * 256; }
+
 template <int FMT>
 static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
-    const size_t lds = ctx->lay.blob_bytes;
-    const int grid = grid_for(ctx, n);
-    if (int rc = set_lds(ctx, decode_i8_kernel<FMT>, lds)) return rc;
-    hipLaunchKernelGGL(decode_i8_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
+    const bool small = small_launch(ctx, n);
+    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
+    const int grid = grid_for(ctx, n, small ? 2 : 1);
+    if (small) {
+        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, true>, lds)) return rc;
+        hipLaunchKernelGGL((decode_i8_kernel<FMT, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
+    } else {
+        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, false>, lds)) return rc;
+        hipLaunchKernelGGL((decode_i8_kernel<FMT, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "decode_i8 launch");
 }
 
 template <int FMT>
 static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, const Code& cd, size_t n, void* d_out, int out_dtype, hipStream_t st) {
-    const size_t lds = ctx->lay.blob_bytes;
-    const int grid = grid_for(ctx, n);
+    // fp32 output is bound by its stores: it always takes the one-workgroup variant
+    const bool small = small_launch(ctx, n) && out_dtype != LLVQ_F32;
+    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
+    const int grid = grid_for(ctx, n, small ? 2 : 1);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
-#define LLVQ_LAUNCH_DQ(OUT)                                                                                     \
-    do {                                                                                                          \
-        if (int rc = set_lds(ctx, dequant_kernel<FMT, OUT>, lds)) return rc;                                      \
-        hipLaunchKernelGGL((dequant_kernel<FMT, OUT>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, cd, n, d_out); \
+#define LLVQ_LAUNCH_DQ(OUT, BG)                                                                                    \
+    do {                                                                                                              \
+        if (int rc = set_lds(ctx, dequant_kernel<FMT, OUT, BG>, lds)) return rc;                                      \
+        hipLaunchKernelGGL((dequant_kernel<FMT, OUT, BG>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, cd, n, d_out); \
     } while (0)
-    if (out_dtype == LLVQ_F16) LLVQ_LAUNCH_DQ(LLVQ_F16);
-    else if (out_dtype == LLVQ_BF16) LLVQ_LAUNCH_DQ(LLVQ_BF16);
-    else LLVQ_LAUNCH_DQ(LLVQ_F32);
+    if (out_dtype == LLVQ_F16) { if (small) LLVQ_LAUNCH_DQ(LLVQ_F16, true); else LLVQ_LAUNCH_DQ(LLVQ_F16, false); }
+    else if (out_dtype == LLVQ_BF16) { if (small) LLVQ_LAUNCH_DQ(LLVQ_BF16, true); else LLVQ_LAUNCH_DQ(LLVQ_BF16, false); }
+    else LLVQ_LAUNCH_DQ(LLVQ_F32, false);
 #undef LLVQ_LAUNCH_DQ
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "dequant launch");
