@@ -69,7 +69,9 @@ def test_quantize_heavy_tailed_and_sparse_blocks(gpu, oracle13):
     a = rng.standard_t(2.5, size=(60, 24))                          # outliers, as in unrotated weights
     b = rng.standard_normal((60, 24)) * (rng.random((60, 24)) < 0.25)   # many exact zeros
     c = np.round(rng.standard_normal((60, 24)) * 2) / 2             # many ties
-    _check(gpu, oracle13, np.concatenate([a, b, c]), "angular", 0.9)
+    d = np.zeros((2, 24))                                           # no direction at all: any point is as good as any other
+    e = rng.standard_normal((6, 24)) * np.array([1e-12, 1e-6, 1e6, 1e12, 1e-3, 1e3])[:, None]   # scale does not matter
+    _check(gpu, oracle13, np.concatenate([a, b, c, d, e]), "angular", 0.9)
 
 
 def test_quantize_lattice_points_return_their_ray(gpu, oracle13):
