@@ -572,6 +572,116 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
     }
 }
 
+// ---- llvq_matmul, prefill kernel for large M: activations shared through LDS, no split along K -----------------
+// A workgroup of eight waves owns a strip of 256 weight rows (wave w: rows 32 w .. 32 w + 31 of the strip) and a pass of
+// 256 tokens, and walks all block pairs of the rows.  Per step the activation tile of the step (256 tokens x 48 channels)
+// is staged once in LDS and read by all eight waves as MFMA A operands, so it is fetched from L2 once per workgroup
+// instead of once per wave; the decoded blocks are the B operands straight from the decoder's registers as in
+// mfma_kernel.  A workgroup sees every channel of its rows, so y is written once with plain stores: no clearing, no
+// atomics, results reproducible.  Only the small tables are kept in LDS (the Golay words and inner-word planes are
+// read from global memory), which leaves room for two activation buffers.
+constexpr int kPrefillThreads = 512;
+constexpr int kPrefillTokens = 256;                    // tokens per pass = 8 tiles of 32
+constexpr int kPrefillRows = 256;                      // weight rows per strip = 8 tiles of 32
+constexpr uint32_t kATokenPitch = 104;                 // bytes per token in the staged tile: 96 of data, padded against bank conflicts
+constexpr uint32_t kABufBytes = kPrefillTokens * kATokenPitch;
+
+template <int FMT, typename X2>
+__global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                                   const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                                   const uint32_t* __restrict__ x, int M, int N, int KB, Code cd,
+                                                                   float* __restrict__ y) {
+    load_tables<kPrefillThreads>(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    unsigned char* abuf = g_lds + lay.lds_bytes;                         // two buffers of kABufBytes
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps (block pairs) per row
+    const int m0 = (int)blockIdx.y * kPrefillTokens;
+    const int wrow = (int)blockIdx.x * kPrefillRows + wave * 32 + col;    // weight row of this lane
+    const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
+
+    // staging role of this thread: token (thread / 2) of the pass, block (thread % 2) of the pair
+    const int s_tok = min(M - 1, m0 + (int)(threadIdx.x >> 1));
+    const uint32_t s_part = threadIdx.x & 1u;
+    const uint32_t* s_src = x + (size_t)s_tok * xpitch;
+    unsigned char* s_dst = abuf + (threadIdx.x >> 1) * kATokenPitch + s_part * 48u;
+    auto stage_load = [&](uint32_t st, uint4 (&v)[3]) {
+        const uint32_t b = min(2 * st + s_part, (uint32_t)KB - 1);       // past the last block: any valid data, its weights are zero
+        const uint4* p = reinterpret_cast<const uint4*>(s_src + (size_t)b * 12);
+        v[0] = p[0]; v[1] = p[1]; v[2] = p[2];
+    };
+    auto stage_store = [&](uint32_t buf, const uint4 (&v)[3]) {
+        uint2* d = reinterpret_cast<uint2*>(s_dst + buf * kABufBytes);
+        d[0] = make_uint2(v[0].x, v[0].y); d[1] = make_uint2(v[0].z, v[0].w);
+        d[2] = make_uint2(v[1].x, v[1].y); d[3] = make_uint2(v[1].z, v[1].w);
+        d[4] = make_uint2(v[2].x, v[2].y); d[5] = make_uint2(v[2].z, v[2].w);
+    };
+
+    float16_t acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; t++) {
+#pragma unroll
+        for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
+    }
+    {
+        uint4 v[3];
+        stage_load(0, v);
+        stage_store(0, v);
+    }
+    __syncthreads();
+    for (uint32_t st = 0; st < spt; st++) {
+        // the next step's activations travel while this step's blocks are decoded
+        uint4 nextv[3];
+        const bool more = st + 1 < spt;
+        stage_load(more ? st + 1 : st, nextv);
+        // this lane's block: row wrow, block 2 st + half
+        const uint32_t b = 2 * st + half;
+        const bool live = wrow < N && b < (uint32_t)KB;
+        const size_t k = (size_t)min(wrow, N - 1) * KB + min(b, (uint32_t)KB - 1);
+        uint64_t I;
+        uint16_t gb;
+        load_block<FMT>(idx, gain, cd, k, I, gb);
+        const float g = __half2float(__ushort_as_half(gb));
+        const bool ok = live && I < T.npoints;
+        uint32_t w[4];
+        const llvq::BlockInfo bi = llvq::decode_back(T, llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0)), w);
+        const float scale = ok ? g * bi.rnorm : 0.0f;
+        uint32_t wt[12];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            uint32_t fe, fo;
+            chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
+            wt[3 * c + 0] = Mma<X2>::scaled(fe, false, scale);
+            wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
+            wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
+        }
+        // A operands from the staged tile: token 32 t + col, the lane half's block (48 bytes), k group j
+        const unsigned char* arow = abuf + (st & 1u) * kABufBytes + (uint32_t)col * kATokenPitch + (uint32_t)half * 48u;
+#pragma unroll
+        for (int t = 0; t < 8; t++) {
+#pragma unroll
+            for (int j = 0; j < 6; j++) {
+                const uint2 a = *reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 8u);
+                acc[t] = Mma<X2>::mma(a.x, a.y, wt[2 * j], wt[2 * j + 1], acc[t]);
+            }
+        }
+        stage_store((st + 1) & 1u, nextv);
+        __syncthreads();
+    }
+    // y[token][wrow]: register v of tile t belongs to token m0 + 32 t + 8 (v / 4) + 4 half + v % 4
+    if (wrow < N) {
+#pragma unroll
+        for (int t = 0; t < 8; t++) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
+                if (tok < M) y[(size_t)tok * N + wrow] = acc[t][v];
+            }
+        }
+    }
+}
+
 // ---- llvq_encode --------------------------------------------------------------------------------------
 // One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
 template <int FMT>
@@ -774,8 +884,22 @@ static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n,
 }
 
 template <int FMT, typename X2>
+static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
+    const dim3 grid((unsigned)((N + kPrefillRows - 1) / kPrefillRows), (unsigned)((M + kPrefillTokens - 1) / kPrefillTokens));
+    const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kABufBytes;
+    if (int rc = set_lds(ctx, prefill_kernel<FMT, X2>, lds)) return rc;
+    hipLaunchKernelGGL((prefill_kernel<FMT, X2>), grid, dim3(kPrefillThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "prefill matmul launch");
+}
+
+template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    // the strip kernel needs about one workgroup per compute unit to pay: (N / 256) x (M / 256) workgroups
+    const size_t strip_wgs = (size_t)((N + kPrefillRows - 1) / kPrefillRows) * (size_t)((M + kPrefillTokens - 1) / kPrefillTokens);
+    if (M > 64 && strip_wgs * 5 >= (size_t)ctx->num_cu * 2) return launch_prefill<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);

@@ -201,7 +201,9 @@ def _round_to(a, kind):
 
 
 @pytest.mark.parametrize("name,M,xd", [("q", 64, "f16"), ("q", 64, "bf16"), ("k", 256, "bf16"), ("q", 1024, "bf16"),
-                                       ("down", 64, "bf16"), ("gate", 100, "f16")])
+                                       ("down", 64, "bf16"), ("gate", 100, "f16"),
+                                       # enough workgroups for the strip kernel (activations shared through LDS)
+                                       ("gate", 1024, "bf16"), ("gate", 520, "f16"), ("down", 700, "bf16")])
 def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
     """Config 4: the matrix-core path.  Weights enter the MFMA scaled and rounded to the activation type, so two
     errors are checked: against the exact fp64 oracle (the 2e-3 bar) and against the oracle whose dequantised
@@ -227,6 +229,12 @@ def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
 @pytest.mark.parametrize("N,K,M", [(33, 48, 3), (31, 24, 40), (100, 72, 65), (257, 24 * 7, 130), (64, 24 * 9, 300)])
 def test_mfma_ragged_shapes(gpu, oracle13, N, K, M):
     _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M)
+
+
+@pytest.mark.parametrize("N,K,M", [(13000, 72, 1024), (26001, 24, 300), (6700, 24 * 5 - 3, 1000)])
+def test_strip_prefill_ragged_shapes(gpu, oracle13, N, K, M):
+    """shapes that take the strip kernel with ragged strips (N not a multiple of 256), ragged passes, an odd block count"""
+    _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M, sample_rows=200)
 
 
 @pytest.mark.parametrize("name,M,xd", [("q", 96, "f16"), ("k", 256, "bf16"), ("q", 1024, "bf16"), ("gate", 130, "f16")])
