@@ -624,29 +624,41 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
 #pragma unroll
         for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
     }
+    // Software pipeline over the steps: the word of the next step is requested first, then this step's block is placed,
+    // then the next step's class search and digit extraction run (their reads from global memory are in flight during
+    // the matrix products), then the products of this step, then the next activation tile is put into LDS.
+    struct Blk { RawBlock raw; bool live; };
+    auto fetch_blk = [&](uint32_t st, Blk& q) {
+        const uint32_t b = 2 * st + half;
+        q.live = wrow < N && b < (uint32_t)KB;
+        const size_t k = (size_t)min(wrow, N - 1) * KB + min(b, (uint32_t)KB - 1);
+        load_raw<FMT>(idx, gain, cd.lut == nullptr, k, q.raw);
+    };
+    auto front_of = [&](const Blk& q, bool& ok, uint16_t& gb) {
+        uint64_t I;
+        finish_block<FMT>(q.raw, cd, I, gb);
+        ok = q.live && I < T.npoints;
+        return llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
+    };
     {
         uint4 v[3];
         stage_load(0, v);
         stage_store(0, v);
     }
+    Blk cur_blk, nxt_blk;
+    fetch_blk(0, cur_blk);
+    bool ok_cur = false, ok_nxt = false;
+    uint16_t g_cur = 0, g_nxt = 0;
+    llvq::Front F = front_of(cur_blk, ok_cur, g_cur), Fn;
     __syncthreads();
     for (uint32_t st = 0; st < spt; st++) {
-        // the next step's activations travel while this step's blocks are decoded
+        const uint32_t st_next = st + 1 < spt ? st + 1 : st;            // past the end the last step is requested again
         uint4 nextv[3];
-        const bool more = st + 1 < spt;
-        stage_load(more ? st + 1 : st, nextv);
-        // this lane's block: row wrow, block 2 st + half
-        const uint32_t b = 2 * st + half;
-        const bool live = wrow < N && b < (uint32_t)KB;
-        const size_t k = (size_t)min(wrow, N - 1) * KB + min(b, (uint32_t)KB - 1);
-        uint64_t I;
-        uint16_t gb;
-        load_block<FMT>(idx, gain, cd, k, I, gb);
-        const float g = __half2float(__ushort_as_half(gb));
-        const bool ok = live && I < T.npoints;
+        stage_load(st_next, nextv);
+        fetch_blk(st_next, nxt_blk);
         uint32_t w[4];
-        const llvq::BlockInfo bi = llvq::decode_back(T, llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0)), w);
-        const float scale = ok ? g * bi.rnorm : 0.0f;
+        const llvq::BlockInfo bi = llvq::decode_back(T, F, w);
+        const float scale = ok_cur ? __half2float(__ushort_as_half(g_cur)) * bi.rnorm : 0.0f;
         uint32_t wt[12];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
@@ -656,17 +668,22 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
             wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
             wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
         }
+        Fn = front_of(nxt_blk, ok_nxt, g_nxt);
         // A operands from the staged tile: token 32 t + col, the lane half's block (48 bytes), k group j
         const unsigned char* arow = abuf + (st & 1u) * kABufBytes + (uint32_t)col * kATokenPitch + (uint32_t)half * 48u;
+        // k group outermost: consecutive MFMAs go to different accumulators and do not wait for each other
 #pragma unroll
-        for (int t = 0; t < 8; t++) {
+        for (int j = 0; j < 6; j++) {
 #pragma unroll
-            for (int j = 0; j < 6; j++) {
+            for (int t = 0; t < 8; t++) {
                 const uint2 a = *reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 8u);
                 acc[t] = Mma<X2>::mma(a.x, a.y, wt[2 * j], wt[2 * j + 1], acc[t]);
             }
         }
         stage_store((st + 1) & 1u, nextv);
+        F = Fn;
+        ok_cur = ok_nxt;
+        g_cur = g_nxt;
         __syncthreads();
     }
     // y[token][wrow]: register v of tile t belongs to token m0 + 32 t + 8 (v / 4) + 4 half + v % 4
