@@ -442,12 +442,11 @@ template <> struct Mma<half2_t> {
 };
 template <> struct Mma<bf16x2_t> {
     static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
-        const uint32_t u = __builtin_bit_cast(uint32_t, fp8x2_to_bf16(fp8, hi));
-        const float f0 = __uint_as_float(u << 16) * scale, f1 = __uint_as_float(u & 0xFFFF0000u) * scale;
-        // round to nearest even (finite values)
-        uint32_t u0 = __float_as_uint(f0), u1 = __float_as_uint(f1);
-        u0 += 0x7FFFu + ((u0 >> 16) & 1u); u1 += 0x7FFFu + ((u1 >> 16) & 1u);
-        return (u0 >> 16) | (u1 & 0xFFFF0000u);
+        // fp8 pair -> fp32 pair, scale in fp32, round to nearest even with the hardware conversion
+        typedef float float2_t __attribute__((ext_vector_type(2)));
+        float2_t f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(fp8, true) : __builtin_amdgcn_cvt_pk_f32_fp8(fp8, false);
+        f *= scale;
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
     }
     static __device__ __forceinline__ float16_t mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float16_t c) {
         const uint2 av = make_uint2(a0, a1), bv = make_uint2(b0, b1);
