@@ -589,13 +589,16 @@ template <int FMT, typename X2>
 __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                                    const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                                    const uint32_t* __restrict__ x, int M, int N, int KB, Code cd,
-                                                                   float* __restrict__ y) {
+                                                                   int ksplit, float* __restrict__ y) {
     load_tables<kPrefillThreads>(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     unsigned char* abuf = g_lds + lay.lds_bytes;                         // two buffers of kABufBytes
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
-    const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps (block pairs) per row
+    // steps (block pairs) of a row; with ksplit > 1 the workgroups of blockIdx.z share them and add their parts to y
+    const uint32_t spt_all = ((uint32_t)KB + 1) / 2;
+    const uint32_t st_first = (uint32_t)(((uint64_t)spt_all * blockIdx.z) / (uint32_t)ksplit);
+    const uint32_t spt = (uint32_t)(((uint64_t)spt_all * (blockIdx.z + 1)) / (uint32_t)ksplit);      // one past this workgroup's last step
     const int m0 = (int)blockIdx.y * kPrefillTokens;
     const int wrow = (int)blockIdx.x * kPrefillRows + wave * 32 + col;    // weight row of this lane
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
@@ -641,16 +644,16 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
     };
     {
         uint4 v[3];
-        stage_load(0, v);
-        stage_store(0, v);
+        stage_load(st_first, v);
+        stage_store(st_first & 1u, v);
     }
     Blk cur_blk, nxt_blk;
-    fetch_blk(0, cur_blk);
+    fetch_blk(st_first, cur_blk);
     bool ok_cur = false, ok_nxt = false;
     uint16_t g_cur = 0, g_nxt = 0;
     llvq::Front F = front_of(cur_blk, ok_cur, g_cur), Fn;
     __syncthreads();
-    for (uint32_t st = 0; st < spt; st++) {
+    for (uint32_t st = st_first; st < spt; st++) {
         const uint32_t st_next = st + 1 < spt ? st + 1 : st;            // past the end the last step is requested again
         uint4 nextv[3];
         stage_load(st_next, nextv);
@@ -692,7 +695,10 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
-                if (tok < M) y[(size_t)tok * N + wrow] = acc[t][v];
+                if (tok < M) {
+                    if (ksplit == 1) y[(size_t)tok * N + wrow] = acc[t][v];
+                    else atomicAdd(y + (size_t)tok * N + wrow, acc[t][v]);
+                }
             }
         }
     }
@@ -901,11 +907,20 @@ static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n,
 
 template <int FMT, typename X2>
 static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    const dim3 grid((unsigned)((N + kPrefillRows - 1) / kPrefillRows), (unsigned)((M + kPrefillTokens - 1) / kPrefillTokens));
+    const unsigned strips = (unsigned)((N + kPrefillRows - 1) / kPrefillRows), passes = (unsigned)((M + kPrefillTokens - 1) / kPrefillTokens);
+    // enough workgroups for the chip: split the block pairs of a row among up to ksplit workgroups (at least 8 steps each)
+    const unsigned spt = ((unsigned)KB + 1) / 2;
+    unsigned ksplit = (unsigned)ctx->num_cu / (strips * passes);
+    ksplit = std::max(1u, std::min(ksplit, std::max(1u, spt / 8)));
+    if (ksplit > 1) {
+        const size_t ny = (size_t)M * N;
+        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+    }
+    const dim3 grid(strips, passes, ksplit);
     const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kABufBytes;
     if (int rc = set_lds(ctx, prefill_kernel<FMT, X2>, lds)) return rc;
     hipLaunchKernelGGL((prefill_kernel<FMT, X2>), grid, dim3(kPrefillThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, d_y);
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "prefill matmul launch");
 }
@@ -913,9 +928,7 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
 template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
-    // the strip kernel needs about one workgroup per compute unit to pay: (N / 256) x (M / 256) workgroups
-    const size_t strip_wgs = (size_t)((N + kPrefillRows - 1) / kPrefillRows) * (size_t)((M + kPrefillTokens - 1) / kPrefillTokens);
-    if (M > 64 && strip_wgs * 5 >= (size_t)ctx->num_cu * 2) return launch_prefill<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    if (M > 64) return launch_prefill<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
