@@ -107,7 +107,8 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
  * M >= 3 (batched decode, prefill): the weights gain * x / sqrt(16 m) are rounded to the activation type
  *   (fp16: relative 2^-10, bf16: 2^-9) and contracted on the matrix cores with fp32 accumulation; partial sums
  *   of different K ranges are combined with fp32 atomic adds, so the last bits of y can differ between calls
- *   (large launches, M > 64 with at least ~100 strips of 256 rows x 256 tokens, do not split K and are reproducible).
+ *   (launches with M > 64 and at least one strip of 256 rows x 256 tokens per compute unit do not split K and are
+ *   reproducible).
  *   Requires M*N < 2^32.                                                                               */
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,

@@ -457,7 +457,7 @@ template <> struct Mma<bf16x2_t> {
 constexpr int kGemmMinM = 96;       // from this many activation rows on, llvq_matmul_ws dequantises once and calls a dense GEMM
 constexpr int kMfmaMinM = 3;        // from this many activation rows on, llvq_matmul uses the MFMA kernel
 // THREADS x TOKTILES: more token tiles per pass over the weights need more accumulator registers, i.e. fewer
-// waves per SIMD: 1024 threads x 2 tiles (64 tokens per pass) or 512 threads x 8 tiles (256 tokens per pass)
+// waves per SIMD.  Used as 1024 threads x 2 tiles (64 tokens per pass) for 3 <= M <= 64; larger M takes prefill_kernel.
 template <int FMT, typename X2, int THREADS, int kTokTiles>
 __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                         const void* __restrict__ idx, const uint16_t* __restrict__ gain,
@@ -579,17 +579,17 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
 // mfma_kernel.  A workgroup sees every channel of its rows, so y is written once with plain stores: no clearing, no
 // atomics, results reproducible.  Only the small tables are kept in LDS (the Golay words and inner-word planes are
 // read from global memory), which leaves room for two activation buffers.
-constexpr int kPrefillThreads = 512;
-constexpr int kPrefillTokens = 256;                    // tokens per pass = 8 tiles of 32
-constexpr int kPrefillRows = 256;                      // weight rows per strip = 8 tiles of 32
+// Shape used: 8 waves x 8 token tiles (strips of 256 rows, passes of 256 tokens; 128 accumulator registers, two waves per
+// SIMD).  16 waves x 2 token tiles was measured for M <= 64 and lost to mfma_kernel (75.6 against 68 us on 14336 x 4104).
 constexpr uint32_t kATokenPitch = 104;                 // bytes per token in the staged tile: 96 of data, padded against bank conflicts
-constexpr uint32_t kABufBytes = kPrefillTokens * kATokenPitch;
 
-template <int FMT, typename X2>
-__global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+template <int FMT, typename X2, int WAVES, int TT>
+__global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                                    const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                                    const uint32_t* __restrict__ x, int M, int N, int KB, Code cd,
                                                                    int ksplit, float* __restrict__ y) {
+    constexpr int kPrefillThreads = 64 * WAVES, kPrefillTokens = 32 * TT, kPrefillRows = 32 * WAVES;
+    constexpr uint32_t kABufBytes = kPrefillTokens * kATokenPitch;
     load_tables<kPrefillThreads>(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
     unsigned char* abuf = g_lds + lay.lds_bytes;                         // two buffers of kABufBytes
@@ -604,25 +604,27 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     // staging role of this thread: token (thread / 2) of the pass, block (thread % 2) of the pair
-    const int s_tok = min(M - 1, m0 + (int)(threadIdx.x >> 1));
+    const bool s_on = (int)(threadIdx.x >> 1) < kPrefillTokens;          // with more threads than staging work the rest sit out
+    const int s_tok = min(M - 1, m0 + min((int)(threadIdx.x >> 1), kPrefillTokens - 1));
     const uint32_t s_part = threadIdx.x & 1u;
     const uint32_t* s_src = x + (size_t)s_tok * xpitch;
-    unsigned char* s_dst = abuf + (threadIdx.x >> 1) * kATokenPitch + s_part * 48u;
+    unsigned char* s_dst = abuf + (uint32_t)min((int)(threadIdx.x >> 1), kPrefillTokens - 1) * kATokenPitch + s_part * 48u;
     auto stage_load = [&](uint32_t st, uint4 (&v)[3]) {
         const uint32_t b = min(2 * st + s_part, (uint32_t)KB - 1);       // past the last block: any valid data, its weights are zero
         const uint4* p = reinterpret_cast<const uint4*>(s_src + (size_t)b * 12);
         v[0] = p[0]; v[1] = p[1]; v[2] = p[2];
     };
     auto stage_store = [&](uint32_t buf, const uint4 (&v)[3]) {
+        if (!s_on) return;
         uint2* d = reinterpret_cast<uint2*>(s_dst + buf * kABufBytes);
         d[0] = make_uint2(v[0].x, v[0].y); d[1] = make_uint2(v[0].z, v[0].w);
         d[2] = make_uint2(v[1].x, v[1].y); d[3] = make_uint2(v[1].z, v[1].w);
         d[4] = make_uint2(v[2].x, v[2].y); d[5] = make_uint2(v[2].z, v[2].w);
     };
 
-    float16_t acc[8];
+    float16_t acc[TT];
 #pragma unroll
-    for (int t = 0; t < 8; t++) {
+    for (int t = 0; t < TT; t++) {
 #pragma unroll
         for (int v = 0; v < 16; v++) acc[t][v] = 0.0f;
     }
@@ -677,7 +679,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
 #pragma unroll
         for (int j = 0; j < 6; j++) {
 #pragma unroll
-            for (int t = 0; t < 8; t++) {
+            for (int t = 0; t < TT; t++) {
                 const uint2 a = *reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 8u);
                 acc[t] = Mma<X2>::mma(a.x, a.y, wt[2 * j], wt[2 * j + 1], acc[t]);
             }
@@ -691,7 +693,7 @@ __global__ void __launch_bounds__(kPrefillThreads) prefill_kernel(const unsigned
     // y[token][wrow]: register v of tile t belongs to token m0 + 32 t + 8 (v / 4) + 4 half + v % 4
     if (wrow < N) {
 #pragma unroll
-        for (int t = 0; t < 8; t++) {
+        for (int t = 0; t < TT; t++) {
 #pragma unroll
             for (int v = 0; v < 16; v++) {
                 const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
@@ -905,9 +907,10 @@ static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n,
     return 0;
 }
 
-template <int FMT, typename X2>
+template <int FMT, typename X2, int WAVES, int TT>
 static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    const unsigned strips = (unsigned)((N + kPrefillRows - 1) / kPrefillRows), passes = (unsigned)((M + kPrefillTokens - 1) / kPrefillTokens);
+    constexpr int kRows = 32 * WAVES, kTokens = 32 * TT;
+    const unsigned strips = (unsigned)((N + kRows - 1) / kRows), passes = (unsigned)((M + kTokens - 1) / kTokens);
     // enough workgroups for the chip: split the block pairs of a row among up to ksplit workgroups (at least 8 steps each)
     const unsigned spt = ((unsigned)KB + 1) / 2;
     unsigned ksplit = (unsigned)ctx->num_cu / (strips * passes);
@@ -917,9 +920,9 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
         hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     }
     const dim3 grid(strips, passes, ksplit);
-    const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kABufBytes;
-    if (int rc = set_lds(ctx, prefill_kernel<FMT, X2>, lds)) return rc;
-    hipLaunchKernelGGL((prefill_kernel<FMT, X2>), grid, dim3(kPrefillThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+    const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kTokens * kATokenPitch;
+    if (int rc = set_lds(ctx, prefill_kernel<FMT, X2, WAVES, TT>, lds)) return rc;
+    hipLaunchKernelGGL((prefill_kernel<FMT, X2, WAVES, TT>), grid, dim3(64 * WAVES), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "prefill matmul launch");
@@ -928,11 +931,10 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
 template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
-    if (M > 64) return launch_prefill<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    if (M > 64) return launch_prefill<FMT, X2, 8, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
-    if (M <= 64) return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
-    return launch_mfma_cfg<FMT, X2, 512, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
 }
 
 // evaluates EXPR with the constant F set to the storage format `fmt` (which check_idx has accepted)
