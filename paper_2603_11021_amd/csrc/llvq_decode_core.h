@@ -10,6 +10,7 @@
 #pragma once
 #include <cstdint>
 #include <cmath>
+#include <type_traits>
 
 #include "llvq_tables.h"
 
@@ -21,16 +22,25 @@
 
 namespace llvq {
 
-// The tables are addressed as `base + constant offset + key`; on the device `base` is the start of LDS and
-// the constant folds into the offset field of the LDS instruction.
+// The tables are addressed as `base + constant offset + key`.  On the device `base` is an LDS pointer whose value
+// the kernels make the literal address 0 (they use no static LDS, so their dynamic LDS starts there; the host side
+// checks this per kernel): constant and base then fold into the offset field of the LDS instruction and a table
+// address costs no addition.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define LLVQ_LDS __attribute__((address_space(3)))
+#else
+#define LLVQ_LDS
+#endif
+typedef const LLVQ_LDS unsigned char* TabBase;
+
 struct TabPtrs {
-    const unsigned char* base;     // LDS-resident part of the blob
+    TabBase base;                  // LDS-resident part of the blob
     const unsigned char* gbase;    // the whole blob in global memory (for kernels that keep only its first part in LDS)
     uint32_t ncls;
     uint64_t npoints;
 };
 
-LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const unsigned char* gbase, const TableLayout& L) {
+LLVQ_HD TabPtrs make_tab_ptrs(TabBase base, const unsigned char* gbase, const TableLayout& L) {
     TabPtrs T;
     T.base = base;
     T.gbase = gbase;
@@ -39,16 +49,48 @@ LLVQ_HD TabPtrs make_tab_ptrs(const unsigned char* base, const unsigned char* gb
     return T;
 }
 
+// a table element of type V at p: records are read as 16-byte pieces (an LDS pointer cannot bind to the reference
+// a struct copy takes)
+template <typename V>
+LLVQ_HD V tab_load(TabBase p) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    if constexpr (std::is_class<V>::value) {
+        static_assert(sizeof(V) % 16 == 0, "records are multiples of 16 bytes");
+        struct Pieces { uint32_t q[sizeof(V) / 4]; } t;
+        typedef uint32_t Piece __attribute__((ext_vector_type(4)));
+        const LLVQ_LDS Piece* src = reinterpret_cast<const LLVQ_LDS Piece*>(p);
+        for (uint32_t i = 0; i < sizeof(V) / 16; i++) {
+            const Piece v = src[i];
+            t.q[4 * i] = v[0]; t.q[4 * i + 1] = v[1]; t.q[4 * i + 2] = v[2]; t.q[4 * i + 3] = v[3];
+        }
+        return __builtin_bit_cast(V, t);
+    } else {
+        return *reinterpret_cast<const LLVQ_LDS V*>(p);
+    }
+#else
+    return *reinterpret_cast<const V*>(p);
+#endif
+}
+
 // element `byte_off` bytes into the table at constant offset OFF
 template <typename V, uint32_t OFF>
 LLVQ_HD V tab_at(const TabPtrs& T, uint32_t byte_off) {
-    return *reinterpret_cast<const V*>(T.base + OFF + byte_off);
+    return tab_load<V>(T.base + OFF + byte_off);
 }
 
 // the same for the tables that stay in global memory
 template <typename V, uint32_t OFF>
 LLVQ_HD V gtab_at(const TabPtrs& T, uint32_t byte_off) {
     return *reinterpret_cast<const V*>(T.gbase + OFF + byte_off);
+}
+
+// product of two numbers below 2^24 (the 24-bit multiplier runs at full rate, the 32-bit one does not)
+LLVQ_HD uint32_t mul24(uint32_t a, uint32_t b) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umul24(a, b);
+#else
+    return a * b;
+#endif
 }
 
 LLVQ_HD uint32_t popc32(uint32_t v) {
@@ -59,13 +101,45 @@ LLVQ_HD uint32_t popc32(uint32_t v) {
 #endif
 }
 
-LLVQ_HD uint32_t bfe6(uint32_t v, uint32_t off) { return (v >> off) & 63u; }
+// bits off..off+5 of v.  On the device the extraction is kept as one v_bfe_u32: written with shift and mask the
+// compiler folds a following scale into the mask and ends up with more instructions per table address.
+LLVQ_HD uint32_t bfe6(uint32_t v, uint32_t off) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_ubfe(v, off, 6u);
+#else
+    return (v >> off) & 63u;
+#endif
+}
 
-// Entry (F, m) of the 6-bit deposit tables sits at F*64 + (m ^ F): the frequent all-zero sources of different
-// masks then fall into different LDS banks instead of all into bank 0.
-// spread6: byte offset of entry (F, bits o..o+5 of plane) given plane2 = plane << 2 and Fx = F * 0x104
-LLVQ_HD uint32_t spread6_at(const TabPtrs& T, uint32_t Fx, uint32_t plane2, uint32_t o) {
-    return tab_at<uint32_t, kOffSpread6>(T, ((plane2 >> o) & 0xFCu) ^ Fx);
+// Entry (F, m) of spread6 is dword F * kSpreadPitch + m (the odd pitch spreads equal m of different masks over
+// the LDS banks).  Fx = F * 4 * kSpreadPitch; the source is bits o..o+5 of plane (bits past the mask's
+// popcount do not change the entry's value).
+LLVQ_HD uint32_t spread6_at(const TabPtrs& T, uint32_t Fx, uint32_t plane, uint32_t o) {
+    return tab_at<uint32_t, kOffSpread6>(T, Fx + (bfe6(plane, o) << 2));
+}
+
+// Marks a product that several table addresses share: without it the compiler repeats the multiplication inside
+// every address (a multiply-add each) instead of adding to the product once computed.
+LLVQ_HD void keep_product(uint32_t& v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm("" : "+v"(v));
+#else
+    (void)v;
+#endif
+}
+
+// any boolean function of three words: bit i of the result is bit (a_i b_i c_i) of the truth table TT
+// (a = 0xF0, b = 0xCC, c = 0xAA), one v_bitop3_b32 on the device
+template <uint32_t TT>
+LLVQ_HD uint32_t lut3(uint32_t a, uint32_t b, uint32_t c) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, TT);
+#else
+    uint32_t r = 0;
+    for (uint32_t i = 0; i < 8; i++)
+        if ((TT >> i) & 1u) r |= ((i & 4u) ? a : ~a) & ((i & 2u) ? b : ~b) & ((i & 1u) ? c : ~c);
+    return r;
+#endif
 }
 
 // true when `v` holds for any active lane of the wavefront (always true on the host, where it only gates work)
@@ -105,22 +179,20 @@ LLVQ_HD ClassHit find_class(const TabPtrs& T, uint64_t I) {
     // the bucket of the top bits names the class of the bucket's first index; the class of I is that one or one of
     // the next few.  Three candidates are tested per round (their offsets are read together), so that the rare lane
     // whose bucket spans several small classes does not make its whole wavefront wait for one table read per class.
-    uint32_t cid = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I >> kBucketShift) * 2u);
-    uint64_t off = tab_at<uint64_t, kOffClsOff>(T, cid * 8u);
+    // The class is carried as the byte offset of its cls_off entry, so the candidates' addresses are constants
+    // apart; the table ends with offset[ncls] = N and three entries above every index, which no lane passes.
+    uint32_t c8 = tab_at<uint16_t, kOffBucket>(T, (uint32_t)(I >> kBucketShift) * 2u);
     for (;;) {
-        const uint32_t last = T.ncls;                       // offset[ncls] = npoints > I: never passed
-        const uint32_t c1 = cid + 1 < last ? cid + 1 : last, c2 = cid + 2 < last ? cid + 2 : last, c3 = cid + 3 < last ? cid + 3 : last;
-        const uint64_t o1 = tab_at<uint64_t, kOffClsOff>(T, c1 * 8u);
-        const uint64_t o2 = tab_at<uint64_t, kOffClsOff>(T, c2 * 8u);
-        const uint64_t o3 = tab_at<uint64_t, kOffClsOff>(T, c3 * 8u);
+        const uint64_t o1 = tab_at<uint64_t, kOffClsOff + 8>(T, c8);
+        const uint64_t o2 = tab_at<uint64_t, kOffClsOff + 16>(T, c8);
+        const uint64_t o3 = tab_at<uint64_t, kOffClsOff + 24>(T, c8);
         const bool p1 = I >= o1, p2 = I >= o2, p3 = I >= o3;     // monotone: p3 implies p2 implies p1
-        off = p3 ? o3 : (p2 ? o2 : (p1 ? o1 : off));
-        cid = p3 ? c3 : (p2 ? c2 : (p1 ? c1 : cid));
+        c8 += (p1 ? 8u : 0u) + (p2 ? 8u : 0u) + (p3 ? 8u : 0u);
         if (!wave_or(p3)) break;
     }
     ClassHit h;
-    h.cid = cid;
-    h.Ic = I - off;
+    h.cid = c8 >> 3;
+    h.Ic = I - tab_at<uint64_t, kOffClsOff>(T, c8);
     return h;
 }
 
@@ -140,7 +212,7 @@ struct Front {
 template <bool BIG_GLOBAL = false>
 LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     Front F;
-    const ClassRec R = tab_at<ClassRec, kOffCls>(T, hit.cid * (uint32_t)sizeof(ClassRec));
+    const ClassRec R = tab_at<ClassRec, kOffCls>(T, mul24(hit.cid, (uint32_t)sizeof(ClassRec)));
     const uint32_t f0 = R.f0, f1 = R.f1;
     // r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are exact: the operands are
     // integers below 2^48 held in doubles and the reciprocals are nudged upwards.
@@ -158,7 +230,7 @@ LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     const uint32_t rem = (uint32_t)fma(-dd, (double)R.PP, ipp);
     F.d = (uint32_t)dd;
     const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
-    const uint32_t rho1 = rem - rin * R.P1;
+    const uint32_t rho1 = rem - mul24(rin, R.P1);             // rem < 2^22
     const uint32_t oc = (((f1 >> F1_GOFF) & 4095u) + r) * 4u, o0 = (R.tb0 + rin) * 4u, o1 = (R.tb1 + rho1) * 4u;
     F.c = BIG_GLOBAL ? gtab_at<uint32_t, kOffGs>(T, oc) : tab_at<uint32_t, kOffGs>(T, oc);
     F.e0 = BIG_GLOBAL ? gtab_at<uint32_t, kOffInner>(T, o0) : tab_at<uint32_t, kOffInner>(T, o0);
@@ -190,7 +262,7 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
     }
     const uint32_t dl = F.d - e.base;
     const uint32_t rk_hi = (uint32_t)((double)dl * (double)e.inv);
-    const uint32_t rk_lo = dl - rk_hi * e.div;
+    const uint32_t rk_lo = dl - mul24(rk_hi, e.div);          // dl < C(24, 12) < 2^22
     const uint32_t U = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12lo + rk_lo) * 2u) |
                        ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12hi + rk_hi) * 2u) << 12);
 
@@ -200,15 +272,15 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
     info.rnorm = F.rnorm;
     info.vt8_lo = F.vt8_lo; info.vt8_hi = F.vt8_hi; info.vti_lo = F.vti_lo; info.vti_hi = F.vti_hi;
     {
-        // planes pre-shifted by two: the deposit keys below are byte offsets into a table of dwords
-        const uint32_t a0 = (F.e0 & 0xFFFFu) << 2, b0 = (F.e0 >> 16) << 2, a1 = (F.e1 & 0xFFFFu) << 2, b1 = (F.e1 >> 16) << 2;
+        // 16-bit planes; the deposit ignores source bits past the popcount of its mask, so e0 serves as its own low plane
+        const uint32_t a0 = F.e0, b0 = F.e0 >> 16, a1 = F.e1, b1 = F.e1 >> 16;
         // signs: w-1 free bits on F1 then one bit per nonzero F0 coordinate; the last F1 slot is forced so
         // that the number of negative F1 coordinates has the parity condition (iii) asks for
         const uint32_t wm1 = (f0 >> F0_WM1) & 31u;
         uint32_t s1 = F.s & ((1u << wm1) - 1u);
         const uint32_t forced = (f0 >> F0_FEN) & ((f0 >> F0_KAPPA) ^ popc32(s1)) & 1u;
         s1 |= forced << wm1;
-        const uint32_t s0 = (F.s >> wm1) << 2;
+        const uint32_t s0 = F.s >> wm1;
 
         const bool odd = (f0 >> F0_ODD) & 1u;
         const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
@@ -216,29 +288,34 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
         const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? cw : 0u;           // slots of the direct F1 word
         const uint32_t om = outer_all ? 0xFFFFFFu : (~cw & 0xFFFFFFu);      // positions of the outer domain
         const uint32_t sm = odd ? 0xFFFFFFu : cw;                           // positions taking a bit of sb
-        const uint32_t sb = (odd ? cw : s1) << 2;                           // odd: the word itself flips signs
+        const uint32_t sb = odd ? cw : s1;                                  // odd: the word itself flips signs
         const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                // keep U as the domain bit
 
         uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
-            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, (omk << 6) | (bfe6(U, ou) ^ omk));   // U in absolute positions
+            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, omk * kPdepPitch + bfe6(U, ou));   // U in absolute positions
             ou += popc32(omk);
             const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
-            const uint32_t cx = cmk * 0x104u, ux = uk * 0x104u, sx = smk * 0x104u;
+            uint32_t cx = cmk * (4u * kSpreadPitch), ux = uk * (4u * kSpreadPitch), sx = smk * (4u * kSpreadPitch);
+            keep_product(cx); keep_product(ux);
             const uint32_t gA1 = spread6_at(T, cx, a1, o1);
-            uint32_t gB = spread6_at(T, cx, b1, o1);
+            const uint32_t gB1 = spread6_at(T, cx, b1, o1);
             o1 += popc32(cmk);
             const uint32_t gA0 = spread6_at(T, ux, a0, o0);
-            gB |= spread6_at(T, ux, b0, o0);
+            const uint32_t gB0 = spread6_at(T, ux, b0, o0);
             const uint32_t gS0 = spread6_at(T, ux, s0, o0);
             o0 += popc32(uk);
             const uint32_t gS1 = spread6_at(T, sx, sb, os);
             os += popc32(smk);
+            // an entry holds the deposited bits in bit 0 and the mask in bit 2 of its nibbles
             const uint32_t ones = 0x01011111u;
-            w[k] = ((gA1 | gA0) & ones) | ((gB & ones) << 1) | (((gS1 | gS0) & ones) << 3) |
-                      (gA1 & 0x04044444u) | (gA0 & dkeep);
+            const uint32_t ta = lut3<0xE0>(ones, gA1, gA0), tb = lut3<0xE0>(ones, gB1, gB0), ts = lut3<0xE0>(ones, gS1, gS0);
+            uint32_t v = (tb << 1) | ta;
+            v = (ts << 3) | v;
+            v = (gA1 & 0x04044444u) | v;
+            w[k] = lut3<0xEA>(gA0, dkeep, v);
         }
     }
     return info;

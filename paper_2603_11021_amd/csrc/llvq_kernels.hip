@@ -14,6 +14,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <atomic>
 #include <string>
 
 #include "../../include/llvq.h"
@@ -34,6 +35,14 @@ typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 extern __shared__ __align__(16) unsigned char g_lds[];
+
+// Address 0 of LDS as a table base.  The kernels here declare no static LDS, so the dynamic LDS that receives the
+// tables starts at 0 (set_lds checks that per kernel); with the base a literal, table offsets fold into the LDS
+// instructions.  (Formed from a variable: a literal 0 would be the null pointer, which is not address 0 in LDS.)
+__device__ __forceinline__ llvq::TabBase lds_origin() {
+    uint32_t zero = 0;
+    return (llvq::TabBase)(uintptr_t)zero;
+}
 
 template <int THREADS = kThreads>
 __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ blob, uint32_t bytes) {
@@ -145,7 +154,7 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel
                                                              const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     // the next word is requested (always: past the end the last one is read again) before this block is decoded
     const size_t stride = (size_t)gridDim.x * kThreads;
     size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
@@ -189,7 +198,7 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
                                                            const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                            Code cd, size_t n, void* __restrict__ out) {
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     // the next word and gain are requested (always: past the end the last ones are read again) before this block is decoded
     const size_t stride = (size_t)gridDim.x * kThreads;
     size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
@@ -284,7 +293,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
     load_tables(blob, table_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
@@ -465,7 +474,7 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
                                                         Code cd, uint32_t steps_per_wave, float* __restrict__ y) {
     constexpr int kWavesHere = THREADS / 64;
     load_tables<THREADS>(blob, lay.blob_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
     // steps (row tile, block pair) are numbered row tile major and dealt to the waves of the grid as contiguous ranges
@@ -591,7 +600,7 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
     constexpr int kPrefillThreads = 64 * WAVES, kPrefillTokens = 32 * TT, kPrefillRows = 32 * WAVES;
     constexpr uint32_t kABufBytes = kPrefillTokens * kATokenPitch;
     load_tables<kPrefillThreads>(blob, lay.lds_bytes);
-    const TabPtrs T = llvq::make_tab_ptrs(g_lds, blob, lay);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     unsigned char* abuf = g_lds + lay.lds_bytes;                         // two buffers of kABufBytes
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -782,8 +791,21 @@ int check_idx(const void* d_idx, int fmt) {
     return LLVQ_EINVAL;
 }
 
+// Sets the dynamic LDS size of a kernel.  The kernels address their tables from LDS address 0 (lds_origin), which
+// holds only while a kernel declares no static LDS: checked here once per kernel.
 template <typename K>
 int set_lds(llvq_ctx* ctx, K kernel, size_t bytes) {
+    static std::atomic<int> static_lds_checked{0};       // one per kernel instantiation
+    if (!static_lds_checked.load(std::memory_order_relaxed)) {
+        hipFuncAttributes attr;
+        hipError_t q = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
+        if (q != hipSuccess) return hip_fail(ctx, q, "hipFuncGetAttributes");
+        if (attr.sharedSizeBytes != 0) {
+            if (ctx) ctx->hip_error = "a kernel that addresses its tables from LDS address 0 declares static LDS";
+            return LLVQ_EHIP;
+        }
+        static_lds_checked.store(1, std::memory_order_relaxed);
+    }
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "hipFuncSetAttribute");
 }

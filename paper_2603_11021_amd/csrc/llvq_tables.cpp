@@ -272,7 +272,7 @@ bool build_tables(int m_max, Tables& out) {
     // ---- class records ---------------------------------------------------------------------------
     std::vector<ClassRec> recs(ncls);
     std::vector<EncRec> encs(ncls);
-    std::vector<uint64_t> cls_off(ncls + 1);
+    std::vector<uint64_t> cls_off(ncls + 4, ~0ull);      // the search reads up to three entries past offset[ncls] = N
     for (uint32_t ci = 0; ci < ncls; ci++) {
         const Leader& L = cls[ci];
         ClassRec R{};
@@ -411,22 +411,22 @@ bool build_tables(int m_max, Tables& out) {
     for (uint32_t b = 0; b < nbuckets; b++) {
         uint64_t first = (uint64_t)b << bucket_shift;
         uint32_t ci = (uint32_t)(std::upper_bound(cls_off.begin(), cls_off.begin() + ncls, first) - cls_off.begin());
-        bucket[b] = (uint16_t)(ci == 0 ? 0 : ci - 1);
+        bucket[b] = (uint16_t)(8u * (ci == 0 ? 0 : ci - 1));
     }
 
     // ---- 6-bit deposit tables ---------------------------------------------------------------------
-    std::vector<uint8_t> pdep6(4096);
-    std::vector<uint32_t> spread6(4096);
+    std::vector<uint8_t> pdep6(64 * kPdepPitch, 0);
+    std::vector<uint32_t> spread6(64 * kSpreadPitch, 0);
     for (uint32_t F = 0; F < 64; F++)
         for (uint32_t mbits = 0; mbits < 64; mbits++) {
             uint32_t dep = deposit(mbits, F);
-            pdep6[F << 6 | (mbits ^ F)] = (uint8_t)dep;       // swizzled: see dep_key()
+            pdep6[F * kPdepPitch + mbits] = (uint8_t)dep;
             uint32_t sp = 0;
             for (int p = 0; p < 6; p++) {
                 if ((dep >> p) & 1u) sp |= 1u << (4 * kNibbleSlot[p]);
                 if ((F >> p) & 1u) sp |= 4u << (4 * kNibbleSlot[p]);
             }
-            spread6[F << 6 | (mbits ^ F)] = sp;
+            spread6[F * kSpreadPitch + mbits] = sp;
         }
 
     // ---- blob ------------------------------------------------------------------------------------

@@ -59,20 +59,23 @@ static_assert(sizeof(SplitEnt) == 16, "SplitEnt layout");
 // the inner-word planes) come last: a kernel either copies the whole blob into LDS or only the first kLdsBytes and
 // reads those two through the vector L1/L2 (a shorter table copy per launch, at the price of three global gathers
 // per block).
-constexpr uint32_t kOffSpread6 = 0;        // 4096 x u32
-constexpr uint32_t kOffPdep6   = 16384;    // 4096 x u8
-constexpr uint32_t kOffLut12   = 20480;    // 4096 x u16
-constexpr uint32_t kOffBucket  = 28672;    // 4096 x u16
-constexpr uint32_t kOffGuess   = 36864;    // up to 48 rows x 64 x u8
-constexpr uint32_t kOffAtab    = 39936;    // 4 x {A, 1/A} doubles
-constexpr uint32_t kOffClsOff  = 40000;    // (ncls + 1) x u64, ncls <= 383
-constexpr uint32_t kOffRnorm   = 43072;    // 16 x float: 1/sqrt(16 m)
-constexpr uint32_t kOffSplit   = 43136;    // up to 352 x SplitEnt
-constexpr uint32_t kOffCls     = 48768;    // ncls x ClassRec
-constexpr uint32_t kLdsBytes   = 67168;    // end of the LDS-resident part
-constexpr uint32_t kOffGs      = 67168;    // 4096 x u32 (global memory)
-constexpr uint32_t kOffInner   = 83552;    // inner-word planes, u32 (global memory)
-constexpr uint32_t kMaxBlob    = 83552 + 4 * 65536;   // the inner-word table bases are 16-bit entry numbers
+constexpr uint32_t kSpreadPitch = 65;      // dwords per mask row of spread6: entry (F, m) at F * 65 + m, so that equal m of
+                                           // different masks (all-zero sources are frequent) fall into different LDS banks
+constexpr uint32_t kPdepPitch  = 68;       // bytes per mask row of pdep6 (17 dwords, for the same reason)
+constexpr uint32_t kOffSpread6 = 0;        // 64 x 65 x u32
+constexpr uint32_t kOffPdep6   = 16640;    // 64 x 68 x u8
+constexpr uint32_t kOffLut12   = 20992;    // 4096 x u16
+constexpr uint32_t kOffBucket  = 29184;    // 4096 x u16: 8 x class id (the byte offset of its entry in cls_off)
+constexpr uint32_t kOffGuess   = 37376;    // up to 48 rows x 64 x u8
+constexpr uint32_t kOffAtab    = 40448;    // 4 x {A, 1/A} doubles
+constexpr uint32_t kOffClsOff  = 40512;    // (ncls + 4) x u64, ncls <= 383: offsets, N, and three entries above every index
+constexpr uint32_t kOffRnorm   = 43616;    // 16 x float: 1/sqrt(16 m)
+constexpr uint32_t kOffSplit   = 43680;    // up to 352 x SplitEnt
+constexpr uint32_t kOffCls     = 49312;    // ncls x ClassRec
+constexpr uint32_t kLdsBytes   = 67712;    // end of the LDS-resident part
+constexpr uint32_t kOffGs      = 67712;    // 4096 x u32 (global memory)
+constexpr uint32_t kOffInner   = 84096;    // inner-word planes, u32 (global memory)
+constexpr uint32_t kMaxBlob    = 84096 + 4 * 65536;   // the inner-word table bases are 16-bit entry numbers
 constexpr uint32_t kBucketShift = 36;      // bucket index = I >> 36 (4096 buckets cover 48 bits)
 constexpr uint32_t kGuessBuckets = 64;     // buckets of the subset-split guess table per (n, q)
 
