@@ -109,7 +109,7 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
  *   of different K ranges are combined with fp32 atomic adds, so the last bits of y can differ between calls
  *   (launches with M > 64 and at least one strip of 256 rows x 256 tokens per compute unit do not split K and are
  *   reproducible).
- *   Requires M*N < 2^32.                                                                               */
+ *   Requires N*KB < 2^32, KB < 2^24 and M*N < 2^32 (LLVQ_EINVAL otherwise).                            */
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
                 float* d_y, void* stream);

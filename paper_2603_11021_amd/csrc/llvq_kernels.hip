@@ -60,16 +60,16 @@ __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ bl
     __syncthreads();
 }
 
-// sum over the 64 lanes of a wavefront with DPP adds inside each row of 16 lanes and four lane reads; every
-// lane receives the total
-__device__ __forceinline__ float wave_sum(float v) {
+// sum over the 64 lanes of a wavefront, valid in lane 63 only: four DPP adds inside each row of 16 lanes, then the
+// row totals travel to the following rows (row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3)
+__device__ __forceinline__ float wave_sum_to_last(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
-    const int iv = __builtin_bit_cast(int, v);
-    return (__builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 0)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 16))) +
-           (__builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 32)) + __builtin_bit_cast(float, __builtin_amdgcn_readlane(iv, 48)));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x142, 0xA, 0xF, false)); // row_bcast:15
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false)); // row_bcast:31
+    return v;
 }
 
 
@@ -133,6 +133,27 @@ __device__ __forceinline__ void load_raw(const void* __restrict__ idx, const uin
     // a condition would make later waits in a pipelined loop conservative
     const uint16_t* gp = gain_array ? gain : reinterpret_cast<const uint16_t*>(idx);
     r.g = gp[k];
+}
+
+// The same loads for a block `k` (below 2^24) past a wave-uniform position of the arrays: the addresses are then a
+// scalar base plus a 32-bit lane offset, one multiplication each.
+template <int FMT>
+__device__ __forceinline__ void load_raw_near(const unsigned char* __restrict__ idx0, const unsigned char* __restrict__ gain0,
+                                              uint32_t k, RawBlock& r) {
+    r.a = r.b = r.c = 0;
+    if constexpr (FMT == LLVQ_IDX_U64) {
+        const uint32_t* p = reinterpret_cast<const uint32_t*>(idx0 + llvq::mul24(k, 8u));
+        r.a = p[0]; r.b = p[1];
+    } else if constexpr (FMT == LLVQ_IDX_U24) {
+        const uint8_t* p = idx0 + llvq::mul24(k, 3u);
+        r.a = p[0]; r.b = p[1]; r.c = p[2];
+    } else {
+        typedef uint32_t u32_align2 __attribute__((aligned(2)));
+        const unsigned char* p = idx0 + llvq::mul24(k, 6u);
+        r.a = *reinterpret_cast<const u32_align2*>(p);
+        r.c = *reinterpret_cast<const uint16_t*>(p + 4);
+    }
+    r.g = *reinterpret_cast<const uint16_t*>(gain0 + 2u * k);
 }
 
 template <int FMT>
@@ -277,10 +298,10 @@ template <int FMT, typename X2, bool BIG_GLOBAL>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                          Code cd, uint32_t kb_magic, int rows_per_wg, float* __restrict__ y) {
+                                                          Code cd, uint32_t kb_magic, int rows_per_wg, int rows_per_pass, float* __restrict__ y) {
     const int wg_r0 = blockIdx.x * rows_per_wg;
     const int wg_r1 = min(N, wg_r0 + rows_per_wg);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: loop control below is wave-uniform
     {
         // touch this thread's first index and gain now: their trip from HBM overlaps the table load below
         const size_t nb = (size_t)(wg_r1 - wg_r0) * KB;
@@ -297,10 +318,14 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
-    for (int r0 = wg_r0; r0 < wg_r1; r0 += kRowsPerPass) {
-        const int nrows = min(kRowsPerPass, wg_r1 - r0);
+    // rows_per_pass <= kRowsPerPass keeps a pass below 2^24 blocks (block numbers inside a pass go through 24-bit multiplies)
+    for (int r0 = wg_r0; r0 < wg_r1; r0 += rows_per_pass) {
+        const int nrows = min(rows_per_pass, wg_r1 - r0);
         const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
         const size_t blk0 = (size_t)r0 * KB;
+        // wave-uniform starts of this pass in the index and gain arrays (gains from a table: any readable address)
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * (FMT == LLVQ_IDX_U64 ? 8 : FMT == LLVQ_IDX_U24 ? 3 : 6);
+        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
             for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
@@ -315,8 +340,8 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 const uint32_t fbc = f.live ? fb : nblk - 1;
                 // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
                 f.row = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
-                f.b = fbc - f.row * (uint32_t)KB;
-                load_raw<FMT>(idx, gain, cd.lut == nullptr, blk0 + fbc, f.raw);
+                f.b = fbc - llvq::mul24(f.row, (uint32_t)KB);
+                load_raw_near<FMT>(idx0, gain0, fbc, f.raw);
             };
             auto front_of = [&](Fetch& f, bool& ok) {
                 uint64_t I;
@@ -341,7 +366,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 if constexpr (kMore) fetch(base + stride, nxt);
                 u32x4 xq[1][3];
                 {
-                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)m0 * xpitch + (size_t)cur.b * 12);
+                    const u32x4* xp = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(x + (size_t)m0 * xpitch) + llvq::mul24(cur.b, 48u));
                     xq[0][0] = xp[0]; xq[0][1] = xp[1]; xq[0][2] = xp[2];
                 }
                 uint32_t w[1][4];
@@ -370,7 +395,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                     for (int mi = 0; mi < mc; mi++) {
                         u32x4 x0 = xq[u][0], x1 = xq[u][1], x2 = xq[u][2];
                         if (mi > 0) {
-                            const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(m0 + mi) * xpitch + (size_t)cur.b * 12);
+                            const u32x4* xp = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(x + (size_t)(m0 + mi) * xpitch) + llvq::mul24(cur.b, 48u));
                             x0 = xp[0]; x1 = xp[1]; x2 = xp[2];
                         }
                         const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
@@ -379,12 +404,12 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                         for (int i = 0; i < 12; i++) acc = Dot<X2>::dot(wt[i], __builtin_bit_cast(X2, xs[i]), acc);
                         float p = cur.live ? acc * scale : 0.0f;
                         if (row_hi == row_lo) {                                  // the whole batch lies in one row
-                            const float s_all = wave_sum(p);
-                            if (lane == 0) atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_all);
+                            const float s_all = wave_sum_to_last(p);
+                            if (lane == 63) atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_all);
                         } else if (two_rows) {
                             const float p_lo = row == row_lo ? p : 0.0f;
-                            const float s_lo = wave_sum(p_lo), s_hi = wave_sum(p - p_lo);
-                            if (lane == 0) {
+                            const float s_lo = wave_sum_to_last(p_lo), s_hi = wave_sum_to_last(p - p_lo);
+                            if (lane == 63) {
                                 atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_lo);
                                 atomicAdd(&ysum[row_hi * kMaxMChunk + mi], s_hi);
                             }
@@ -868,14 +893,15 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     // from about 256 batches of 64 blocks per compute unit on, copying all tables into LDS pays (measured on Llama-3-70B shapes)
     const bool big_global = (size_t)N * (size_t)KB < (size_t)ctx->num_cu * 64 * 256;
     const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
+    const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
     if (big_global) {
         if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true>, lds)) return rc;
         hipLaunchKernelGGL((matmul_kernel<FMT, X2, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
+                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
     } else {
         if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, false>, lds)) return rc;
         hipLaunchKernelGGL((matmul_kernel<FMT, X2, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, d_y);
+                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
@@ -1018,7 +1044,7 @@ int decode_impl(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, c
 int matmul_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain, const Code& cd,
                 int N, int KB, float* d_y, void* stream) {
     if (!d_x || (!d_gain && !cd.lut) || !d_y) return LLVQ_EINVAL;
-    if (M < 1 || M > 1024 || N < 1 || KB < 1) return LLVQ_EINVAL;
+    if (M < 1 || M > 1024 || N < 1 || KB < 1 || KB >= (1 << 24)) return LLVQ_EINVAL;
     if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
     if ((size_t)N * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
     if (int rc = check_idx(d_idx, fmt)) return rc;
