@@ -219,7 +219,9 @@ LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     const uint32_t acode = (f1 >> F1_ACODE) & 3u;
     const double A = tab_at<double, kOffAtab>(T, acode * 16u);
     const double invA = tab_at<double, kOffAtab + 8>(T, acode * 16u);
-    const double x = (double)hit.Ic;
+    // Ic < 2^48 as a double: its bits under the exponent of 2^52, minus 2^52 (two instructions instead of two
+    // conversions, a scaling and an addition)
+    const double x = __builtin_bit_cast(double, hit.Ic | 0x4330000000000000ull) - 4503599627370496.0;
     const double q1 = floor(x * invA);
     const uint32_t r = (uint32_t)fma(-q1, A, x);
     const int B = (int)((f0 >> F0_B) & 31u);
