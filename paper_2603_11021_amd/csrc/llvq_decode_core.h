@@ -208,11 +208,13 @@ struct Front {
     float rnorm;
 };
 
-// BIG_GLOBAL: the Golay words and the inner-word planes are read from global memory instead of LDS
-template <bool BIG_GLOBAL = false>
+// BIG_GLOBAL: the Golay words and the inner-word planes are read from global memory instead of LDS;
+// REC_GLOBAL: so is the class record
+template <bool BIG_GLOBAL = false, bool REC_GLOBAL = false>
 LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     Front F;
-    const ClassRec R = tab_at<ClassRec, kOffCls>(T, mul24(hit.cid, (uint32_t)sizeof(ClassRec)));
+    const ClassRec R = REC_GLOBAL ? gtab_at<ClassRec, kOffCls>(T, mul24(hit.cid, (uint32_t)sizeof(ClassRec)))
+                                  : tab_at<ClassRec, kOffCls>(T, mul24(hit.cid, (uint32_t)sizeof(ClassRec)));
     const uint32_t f0 = R.f0, f1 = R.f1;
     // r = Ic mod A, then B sign bits, then the permutation rank I''.  All quotients are exact: the operands are
     // integers below 2^48 held in doubles and the reciprocals are nudged upwards.

@@ -86,6 +86,9 @@ __device__ __forceinline__ uint64_t load_index(const void* __restrict__ idx, siz
     }
 }
 
+// bytes of a stored code word
+template <int FMT> constexpr uint32_t kWordBytes = FMT == LLVQ_IDX_U64 ? 8u : FMT == LLVQ_IDX_U24 ? 3u : 6u;
+
 // How a stored code word maps to (lattice index, gain): index = (word & mask) + base; the gain is either the
 // per-block fp16 array or entry (word >> shape_bits) of a small table (gain bits carried inside the word).
 struct Code {
@@ -176,13 +179,21 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel
                                                              uint32_t* __restrict__ out) {
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    // the next word is requested (always: past the end the last one is read again) before this block is decoded
+    // A pass of the workgroup covers kThreads consecutive blocks from a wave-uniform position, so the streamed arrays
+    // are addressed as scalar base + 32-bit lane offset.  The next word is requested (always: past the end the last
+    // one is read again) before this block is decoded.
     const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t t = threadIdx.x;
+    auto request = [&](size_t base, RawBlock& r) {
+        const size_t b0 = base < n ? base : n - 1;
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + b0 * kWordBytes<FMT>;
+        load_raw_near<FMT>(idx0, idx0, (uint32_t)min((size_t)t, n - 1 - b0), r);
+    };
+    size_t base = (size_t)blockIdx.x * kThreads;
     RawBlock raw, raw_next;
-    if (k < n) load_raw<FMT>(idx, nullptr, false, k, raw);
-    for (; k < n; k += stride, raw = raw_next) {
-        load_raw<FMT>(idx, nullptr, false, min(k + stride, n - 1), raw_next);
+    if (base < n) request(base, raw);
+    for (; base < n; base += stride, raw = raw_next) {
+        request(base + stride, raw_next);
         uint64_t I;
         uint16_t gdummy;
         finish_block<FMT>(raw, cd, I, gdummy);
@@ -190,10 +201,12 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel
         uint32_t w[4], o[6];
         const llvq::BlockInfo bi = llvq::decode_back(T, llvq::decode_front<BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0)), w);
         llvq::nibbles_to_i8(w, bi.vti_lo, bi.vti_hi, o);
-        uint2* dst = reinterpret_cast<uint2*>(out + 6 * k);
-        dst[0] = ok ? make_uint2(o[0], o[1]) : make_uint2(0, 0);
-        dst[1] = ok ? make_uint2(o[2], o[3]) : make_uint2(0, 0);
-        dst[2] = ok ? make_uint2(o[4], o[5]) : make_uint2(0, 0);
+        if (base + t < n) {
+            uint2* dst = reinterpret_cast<uint2*>(reinterpret_cast<unsigned char*>(out + 6 * base) + llvq::mul24(t, 24u));
+            dst[0] = ok ? make_uint2(o[0], o[1]) : make_uint2(0, 0);
+            dst[1] = ok ? make_uint2(o[2], o[3]) : make_uint2(0, 0);
+            dst[2] = ok ? make_uint2(o[4], o[5]) : make_uint2(0, 0);
+        }
     }
 }
 
@@ -220,13 +233,21 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
                                                            Code cd, size_t n, void* __restrict__ out) {
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    // the next word and gain are requested (always: past the end the last ones are read again) before this block is decoded
+    // passes and addressing as in decode_i8_kernel; the next word and gain are requested before this block is decoded
     const size_t stride = (size_t)gridDim.x * kThreads;
-    size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x;
+    const uint32_t t = threadIdx.x;
+    auto request = [&](size_t base, RawBlock& r) {
+        const size_t b0 = base < n ? base : n - 1;
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + b0 * kWordBytes<FMT>;
+        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + b0) : idx0;
+        load_raw_near<FMT>(idx0, gain0, (uint32_t)min((size_t)t, n - 1 - b0), r);
+    };
+    size_t base = (size_t)blockIdx.x * kThreads;
     RawBlock raw, raw_next;
-    if (k < n) load_raw<FMT>(idx, gain, cd.lut == nullptr, k, raw);
-    for (; k < n; k += stride, raw = raw_next) {
-        load_raw<FMT>(idx, gain, cd.lut == nullptr, min(k + stride, n - 1), raw_next);
+    if (base < n) request(base, raw);
+    for (; base < n; base += stride, raw = raw_next) {
+        request(base + stride, raw_next);
+        const bool live = base + t < n;
         uint64_t I;
         uint16_t gb;
         finish_block<FMT>(raw, cd, I, gb);
@@ -236,38 +257,41 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
         const uint32_t vt_lo = bi.vt8_lo, vt_hi = bi.vt8_hi;
         const float g = __half2float(__ushort_as_half(gb));
         const float scale = ok ? g * bi.rnorm : 0.0f;
-        float v[24];
+        // the signed fp8 bytes of a chunk come as pairs of positions (0,1), (2,3), (4,5); a pair is converted, scaled in
+        // fp32 and rounded once to the output type
+        typedef float float2_t __attribute__((ext_vector_type(2)));
+        uint32_t pair[12];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
             uint32_t fe, fo;
             chunk_fp8(w[c], vt_lo, vt_hi, fe, fo);
-            const half2_t h01 = fp8x2_to_f16(fe, false), h45 = fp8x2_to_f16(fe, true), h23 = fp8x2_to_f16(fo, false);
-            v[6 * c + 0] = (float)h01[0]; v[6 * c + 1] = (float)h01[1];
-            v[6 * c + 2] = (float)h23[0]; v[6 * c + 3] = (float)h23[1];
-            v[6 * c + 4] = (float)h45[0]; v[6 * c + 5] = (float)h45[1];
+            pair[3 * c + 0] = fe; pair[3 * c + 1] = fo; pair[3 * c + 2] = fe;
         }
         if constexpr (OUT == LLVQ_F32) {
-            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + 24 * k);
+            float2_t f[12];
 #pragma unroll
-            for (int i = 0; i < 6; i++) dst[i] = make_float4(v[4 * i] * scale, v[4 * i + 1] * scale, v[4 * i + 2] * scale, v[4 * i + 3] * scale);
+            for (int i = 0; i < 12; i++)
+                f[i] = (i % 3 == 2 ? __builtin_amdgcn_cvt_pk_f32_fp8(pair[i], true) : __builtin_amdgcn_cvt_pk_f32_fp8(pair[i], false)) * scale;
+            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<unsigned char*>(reinterpret_cast<float*>(out) + 24 * base) + llvq::mul24(t, 96u));
+            if (live) {
+#pragma unroll
+                for (int i = 0; i < 6; i++) dst[i] = make_float4(f[2 * i][0], f[2 * i][1], f[2 * i + 1][0], f[2 * i + 1][1]);
+            }
         } else {
             uint32_t pk[12];
 #pragma unroll
             for (int i = 0; i < 12; i++) {
-                const float a = v[2 * i] * scale, b = v[2 * i + 1] * scale;
-                if constexpr (OUT == LLVQ_F16) {
-                    pk[i] = (uint32_t)__half_as_ushort(__float2half_rn(a)) | ((uint32_t)__half_as_ushort(__float2half_rn(b)) << 16);
-                } else {
-                    // bf16 round to nearest even from fp32 bits (finite inputs)
-                    uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-                    ua += 0x7FFFu + ((ua >> 16) & 1u); ub += 0x7FFFu + ((ub >> 16) & 1u);
-                    pk[i] = (ua >> 16) | (ub & 0xFFFF0000u);
-                }
+                // round to nearest even with the hardware conversions
+                const float2_t f = (i % 3 == 2 ? __builtin_amdgcn_cvt_pk_f32_fp8(pair[i], true) : __builtin_amdgcn_cvt_pk_f32_fp8(pair[i], false)) * scale;
+                if constexpr (OUT == LLVQ_F16) pk[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, half2_t));
+                else pk[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
             }
-            uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + 24 * k);
-            dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-            dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-            dst[2] = make_uint4(pk[8], pk[9], pk[10], pk[11]);
+            uint4* dst = reinterpret_cast<uint4*>(reinterpret_cast<unsigned char*>(reinterpret_cast<uint16_t*>(out) + 24 * base) + llvq::mul24(t, 48u));
+            if (live) {
+                dst[0] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                dst[1] = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                dst[2] = make_uint4(pk[8], pk[9], pk[10], pk[11]);
+            }
         }
     }
 }
@@ -324,7 +348,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
         const size_t blk0 = (size_t)r0 * KB;
         // wave-uniform starts of this pass in the index and gain arrays (gains from a table: any readable address)
-        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * (FMT == LLVQ_IDX_U64 ? 8 : FMT == LLVQ_IDX_U24 ? 3 : 6);
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
         const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
@@ -347,7 +371,9 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 uint64_t I;
                 finish_block<FMT>(f.raw, cd, I, f.g);
                 ok = f.live && I < T.npoints;
-                return llvq::decode_front<BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
+                // long launches (all tables in LDS) read the class record through the otherwise idle vector cache: the LDS
+                // gather pipe is as busy as the vector ALUs there, and three 16-byte gathers per block are a tenth of its load
+                return llvq::decode_front<BIG_GLOBAL, !BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
             };
             const uint32_t stride = kWaves * 64;
             uint32_t base = (uint32_t)wave * 64;
