@@ -474,13 +474,13 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
 // ---- llvq_matmul, MFMA kernel for 2 <= M (batched decode and prefill) --------------------------------------
 // A wave owns 32 weight rows and two neighbouring blocks of 24 input channels per step: lanes 0..31 decode
 // block b of rows r0..r0+31, lanes 32..63 block b+1 of the same rows.  The decoded block, scaled by
-// gain/sqrt(16 m) and rounded to the activation type, is exactly the B operand of v_mfma_f32_32x32x8 (lane l
-// supplies k = 4*(l/32)..+3 of column l%32), so the weights go from the decoder's registers straight into the
-// matrix cores; the A operand (32 tokens x the same 8 channels) is read from global memory.  Six MFMAs consume
+// gain/sqrt(16 m) and rounded to the activation type, is exactly the B operand of v_mfma_f32_32x32x16 (lane l
+// supplies k = 8*(l/32)..+7 of column l%32), so the weights go from the decoder's registers straight into the
+// matrix cores; the A operand (32 tokens x the same 16 channels) is read from global memory.  Three MFMAs consume
 // the 24 channels of both blocks.  Steps are dealt to the waves of the whole grid as contiguous ranges (split
 // along K), partial tiles are added to y with fp32 atomics, y is cleared first by fill_kernel.
-typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
-typedef short short4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
 __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
@@ -495,9 +495,9 @@ template <> struct Mma<half2_t> {
         const half2_t r = h * half2_t{sh, sh};
         return __builtin_bit_cast(uint32_t, r);
     }
-    static __device__ __forceinline__ float16_t mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float16_t c) {
-        const uint2 av = make_uint2(a0, a1), bv = make_uint2(b0, b1);
-        return __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(half4_t, av), __builtin_bit_cast(half4_t, bv), c, 0, 0, 0);
+    // c += A B over 16 values of k: lane l holds k = 8 (l / 32) .. + 7 of row (A) or column (B) l % 32
+    static __device__ __forceinline__ float16_t mma(u32x4 a, u32x4 b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
     }
 };
 template <> struct Mma<bf16x2_t> {
@@ -508,9 +508,8 @@ template <> struct Mma<bf16x2_t> {
         f *= scale;
         return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
     }
-    static __device__ __forceinline__ float16_t mma(uint32_t a0, uint32_t a1, uint32_t b0, uint32_t b1, float16_t c) {
-        const uint2 av = make_uint2(a0, a1), bv = make_uint2(b0, b1);
-        return __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(short4_t, av), __builtin_bit_cast(short4_t, bv), c, 0, 0, 0);
+    static __device__ __forceinline__ float16_t mma(u32x4 a, u32x4 b, float16_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
 };
 
@@ -615,11 +614,11 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
 #pragma unroll
             for (int t = 0; t < kTokTiles; t++) {
                 if (t < ntile) {
-                    const uint4* xp = reinterpret_cast<const uint4*>(x + (size_t)(xoff[t] + bx));
-                    const uint4 x0 = xp[0], x1 = xp[1], x2 = xp[2];
-                    const uint32_t xs[12] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w, x2.x, x2.y, x2.z, x2.w};
+                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
+                    const u32x4 xa[3] = {xp[0], xp[1], xp[2]};
 #pragma unroll
-                    for (int j = 0; j < 6; j++) acc[t] = Mma<X2>::mma(xs[2 * j], xs[2 * j + 1], wt[2 * j], wt[2 * j + 1], acc[t]);
+                    for (int j = 0; j < 3; j++)
+                        acc[t] = Mma<X2>::mma(xa[j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
                 }
                 if (kTokTiles > 2 && (t & 1)) __builtin_amdgcn_sched_barrier(0);   // keep only two tiles of activations in flight
             }
@@ -737,11 +736,14 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
         const unsigned char* arow = abuf + (st & 1u) * kABufBytes + (uint32_t)col * kATokenPitch + (uint32_t)half * 48u;
         // k group outermost: consecutive MFMAs go to different accumulators and do not wait for each other
 #pragma unroll
-        for (int j = 0; j < 6; j++) {
+        for (int j = 0; j < 3; j++) {
+            const u32x4 bw = {wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]};
 #pragma unroll
             for (int t = 0; t < TT; t++) {
-                const uint2 a = *reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 8u);
-                acc[t] = Mma<X2>::mma(a.x, a.y, wt[2 * j], wt[2 * j + 1], acc[t]);
+                // token rows are 8-byte aligned in the staged tile (pitch 104): two 8-byte reads
+                const uint2* ap = reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 16u);
+                const uint2 a0 = ap[0], a1 = ap[1];
+                acc[t] = Mma<X2>::mma(u32x4{a0.x, a0.y, a1.x, a1.y}, bw, acc[t]);
             }
         }
         stage_store((st + 1) & 1u, nextv);

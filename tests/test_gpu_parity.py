@@ -189,6 +189,14 @@ def test_matmul_invalid_arguments(gpu):
         gpu.llvq_matmul(x, idx, g, 3, 2)          # sizes do not match
     with pytest.raises(LLVQError):
         gpu._check(gpu._lib.llvq_matmul(gpu._h, x.data_ptr() + 2, 0, 1, idx.data_ptr(), 0, g.data_ptr(), 2, 2, y.data_ptr(), None), "misaligned x")
+    with pytest.raises(LLVQError):             # rows longer than 2^24 blocks are refused before anything is read
+        gpu._check(gpu._lib.llvq_matmul(gpu._h, x.data_ptr(), 0, 1, idx.data_ptr(), 0, g.data_ptr(), 1, 1 << 24, y.data_ptr(), None), "KB too large")
+
+
+def test_matmul_very_long_rows(gpu, oracle13):
+    """a few rows of 2.4 million input channels: block numbers inside a pass far beyond 16 bits"""
+    _matmul_case(gpu, oracle13, 6, 5100, 3, 24 * 100000 - 5, 1)
+    _matmul_case(gpu, oracle13, 6, 5101, 2, 24 * 70001, 2)
 
 
 def _round_to(a, kind):
