@@ -477,7 +477,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
 // gain/sqrt(16 m) and rounded to the activation type, is exactly the B operand of v_mfma_f32_32x32x16 (lane l
 // supplies k = 8*(l/32)..+7 of column l%32), so the weights go from the decoder's registers straight into the
 // matrix cores; the A operand (32 tokens x the same 16 channels) is read from global memory.  Three MFMAs consume
-// the 24 channels of both blocks.  Steps are dealt to the waves of the whole grid as contiguous ranges (split
+// the 24 channels of both blocks.  The block pairs of a row are cut into ranges that different workgroups take (split
 // along K), partial tiles are added to y with fp32 atomics, y is cleared first by fill_kernel.
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -521,20 +521,22 @@ template <int FMT, typename X2, int THREADS, int kTokTiles>
 __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                         const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                         const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                        Code cd, uint32_t steps_per_wave, float* __restrict__ y) {
+                                                        Code cd, uint32_t kranges, float* __restrict__ y) {
     constexpr int kWavesHere = THREADS / 64;
     load_tables<THREADS>(blob, lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 31, half = lane >> 5;
-    // steps (row tile, block pair) are numbered row tile major and dealt to the waves of the grid as contiguous ranges
-    const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps per row tile
+    // The waves of a workgroup own neighbouring row tiles and walk the same block pairs (the range blockIdx.y of the
+    // kranges ranges a row is cut into), so they ask for the same activation lines at about the same time and the
+    // vector cache serves fifteen of sixteen requests.  (Dealing the steps to the waves as one contiguous sequence made
+    // every wave fetch its own activations from L2: at M = 64 that traffic, not the decode, set the time.)
+    const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps (block pairs) per row tile
     const uint32_t n_rt = ((uint32_t)N + 31) / 32;
-    const uint32_t total = n_rt * spt;
-    const uint32_t gw = (uint32_t)blockIdx.x * kWavesHere + wave;
-    const uint32_t s0 = gw * steps_per_wave;
-    const uint32_t s1 = min(total, s0 + steps_per_wave);
-    if (s0 >= s1) return;
+    const uint32_t rt = (uint32_t)blockIdx.x * kWavesHere + wave;
+    const uint32_t s0 = (uint32_t)(((uint64_t)spt * blockIdx.y) / kranges);
+    const uint32_t s1 = (uint32_t)(((uint64_t)spt * (blockIdx.y + 1)) / kranges);
+    if (rt >= n_rt || s0 >= s1) return;
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     for (int m0 = 0; m0 < M; m0 += 32 * kTokTiles) {
@@ -586,8 +588,7 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
             }
         };
 
-        uint32_t rt = s0 / spt, st = s0 - rt * spt;
-        for (uint32_t s = s0; s < s1; s++) {
+        for (uint32_t st = s0; st < s1; st++) {
             const int row = (int)rt * 32 + col;
             const uint32_t b = 2 * st + half;
             const bool live = row < N && b < (uint32_t)KB;
@@ -622,11 +623,8 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
                 }
                 if (kTokTiles > 2 && (t & 1)) __builtin_amdgcn_sched_barrier(0);   // keep only two tiles of activations in flight
             }
-            if (++st == spt || s + 1 == s1) {                                // end of the row tile or of this wave's range
-                flush(rt);
-                if (st == spt) { st = 0; rt++; }
-            }
         }
+        flush(rt);
     }
 }
 
@@ -937,16 +935,18 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
 
 template <int FMT, typename X2, int THREADS, int TOKTILES>
 static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    const uint32_t total = (uint32_t)((N + 31) / 32) * (uint32_t)((KB + 1) / 2);
+    // workgroups = groups of row tiles (one tile per wave) x ranges of block pairs; enough ranges to fill the chip, but
+    // at least two steps each to amortise the write-back of a partial tile
     constexpr uint32_t wpg = THREADS / 64;
-    const uint32_t waves = (uint32_t)ctx->num_cu * wpg;
-    uint32_t spw = (total + waves - 1) / waves;
-    if (spw < 2) spw = 2;                                               // amortise the write-back of a partial tile
-    const int grid = (int)((total + spw * wpg - 1) / (spw * wpg));
+    const uint32_t n_rt = (uint32_t)((N + 31) / 32), spt = (uint32_t)((KB + 1) / 2);
+    const uint32_t groups = (n_rt + wpg - 1) / wpg;
+    uint32_t kranges = (uint32_t)ctx->num_cu / groups;
+    kranges = std::max(1u, std::min(kranges, std::max(1u, spt / 2)));
+    kranges = std::min(kranges, 65535u);
     const size_t lds = ctx->lay.blob_bytes;
     if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES>, lds)) return rc;
-    hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(grid), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, spw, d_y);
+    hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(groups, kranges), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kranges, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
 }
