@@ -326,14 +326,14 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     const int wg_r0 = blockIdx.x * rows_per_wg;
     const int wg_r1 = min(N, wg_r0 + rows_per_wg);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: loop control below is wave-uniform
+    // the words of this wave's first batch are requested now: their trip from HBM overlaps the table copy below
+    RawBlock first_raw;
     {
-        // touch this thread's first index and gain now: their trip from HBM overlaps the table load below
-        const size_t nb = (size_t)(wg_r1 - wg_r0) * KB;
-        const size_t k = (size_t)wg_r0 * KB + min((size_t)threadIdx.x, nb - 1);
-        uint64_t warm_i;
-        uint16_t warm_g;
-        load_block<FMT>(idx, gain, cd, k, warm_i, warm_g);
-        asm volatile("" ::"v"((uint32_t)warm_i), "v"((uint32_t)(warm_i >> 32)), "v"((uint32_t)warm_g));
+        const uint32_t nblk = (uint32_t)min(rows_per_pass, wg_r1 - wg_r0) * (uint32_t)KB;
+        const size_t blk0 = (size_t)wg_r0 * KB;
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
+        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
+        load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
@@ -358,15 +358,16 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             // the next batch are requested before this one is decoded, and the next batch's class search and digit
             // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
             struct Fetch { RawBlock raw; uint32_t row, b; uint16_t g; bool live; };
-            auto fetch = [&](uint32_t base, Fetch& f) {
+            auto place = [&](uint32_t base, Fetch& f) {
                 const uint32_t fb = base + lane;
                 f.live = fb < nblk;
                 const uint32_t fbc = f.live ? fb : nblk - 1;
                 // fbc < 64*KB and KB < 8192: ceil(2^32/KB) is an exact reciprocal; otherwise divide
                 f.row = kb_magic ? __umulhi(fbc, kb_magic) : fbc / (uint32_t)KB;
                 f.b = fbc - llvq::mul24(f.row, (uint32_t)KB);
-                load_raw_near<FMT>(idx0, gain0, fbc, f.raw);
+                return fbc;
             };
+            auto fetch = [&](uint32_t base, Fetch& f) { load_raw_near<FMT>(idx0, gain0, place(base, f), f.raw); };
             auto front_of = [&](Fetch& f, bool& ok) {
                 uint64_t I;
                 finish_block<FMT>(f.raw, cd, I, f.g);
@@ -381,7 +382,12 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             llvq::Front front_cur, front_nxt;
             bool ok_cur = false, ok_nxt = false;
             if (base < nblk) {
-                fetch(base, cur);
+                if (r0 == wg_r0 && m0 == 0) {                        // the batch requested before the table copy
+                    place(base, cur);
+                    cur.raw = first_raw;
+                } else {
+                    fetch(base, cur);
+                }
                 front_cur = front_of(cur, ok_cur);
             }
             // one batch: kMore says whether another batch follows.  The two cases are separate copies of the code so that
