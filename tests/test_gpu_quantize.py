@@ -105,3 +105,35 @@ def test_quantize_smaller_cut_and_sizes(oracle13):
     pts, idx, score = g.llvq_quantize(e)
     assert pts.shape == (0, 24)
     g.close()
+
+
+def test_gaussian_source_table_rows_with_gain_bits():
+    """The quantiser end to end against figures the paper prints (App. I table, shape-gain rows at 2 bits per
+    dimension): angular search over norm(Lambda_24(m)), the norm coded with 0, 1 or 2 bits by a chi_24-matched
+    gain code, per-dimension squared error of a unit Gaussian source.  200,000 blocks: the sampling error is far
+    below half a unit of the last printed digit."""
+    import os
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2603_11021_amd import LLVQ
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "gaussian_source_mse.txt"))
+            if l.strip() and not l.startswith("#")]
+    printed = {(r[0], int(r[1])): float(r[2]) for r in rows}
+    rng = np.random.default_rng(2026)
+    w = rng.standard_normal((200000, 24)).astype(np.float32)
+    dw = _dev(w)
+    w64 = w.astype(np.float64)
+    nrm = np.linalg.norm(w64, axis=1)
+    for m, bits in [(13, 0), (12, 1), (11, 2)]:
+        pts, _, _ = LLVQ(m, 0).llvq_quantize(dw, LLVQ_ANGULAR, want_idx=False)
+        p = pts.cpu().numpy().astype(np.float64)
+        assert ((p ** 2).sum(axis=1) <= 16 * m).all()
+        u = p / np.linalg.norm(p, axis=1, keepdims=True)
+        levels = synth.chi_gain_levels(bits).astype(np.float64) * np.sqrt(24.0)        # levels for the norm of 24 unit normals
+        g = levels[np.abs(nrm[:, None] - levels[None, :]).argmin(axis=1)]
+        per_block = ((w64 - g[:, None] * u) ** 2).sum(axis=1) / 24.0
+        mse, sem = per_block.mean(), per_block.std() / np.sqrt(per_block.size)
+        want = printed[("norm(Lambda24(%d))" % m, bits)]
+        assert sem < 1e-4
+        assert abs(mse - want) < 0.0005 + 3 * sem, (m, bits, mse)

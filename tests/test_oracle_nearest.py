@@ -1,6 +1,6 @@
 """Pins of the oracle's nearest-point search (paper Sec. 3.1), none of which uses the search itself:
 brute force over every point of the small ball cuts, lattice points as inputs, monotonicity in the cut, and the
-Gaussian-source distortion the paper prints for shape-gain with no gain bits (App. I table: 0.085)."""
+Gaussian-source distortions the paper prints for shape-gain with 0, 1 and 2 gain bits (App. I table)."""
 import os
 from math import exp, lgamma, sqrt
 
@@ -116,3 +116,32 @@ def test_gaussian_source_distortion_matches_the_paper(oracle13):
     assert abs(mse - printed) < 0.0005 + 3 * sem, mse          # half a unit of the last printed digit + sampling error
     _, bad = oracle13.encode(got)
     assert bad == 0
+
+
+@pytest.mark.parametrize("m,bits", [(12, 1), (11, 2)])
+def test_gaussian_source_distortion_with_gain_bits_matches_the_paper(m, bits):
+    """shape-gain over norm(Lambda_24(m)) with a 1- or 2-bit gain code (App. I table: 0.078 for m = 12, 0.080 for
+    m = 11), the norm going to the nearest of 2^bits chi_24-matched levels (see the golden file for this reading).
+    Direction and norm r of a Gaussian block are independent, so the per-dimension distortion is
+    (E r^2 - 2 E[r g(r)] E cos + E g(r)^2) / 24: the expectations over r by numerical integration, E cos from the
+    oracle's search on a sample."""
+    from scipy import integrate
+    from scipy.stats import chi
+    L = 1 << bits
+    levels = chi.ppf((np.arange(L) + 0.5) / L, 24)
+    cuts = np.concatenate([[0.0], (levels[1:] + levels[:-1]) / 2, [np.inf]])
+    e_rg = sum(levels[i] * integrate.quad(lambda r: r * chi.pdf(r, 24), cuts[i], cuts[i + 1])[0] for i in range(L))
+    e_g2 = sum(levels[i] ** 2 * (chi.cdf(cuts[i + 1], 24) - chi.cdf(cuts[i], 24)) for i in range(L))
+    rng = np.random.default_rng(56 + m)
+    w = rng.standard_normal((200, 24))
+    oracle = Oracle(m)
+    got, sc = oracle.nearest(w)
+    assert ((got.astype(np.int64) ** 2).sum(axis=1) <= 16 * m).all()
+    cos = sc / np.linalg.norm(w, axis=1)
+    mse = (24.0 - 2.0 * e_rg * cos.mean() + e_g2) / 24.0
+    sem = 2.0 * e_rg / 24.0 * cos.std() / sqrt(cos.size)
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "gaussian_source_mse.txt"))
+            if l.strip() and not l.startswith("#")]
+    printed = {(r[0], int(r[1])): float(r[2]) for r in rows}[("norm(Lambda24(%d))" % m, bits)]
+    assert sem < 8e-4
+    assert abs(mse - printed) < 0.0005 + 3 * sem, mse
