@@ -166,13 +166,15 @@ def main():
         "hbm_copy_measured_GBs": copy_gbs, "pct_of_measured_copy": 100.0 * gbs / copy_gbs,
         "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
         "max_rel_err_vs_oracle": err,
-        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+        # the kernel is bound by the vector-ALU (and LDS-gather) work of the index decode, not by HBM: the roofline is the
+        # ALU one (vector instructions per block, measured, x blocks / kernel time against one instruction per lane and
+        # cycle); the HBM view of the same launch (algorithmic bytes against 8 TB/s) rides along
+        "roofline": {"bound": "alu", "achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
+                     "unit": "T lane-ops/s", "frac": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12 / ALU_PEAK_TLOPS,
                      "traffic": TRAFFIC_BYTES_PER_LAUNCH, "kernel": "matmul_kernel<U48,f16,BIG_GLOBAL>", "kernel_ms": kern_ms,
-                     "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk,
-                     # the kernel is bound by the vector ALU work of the index decode, not by HBM: second roofline
-                     "alu": {"achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
-                             "unit": "T lane-ops/s", "frac": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12 / ALU_PEAK_TLOPS,
-                             "valu_instructions_per_block": VALU_PER_BLOCK}},
+                     "valu_instructions_per_block": VALU_PER_BLOCK,
+                     "hbm": {"achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                             "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk}},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
