@@ -54,8 +54,13 @@ LLVQ_HD TabPtrs make_tab_ptrs(TabBase base, const unsigned char* gbase, const Ta
 template <typename V>
 LLVQ_HD V tab_load(TabBase p) {
 #if defined(__HIP_DEVICE_COMPILE__)
-    if constexpr (std::is_class<V>::value) {
-        static_assert(sizeof(V) % 16 == 0, "records are multiples of 16 bytes");
+    if constexpr (std::is_class<V>::value && sizeof(V) == 8) {
+        typedef uint32_t Piece __attribute__((ext_vector_type(2)));
+        const Piece v = *reinterpret_cast<const LLVQ_LDS Piece*>(p);
+        struct Pieces { uint32_t q[2]; } t = {{v[0], v[1]}};
+        return __builtin_bit_cast(V, t);
+    } else if constexpr (std::is_class<V>::value) {
+        static_assert(sizeof(V) % 16 == 0, "records are 8 bytes or multiples of 16 bytes");
         struct Pieces { uint32_t q[sizeof(V) / 4]; } t;
         typedef uint32_t Piece __attribute__((ext_vector_type(4)));
         const LLVQ_LDS Piece* src = reinterpret_cast<const LLVQ_LDS Piece*>(p);

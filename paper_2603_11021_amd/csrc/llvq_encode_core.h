@@ -17,12 +17,12 @@ namespace llvq {
 constexpr uint64_t kInvalidIndex = ~0ull;
 
 struct EncPtrs {
-    const unsigned char* base;
+    TabBase base;               // the encoder blob in LDS (address 0 on the device, see TabBase)
     uint32_t hash_mult[2];
     uint32_t m_max;
 };
 
-LLVQ_HD EncPtrs make_enc_ptrs(const unsigned char* base, const EncLayout& L) {
+LLVQ_HD EncPtrs make_enc_ptrs(TabBase base, const EncLayout& L) {
     EncPtrs T;
     T.base = base;
     T.hash_mult[0] = L.hash_mult[0];
@@ -33,7 +33,7 @@ LLVQ_HD EncPtrs make_enc_ptrs(const unsigned char* base, const EncLayout& L) {
 
 template <typename V, uint32_t OFF>
 LLVQ_HD V enc_at(const EncPtrs& T, uint32_t byte_off) {
-    return *reinterpret_cast<const V*>(T.base + OFF + byte_off);
+    return tab_load<V>(T.base + OFF + byte_off);
 }
 
 // v holds one bit per byte (bit 0 of each byte): the four bits, byte 0 lowest

@@ -779,7 +779,7 @@ __global__ void __launch_bounds__(kThreads, 8) encode_kernel(const unsigned char
                                                           const uint2* __restrict__ pts, size_t n, void* __restrict__ idx,
                                                           size_t out_stride) {
     load_tables(blob, lay.bytes);
-    const llvq::EncPtrs T = llvq::make_enc_ptrs(g_lds, lay);
+    const llvq::EncPtrs T = llvq::make_enc_ptrs(lds_origin(), lay);
     for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
         const uint2 p0 = pts[3 * k], p1 = pts[3 * k + 1], p2 = pts[3 * k + 2];
         const uint32_t x[6] = {p0.x, p0.y, p1.x, p1.y, p2.x, p2.y};
