@@ -481,7 +481,7 @@ bool build_tables(int m_max, Tables& out) {
             uint32_t o = 0;
             for (int pos = 0, k = 0; pos < 6; pos++)
                 if ((F >> pos) & 1u) { if ((src >> pos) & 1u) o |= 1u << k; k++; }
-            pext6[F << 6 | (src ^ F)] = (uint8_t)o;            // swizzled like the deposit tables
+            pext6[F << 6 | (src ^ F)] = (uint8_t)o;            // XOR with the mask: equal sources of different masks in different LDS banks
         }
     // g16[H][p]: number of 16-bit masks of popcount p whose bits 12..15, read as a number, are below H
     std::vector<uint16_t> g16(16 * 17, 0);
