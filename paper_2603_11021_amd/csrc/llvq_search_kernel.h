@@ -127,21 +127,26 @@ __device__ __forceinline__ void make_operands(const float (&v)[24], float x24, f
     }
 }
 
-// best score of one class tile against one column tile, per lane (the lane's 16 accumulator rows)
+// best score of one class tile against one column tile, per lane (the lane's 16 accumulator rows).  Angular metric:
+// score = product x factor of the class.  Euclidean metric: score = product + offset of the class, and the offsets
+// are what the accumulators start from, so the products need no further instruction.
 template <int METRIC>
 __device__ __forceinline__ float tile_best(const uint4 (&A)[2], const ColumnOperands& B, const float (&scale)[16]) {
     f32x16_t acc;
 #pragma unroll
-    for (int r = 0; r < 16; r++) acc[r] = 0.0f;
+    for (int r = 0; r < 16; r++) acc[r] = METRIC == 0 ? 0.0f : scale[r];
 #pragma unroll
     for (int t = 0; t < 3; t++) {
 #pragma unroll
         for (int kb = 0; kb < 2; kb++)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, A[kb]), __builtin_bit_cast(bf16x8_t, B.b[t][kb]), acc, 0, 0, 0);
     }
-    float best = -INFINITY;
+    float x[16];
 #pragma unroll
-    for (int r = 0; r < 16; r++) best = fmaxf(best, METRIC == 0 ? acc[r] * scale[r] : acc[r] + scale[r]);
+    for (int r = 0; r < 16; r++) x[r] = METRIC == 0 ? acc[r] * scale[r] : acc[r];
+    float best = fmaxf(x[0], x[1]);
+#pragma unroll
+    for (int r = 2; r < 16; r += 2) best = fmaxf(fmaxf(x[r], x[r + 1]), best);       // compiles to v_max3_f32
     return best;
 }
 
