@@ -50,7 +50,12 @@ __device__ __forceinline__ void load_tables(const unsigned char* __restrict__ bl
     // addresses (base in M0, wave-uniform); chunks of 1 KB are dealt round-robin to the waves
     const uint32_t n16 = bytes / 16;
     const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    for (uint32_t c = wave; c * 64 < n16; c += THREADS / 64) {
+    const uint32_t nchunk = (n16 + 63) / 64;
+    // workgroups start at different chunks: all of them copy the same bytes at the same time, and in the same order
+    // they would all queue at the same L2 channel
+    const uint32_t rot = (blockIdx.x * 5u) % nchunk;
+    for (uint32_t c0 = wave; c0 < nchunk; c0 += THREADS / 64) {
+        const uint32_t c = c0 + rot < nchunk ? c0 + rot : c0 + rot - nchunk;
         const uint32_t k = c * 64 + lane;
         if (k < n16)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(blob + (size_t)k * 16),
