@@ -378,3 +378,51 @@ def test_calls_run_on_the_callers_stream(gpu, oracle13):
     assert np.abs(y.cpu().numpy() - ref).max() / np.abs(ref).max() <= TOL
     want, _ = oracle13.decode(idx.reshape(-1))
     assert np.array_equal(out.cpu().numpy(), want)
+
+
+def test_one_context_from_several_threads(gpu, oracle13):
+    """the calls the header lists as callable from several threads on one context: four host threads, each with its
+    own stream, inputs and outputs, interleave decode, encode and matmul calls"""
+    import threading
+    import torch
+    cases = []
+    for t in range(4):
+        idx, gain, x = synth.layer(6, 5200 + t, 200 + 37 * t, 24 * (20 + 3 * t), 1 + (t % 2) * 3)
+        cases.append((idx, gain, x))
+    torch.cuda.synchronize()
+    results, errors = [None] * 4, []
+
+    def work(t):
+        try:
+            idx, gain, x = cases[t]
+            N, KB = idx.shape
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                d_x, d_idx, d_gain = _dev(x).half(), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1))
+                y = torch.empty((x.shape[0], N), dtype=torch.float32, device="cuda:0")
+                pts = torch.empty((N * KB, 24), dtype=torch.int8, device="cuda:0")
+                back = torch.empty((N * KB, 6), dtype=torch.uint8, device="cuda:0")
+            s.synchronize()
+            for _ in range(20):                # outputs allocated once: the loop only enqueues library calls
+                gpu.llvq_matmul(d_x, d_idx, d_gain, N, KB, out=y, stream=s)
+                gpu.llvq_decode_i8(d_idx, out=pts, stream=s)
+                gpu.llvq_encode(pts, out=back, stream=s)
+            s.synchronize()
+            results[t] = (y.cpu().numpy(), pts.cpu().numpy(), back.cpu().numpy())
+        except Exception as e:          # reported by the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors
+    for t in range(4):
+        idx, gain, x = cases[t]
+        y, pts, back = results[t]
+        ref = oracle13.matmul(x, idx, gain)
+        assert np.abs(y - ref).max() / np.abs(ref).max() <= TOL
+        want, _ = oracle13.decode(idx.reshape(-1))
+        assert np.array_equal(pts, want)
+        assert np.array_equal(back, synth.pack_u48(idx).reshape(-1, 6))
