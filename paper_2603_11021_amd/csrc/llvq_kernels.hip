@@ -649,7 +649,8 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
 // read from global memory), which leaves room for two activation buffers.
 // Shape used: 8 waves x 8 token tiles (strips of 256 rows, passes of 256 tokens; 128 accumulator registers, two waves per
 // SIMD).  16 waves x 2 token tiles was measured for M <= 64 and lost to mfma_kernel (75.6 against 68 us on 14336 x 4104).
-constexpr uint32_t kATokenPitch = 104;                 // bytes per token in the staged tile: 96 of data, padded against bank conflicts
+constexpr uint32_t kATokenPitch = 112;                 // bytes per token in the staged tile: 96 of data, padded so that rows stay 16-byte
+                                                       // aligned (128-bit LDS accesses) and eight consecutive tokens cover all banks
 
 template <int FMT, typename X2, int WAVES, int TT>
 __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
@@ -684,10 +685,8 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
     };
     auto stage_store = [&](uint32_t buf, const uint4 (&v)[3]) {
         if (!s_on) return;
-        uint2* d = reinterpret_cast<uint2*>(s_dst + buf * kABufBytes);
-        d[0] = make_uint2(v[0].x, v[0].y); d[1] = make_uint2(v[0].z, v[0].w);
-        d[2] = make_uint2(v[1].x, v[1].y); d[3] = make_uint2(v[1].z, v[1].w);
-        d[4] = make_uint2(v[2].x, v[2].y); d[5] = make_uint2(v[2].z, v[2].w);
+        uint4* d = reinterpret_cast<uint4*>(s_dst + buf * kABufBytes);
+        d[0] = v[0]; d[1] = v[1]; d[2] = v[2];
     };
 
     float16_t acc[TT];
@@ -749,10 +748,8 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
             const u32x4 bw = {wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]};
 #pragma unroll
             for (int t = 0; t < TT; t++) {
-                // token rows are 8-byte aligned in the staged tile (pitch 104): two 8-byte reads
-                const uint2* ap = reinterpret_cast<const uint2*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 16u);
-                const uint2 a0 = ap[0], a1 = ap[1];
-                acc[t] = Mma<X2>::mma(u32x4{a0.x, a0.y, a1.x, a1.y}, bw, acc[t]);
+                const u32x4 a = *reinterpret_cast<const u32x4*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 16u);
+                acc[t] = Mma<X2>::mma(a, bw, acc[t]);
             }
         }
         stage_store((st + 1) & 1u, nextv);
