@@ -284,15 +284,6 @@ def extra_shapes(q, synth, torch, dev):
         us = timeit(lambda: q.llvq_matmul(x, idx, gain, N, KB, out=y))
         print("matmul %dx%d M=%-4d %s: %9.2f us  %.1f GB/s packed  %.1f TFLOP/s" %
               (N, 24 * KB, M, str(dt).split(".")[-1], us, N * KB * 8 / us / 1e3, 2.0 * M * N * KB * 24 / us / 1e6), file=sys.stderr)
-    # the same product with a caller workspace: dequantise once, then the library GEMM
-    ws = torch.empty(N * KB * 24, dtype=torch.bfloat16, device=dev)
-    for M in (256, 1024):
-        x = torch.from_numpy(synth.activations(r, M, K)).to(dev).to(torch.bfloat16)
-        y = torch.empty((M, N), dtype=torch.float32, device=dev)
-        us = timeit(lambda: q.llvq_matmul(x, idx, gain, N, KB, out=y, workspace=ws))
-        print("matmul_ws %dx%d M=%-4d bfloat16: %9.2f us  %.1f TFLOP/s (dequantise once + library GEMM)" %
-              (N, 24 * KB, M, us, 2.0 * M * N * KB * 24 / us / 1e6), file=sys.stderr)
-    del ws
     n = N * KB
     for name, dt in (("int8", None), ("float16", torch.float16), ("bfloat16", torch.bfloat16), ("float32", torch.float32)):
         if dt is None:
@@ -311,6 +302,16 @@ def extra_shapes(q, synth, torch, dev):
     same = bool(torch.equal(back.reshape(-1), idx))
     print("encode int8 points -> index %d blocks: %9.2f us  %.2f G blocks/s  read+write %.1f GB/s  round trip %s" %
           (n, us, n / us / 1e3, n * 30 / us / 1e3, "exact" if same else "MISMATCH"), file=sys.stderr)
+    # the same product with a caller workspace: dequantise once, then the library GEMM (after the bulk-decode timings:
+    # kernels timed right after a long library GEMM run several microseconds slower, presumably at a lower clock)
+    ws = torch.empty(N * KB * 24, dtype=torch.bfloat16, device=dev)
+    for M in (256, 1024):
+        x = torch.from_numpy(synth.activations(r, M, K)).to(dev).to(torch.bfloat16)
+        y = torch.empty((M, N), dtype=torch.float32, device=dev)
+        us = timeit(lambda: q.llvq_matmul(x, idx, gain, N, KB, out=y, workspace=ws))
+        print("matmul_ws %dx%d M=%-4d bfloat16: %9.2f us  %.1f TFLOP/s (dequantise once + library GEMM)" %
+              (N, 24 * KB, M, us, 2.0 * M * N * KB * 24 / us / 1e6), file=sys.stderr)
+    del ws
     # quantiser: nearest direction of Lambda_24(13) for Gaussian blocks (one 4096 x 384 slice of a layer)
     from paper_2603_11021_amd import LLVQ_ANGULAR
     nq = 4096 * 16

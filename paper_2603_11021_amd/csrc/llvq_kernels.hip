@@ -878,12 +878,14 @@ int grid_for(const llvq_ctx* ctx, size_t n, int per_cu = 1) {
 
 }  // namespace
 
-// short launches keep only the small tables in LDS and run two workgroups per compute unit (see the kernels)
-static bool small_launch(const llvq_ctx* ctx, size_t n) { return n < (size_t)ctx->num_cu * 64 * 256; }
+// Short launches keep only the small tables in LDS and run two workgroups per compute unit (see the kernels); long ones
+// copy all tables and run one.  The crossover, in wave-batches of 64 blocks per compute unit, depends on how much the
+// kernel stores (measured on 14336 x 4104 and on slices and multiples of it): int8 output about 768, 16-bit output about 64.
+static bool small_launch(const llvq_ctx* ctx, size_t n, size_t batches_per_cu) { return n < (size_t)ctx->num_cu * 64 * batches_per_cu; }
 
 template <int FMT>
 static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
-    const bool small = small_launch(ctx, n);
+    const bool small = small_launch(ctx, n, 768);
     const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
     const int grid = grid_for(ctx, n, small ? 2 : 1);
     if (small) {
@@ -900,7 +902,7 @@ static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, si
 template <int FMT>
 static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, const Code& cd, size_t n, void* d_out, int out_dtype, hipStream_t st) {
     // fp32 output is bound by its stores: it always takes the one-workgroup variant
-    const bool small = small_launch(ctx, n) && out_dtype != LLVQ_F32;
+    const bool small = small_launch(ctx, n, 64) && out_dtype != LLVQ_F32;
     const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
     const int grid = grid_for(ctx, n, small ? 2 : 1);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
