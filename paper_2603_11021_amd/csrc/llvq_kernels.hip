@@ -342,9 +342,11 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     }
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
+    float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
+    // the accumulators of the first pass are cleared here: the barrier that ends the table copy covers them too
+    for (int i = threadIdx.x; i < kRowsPerPass * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
     load_tables(blob, table_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     // rows_per_pass <= kRowsPerPass keeps a pass below 2^24 blocks (block numbers inside a pass go through 24-bit multiplies)
@@ -357,8 +359,10 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
-            for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
-            __syncthreads();
+            if (r0 != wg_r0 || m0 != 0) {
+                for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+                __syncthreads();
+            }
             // a wave takes every 16th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
             // the next batch are requested before this one is decoded, and the next batch's class search and digit
             // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
