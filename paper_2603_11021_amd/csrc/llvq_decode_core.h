@@ -300,7 +300,11 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
         const uint32_t sb = odd ? cw : s1;                                  // odd: the word itself flips signs
         const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                // keep U as the domain bit
 
-        uint32_t o1 = 0, o0 = 0, os = 0, ou = 0;
+        // the running bit offsets start from a zero the compiler does not see through: with a literal 0 it rewrites the
+        // first chunk's bit-field extracts into shift-and-mask forms that cost one more instruction per table address
+        uint32_t zero = 0;
+        keep_product(zero);
+        uint32_t o1 = zero, o0 = zero, os = zero, ou = zero;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
