@@ -22,8 +22,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
 ALU_PEAK_TLOPS = 39.3          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one vector instruction per lane and cycle
-VALU_PER_BLOCK = 366           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
-TRAFFIC_BYTES_PER_LAUNCH = 7211213  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
+VALU_PER_BLOCK = 364           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
+TRAFFIC_BYTES_PER_LAUNCH = 7200973  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
 
 
 def main():
