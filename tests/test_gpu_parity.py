@@ -426,3 +426,28 @@ def test_one_context_from_several_threads(gpu, oracle13):
         want, _ = oracle13.decode(idx.reshape(-1))
         assert np.array_equal(pts, want)
         assert np.array_equal(back, synth.pack_u48(idx).reshape(-1, 6))
+
+
+def test_bulk_decode_at_llama3_70b_block_size(gpu, oracle13):
+    """the bulk decode at the size bench.py times it (one Llama-3-70B-shaped block: 35,704,832 blocks, the long-launch
+    variants of the kernels): sampled outputs against the oracle, every int8 block a point of a shell 2..13, and the
+    encoder returns every index"""
+    import torch
+    n = 35704832
+    rng = synth.rng_for(5, 700)
+    idx = synth.indices(rng, n)
+    gain = synth.gains(rng, n)
+    d_idx = _dev(synth.pack_u48(idx).reshape(-1))
+    pts = gpu.llvq_decode_i8(d_idx)
+    n2 = (pts.to(torch.int32) ** 2).sum(dim=1)
+    assert bool(((n2 % 16 == 0) & (n2 >= 32) & (n2 <= 208)).all())
+    back = gpu.llvq_encode(pts)
+    assert torch.equal(back.reshape(-1), d_idx)
+    sample = np.sort(np.random.default_rng(1).choice(n, 20000, replace=False))
+    want, _ = oracle13.decode(idx[sample])
+    assert np.array_equal(pts[torch.from_numpy(sample).to("cuda:0")].cpu().numpy(), want)
+    del pts, back, n2
+    w = gpu.llvq_decode(d_idx, _dev(gain), out_dtype=torch.bfloat16)
+    got = w[torch.from_numpy(sample).to("cuda:0")].float().cpu().numpy().astype(np.float64)
+    ref = oracle13.dequant(idx[sample], gain[sample])
+    assert (np.abs(got - ref) <= (2.0 ** -8 + 3 * 2.0 ** -24) * np.abs(ref) + 1e-30).all()
