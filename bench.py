@@ -368,6 +368,11 @@ def extra_shapes(q, synth, torch, dev):
     us = timeit(lambda: q.llvq_matmul_coded(x, w47, N, KB, 47, gain_lut=lut, out=y))
     print("matmul %dx%d M=1 coded 47+1 bits (6 B/block): %9.2f us  %.1f GB/s packed  %.2f G blocks/s" %
           (N, 24 * KB, us, n * 6 / us / 1e3, n / us / 1e3), file=sys.stderr)
+    packed = q.llvq_repack(idx, gain)
+    us = timeit(lambda: q.llvq_matmul_coded(x, packed, N, KB, 48, out=y))
+    print("matmul %dx%d M=1 packed words, index + fp16 gain in one aligned 64-bit word (8 B/block): %9.2f us  %.1f GB/s packed  "
+          "%.2f G blocks/s" % (N, 24 * KB, us, n * 8 / us / 1e3, n / us / 1e3), file=sys.stderr)
+    del packed
     from paper_2603_11021_amd import LLVQ_IDX_U24
     base = q.llvq_shell_offset(3)
     w24 = torch.from_numpy(synth.pack_u24(r.integers(0, q.llvq_shell_offset(4) - base, size=n, dtype=np.uint64)).reshape(-1)).to(dev)

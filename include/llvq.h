@@ -68,7 +68,7 @@ enum {
 /* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 13, on HIP device `device`.
  * Builds the constant tables (Golay words, class records, ranking tables) on the host and copies
  * them to the device.  The tables are immutable afterwards; llvq_decode*, llvq_matmul, llvq_matmul_coded, llvq_encode,
- * llvq_quantize and llvq_shell_offset may be called on one context from several threads.  llvq_matmul_ws,
+ * llvq_repack, llvq_quantize and llvq_shell_offset may be called on one context from several threads.  llvq_matmul_ws,
  * llvq_gptq_quantize (they share the context's BLAS handle) and llvq_validate (its counter) may not.   */
 int llvq_create(llvq_ctx** out, int m_max, int device);
 void llvq_destroy(llvq_ctx* ctx);
@@ -143,6 +143,15 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                       const void* d_idx, int fmt, int shape_bits, uint64_t base_index,
                       const void* d_gain_lut, const void* d_gain, int N, int KB,
                       float* d_y, void* stream);
+
+/* One aligned 64-bit word per block (8 bytes per block as with separate arrays: paper App. E, one integer carries
+ * shape and gain): d_packed[k] = index k (bits 0..47) | the fp16 bits of gain k (bits 48..63).
+ *   d_idx : n_blocks indices, LLVQ_IDX_U48 or LLVQ_IDX_U64;  d_gain: n_blocks fp16;  d_packed: n_blocks uint64, 8-byte aligned
+ * The packed array is read by llvq_decode_coded and llvq_matmul_coded called with fmt = LLVQ_IDX_U64, shape_bits = 48,
+ * d_gain_lut = NULL and d_gain = NULL: with no gain table and no gain array the gain of a block is taken from
+ * the top 16 bits of its word.  (llvq_decode_i8_coded ignores those bits anyway.)                            */
+int llvq_repack(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks,
+                uint64_t* d_packed, void* stream);
 
 /* Encoder side of the index map (paper Sec. 3.2, "bijective indexing"; the inverse of the dequantiser of
  * App. A): d_idx[k] = the index I with llvq_decode_i8(I) = d_x[k][0..23].

@@ -58,6 +58,7 @@ def _load():
     lib.llvq_decode_coded.argtypes = [vp, vp, i32, i32, u64, vp, vp, sz, vp, i32, vp]; lib.llvq_decode_coded.restype = i32
     lib.llvq_matmul_coded.argtypes = [vp, vp, i32, i32, vp, i32, i32, u64, vp, vp, i32, i32, vp, vp]; lib.llvq_matmul_coded.restype = i32
     lib.llvq_encode.argtypes = [vp, vp, sz, vp, i32, vp]; lib.llvq_encode.restype = i32
+    lib.llvq_repack.argtypes = [vp, vp, i32, vp, sz, vp, vp]; lib.llvq_repack.restype = i32
     lib.llvq_quantize.argtypes = [vp, vp, sz, i32, vp, vp, i32, vp, vp]; lib.llvq_quantize.restype = i32
     lib.llvq_gptq_workspace_bytes.argtypes = [i32]; lib.llvq_gptq_workspace_bytes.restype = sz
     lib.llvq_gptq_quantize.argtypes = [vp, vp, i32, i32, sz, vp, vp, i32, vp, vp, sz, vp]; lib.llvq_gptq_quantize.restype = i32
@@ -227,6 +228,18 @@ class LLVQ:
             out = (torch.empty((n, 6), dtype=torch.uint8, device=pts.device) if fmt == LLVQ_IDX_U48
                    else torch.empty(n, dtype=torch.int64, device=pts.device))
         self._check(self._lib.llvq_encode(self._h, pts.data_ptr(), n, out.data_ptr(), fmt, _stream_handle(stream)), "llvq_encode")
+        return out
+
+    def llvq_repack(self, idx, gain, out=None, stream=None):
+        """idx (uint8 6 bytes per block, or int64) + gain float16 -> int64 [n]: index | gain bits << 48"""
+        import torch
+        fmt, n = self._idx_fmt(idx)
+        if gain.dtype != torch.float16 or gain.numel() != n:
+            raise LLVQError("gain must hold one float16 per block")
+        if out is None:
+            out = torch.empty(n, dtype=torch.int64, device=idx.device)
+        self._check(self._lib.llvq_repack(self._h, idx.data_ptr(), fmt, gain.data_ptr(), n, out.data_ptr(), _stream_handle(stream)),
+                    "llvq_repack")
         return out
 
     def llvq_quantize(self, w, metric=LLVQ_ANGULAR, fmt=LLVQ_IDX_U48, want_idx=True, stream=None):

@@ -81,7 +81,7 @@ __device__ __forceinline__ float wave_sum_to_last(float v) {
 template <int FMT>
 __device__ __forceinline__ uint64_t load_index(const void* __restrict__ idx, size_t k) {
     if constexpr (FMT == LLVQ_IDX_U64) {
-        return reinterpret_cast<const uint64_t*>(idx)[k] & 0xFFFFFFFFFFFFull;
+        return reinterpret_cast<const uint64_t*>(idx)[k];             // callers mask: the top 16 bits may carry a gain
     } else if constexpr (FMT == LLVQ_IDX_U24) {
         const uint8_t* p = reinterpret_cast<const uint8_t*>(idx) + 3 * k;
         return (uint64_t)p[0] | ((uint64_t)p[1] << 8) | ((uint64_t)p[2] << 16);
@@ -99,16 +99,20 @@ template <int FMT> constexpr uint32_t kWordBytes = FMT == LLVQ_IDX_U64 ? 8u : FM
 struct Code {
     uint64_t base;
     uint64_t mask;
-    const uint16_t* lut;       // nullptr: gains come from the per-block array
+    const uint16_t* lut;       // nullptr: gains come from the per-block array or from the word itself
     uint32_t shape_bits;
     uint32_t lut_last;         // last valid entry of lut
+    uint32_t gain_in_word;     // 64-bit words only, lut == nullptr: bits 48..63 of the word are the block's fp16 gain
+    // true when the kernels have to read the per-block gain array
+    __host__ __device__ bool gain_array() const { return lut == nullptr && !gain_in_word; }
 };
 
 template <int FMT>
 __device__ __forceinline__ void load_block(const void* __restrict__ idx, const uint16_t* __restrict__ gain, const Code& cd,
                                            size_t k, uint64_t& I, uint16_t& g) {
     const uint64_t v = load_index<FMT>(idx, k);
-    if (cd.lut) g = cd.lut[min((uint32_t)(v >> cd.shape_bits), cd.lut_last)];
+    if (cd.lut) g = cd.lut[min((uint32_t)((v & 0xFFFFFFFFFFFFull) >> cd.shape_bits), cd.lut_last)];
+    else if (FMT == LLVQ_IDX_U64 && cd.gain_in_word) g = (uint16_t)(v >> 48);
     else g = gain ? gain[k] : (uint16_t)0;
     I = (v & cd.mask) + cd.base;
 }
@@ -171,6 +175,7 @@ __device__ __forceinline__ void finish_block(const RawBlock& r, const Code& cd, 
     else if constexpr (FMT == LLVQ_IDX_U24) v = (uint64_t)(r.a | (r.b << 8) | (r.c << 16));
     else v = (uint64_t)r.a | ((uint64_t)r.c << 32);
     g = cd.lut ? cd.lut[min((uint32_t)(v >> cd.shape_bits), cd.lut_last)] : r.g;
+    if constexpr (FMT == LLVQ_IDX_U64) { if (cd.gain_in_word) g = (uint16_t)(r.b >> 16); }
     I = (v & cd.mask) + cd.base;
 }
 
@@ -244,7 +249,7 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
     auto request = [&](size_t base, RawBlock& r) {
         const size_t b0 = base < n ? base : n - 1;
         const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + b0 * kWordBytes<FMT>;
-        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + b0) : idx0;
+        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + b0) : idx0;
         load_raw_near<FMT>(idx0, gain0, (uint32_t)min((size_t)t, n - 1 - b0), r);
     };
     size_t base = (size_t)blockIdx.x * kThreads;
@@ -337,7 +342,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         const uint32_t nblk = (uint32_t)min(rows_per_pass, wg_r1 - wg_r0) * (uint32_t)KB;
         const size_t blk0 = (size_t)wg_r0 * KB;
         const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
-        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
+        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
@@ -356,7 +361,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         const size_t blk0 = (size_t)r0 * KB;
         // wave-uniform starts of this pass in the index and gain arrays (gains from a table: any readable address)
         const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
-        const unsigned char* gain0 = cd.lut == nullptr ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
+        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
             if (r0 != wg_r0 || m0 != 0) {
@@ -707,7 +712,7 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
         const uint32_t b = 2 * st + half;
         q.live = wrow < N && b < (uint32_t)KB;
         const size_t k = (size_t)min(wrow, N - 1) * KB + min(b, (uint32_t)KB - 1);
-        load_raw<FMT>(idx, gain, cd.lut == nullptr, k, q.raw);
+        load_raw<FMT>(idx, gain, cd.gain_array(), k, q.raw);
     };
     auto front_of = [&](const Blk& q, bool& ok, uint16_t& gb) {
         uint64_t I;
@@ -805,12 +810,19 @@ __global__ void __launch_bounds__(kThreads, 8) encode_kernel(const unsigned char
 
 namespace {
 
+// ---- llvq_repack --------------------------------------------------------------------------------------
+template <int FMT>
+__global__ void repack_kernel(const void* __restrict__ idx, const uint16_t* __restrict__ gain, size_t n, uint64_t* __restrict__ out) {
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
+        out[k] = (load_index<FMT>(idx, k) & 0xFFFFFFFFFFFFull) | ((uint64_t)gain[k] << 48);
+}
+
 // ---- llvq_validate ------------------------------------------------------------------------------------
 template <int FMT>
 __global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
     unsigned long long local = 0;
     for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
-        local += load_index<FMT>(idx, k) >= npoints;
+        local += (load_index<FMT>(idx, k) & 0xFFFFFFFFFFFFull) >= npoints;
     for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
     if ((threadIdx.x & 63) == 0 && local) atomicAdd(bad, local);
 }
@@ -997,6 +1009,13 @@ static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n,
     return 0;
 }
 
+template <int FMT>
+static int launch_repack(const void* d_idx, const void* d_gain, size_t n, uint64_t* d_packed, hipStream_t st) {
+    const unsigned grid = (unsigned)std::min<size_t>((n + 255) / 256, 65536);
+    hipLaunchKernelGGL(repack_kernel<FMT>, dim3(grid), dim3(256), 0, st, d_idx, reinterpret_cast<const uint16_t*>(d_gain), n, d_packed);
+    return 0;
+}
+
 template <int FMT, typename X2, int WAVES, int TT>
 static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     constexpr int kRows = 32 * WAVES, kTokens = 32 * TT;
@@ -1045,6 +1064,7 @@ Code plain_code(int fmt) {
     cd.lut = nullptr;
     cd.shape_bits = (uint32_t)word_bits(fmt);
     cd.lut_last = 0;
+    cd.gain_in_word = 0;
     return cd;
 }
 
@@ -1060,6 +1080,7 @@ int make_code(int fmt, int shape_bits, uint64_t base_index, const void* d_gain_l
     cd.lut = reinterpret_cast<const uint16_t*>(d_gain_lut);
     cd.shape_bits = (uint32_t)shape_bits;
     cd.lut_last = (1u << (wb - shape_bits)) - 1;
+    cd.gain_in_word = 0;
     return LLVQ_OK;
 }
 
@@ -1076,7 +1097,7 @@ int decode_impl(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, c
                 int out_dtype, void* stream) {
     if (out_dtype != LLVQ_F16 && out_dtype != LLVQ_BF16 && out_dtype != LLVQ_F32) return LLVQ_EINVAL;
     if (n_blocks == 0) return LLVQ_OK;
-    if (!d_out || (!d_gain && !cd.lut)) return LLVQ_EINVAL;
+    if (!d_out || (!d_gain && cd.gain_array())) return LLVQ_EINVAL;
     if (int rc = check_idx(d_idx, fmt)) return rc;
     if (!aligned(d_out, 16) || !aligned(d_gain, 2)) return LLVQ_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
@@ -1085,7 +1106,7 @@ int decode_impl(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, c
 
 int matmul_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain, const Code& cd,
                 int N, int KB, float* d_y, void* stream) {
-    if (!d_x || (!d_gain && !cd.lut) || !d_y) return LLVQ_EINVAL;
+    if (!d_x || (!d_gain && cd.gain_array()) || !d_y) return LLVQ_EINVAL;
     if (M < 1 || M > 1024 || N < 1 || KB < 1 || KB >= (1 << 24)) return LLVQ_EINVAL;
     if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
     if ((size_t)N * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
@@ -1219,6 +1240,7 @@ int llvq_decode_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits,
     if (!ctx) return LLVQ_EINVAL;
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
+    cd.gain_in_word = !d_gain_lut && !d_gain && fmt == LLVQ_IDX_U64 && shape_bits == 48;     // the layout llvq_repack writes
     return decode_impl(ctx, d_idx, fmt, d_gain, cd, n_blocks, d_out, out_dtype, stream);
 }
 
@@ -1227,7 +1249,20 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const 
     if (!ctx) return LLVQ_EINVAL;
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
+    cd.gain_in_word = !d_gain_lut && !d_gain && fmt == LLVQ_IDX_U64 && shape_bits == 48;     // the layout llvq_repack writes
     return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, cd, N, KB, d_y, stream);
+}
+
+int llvq_repack(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks, uint64_t* d_packed, void* stream) {
+    if (!ctx || (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64)) return LLVQ_EINVAL;
+    if (n_blocks == 0) return LLVQ_OK;
+    if (!d_gain || !d_packed) return LLVQ_EINVAL;
+    if (int rc = check_idx(d_idx, fmt)) return rc;
+    if (!aligned(d_gain, 2) || !aligned(d_packed, 8)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    LLVQ_BY_FMT(fmt, launch_repack<F>(d_idx, d_gain, n_blocks, d_packed, st));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "repack launch");
 }
 
 int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, int fmt, void* stream) {

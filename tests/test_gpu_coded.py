@@ -152,3 +152,47 @@ def test_coded_argument_checks(gpu):
     # empty input is a no-op
     e = torch.empty(0, dtype=torch.uint8, device="cuda:0")
     assert gpu.llvq_decode_i8_coded(e, 47).shape == (0, 24)
+
+
+@pytest.mark.parametrize("src_fmt", ["u48", "u64"])
+def test_packed_words_carry_index_and_gain(gpu, oracle13, src_fmt):
+    """llvq_repack writes index | gain bits << 48; the coded calls with 64-bit words, 48 shape bits, no gain table and
+    no gain array read both from the word: bit-exact packing, decode and products against the oracle"""
+    import torch
+    N, K, M = 300, 24 * 57 - 3, 2
+    idx, gain, x = synth.layer(6, 6100, N, K, M)
+    KB = idx.shape[1]
+    flat = idx.reshape(-1)
+    d_idx = _dev(synth.pack_u48(flat).reshape(-1)) if src_fmt == "u48" else _dev(flat.astype(np.int64))
+    d_gain = _dev(gain.reshape(-1))
+    packed = gpu.llvq_repack(d_idx, d_gain)
+    want = flat | (gain.reshape(-1).view(np.uint16).astype(np.uint64) << np.uint64(48))
+    assert np.array_equal(packed.cpu().numpy().view(np.uint64), want)
+    # integer coordinates ignore the gain bits
+    pts = gpu.llvq_decode_i8_coded(packed, 48).cpu().numpy()
+    ref_pts, _ = oracle13.decode(flat)
+    assert np.array_equal(pts, ref_pts)
+    for dt, rel in ((torch.float16, 2.0 ** -11), (torch.float32, 0.0)):
+        w = gpu.llvq_decode_coded(packed, 48, out_dtype=dt).float().cpu().numpy().astype(np.float64)
+        ref = oracle13.dequant(flat, gain.reshape(-1))
+        assert (np.abs(w - ref) <= (rel + 3 * 2.0 ** -24) * np.abs(ref) + 1e-30).all()
+    ref = oracle13.matmul(x, idx, gain)
+    for m_rows in (1, M):                                    # vector-ALU kernel, and the same with two rows
+        y = gpu.llvq_matmul_coded(_dev(x[:m_rows]).half(), packed, N, KB, 48).cpu().numpy()
+        assert _rel(y, ref[:m_rows]) <= TOL
+    x16 = synth.activations(synth.rng_for(6, 6101), 16, K)
+    y = gpu.llvq_matmul_coded(_dev(x16).half(), packed, N, KB, 48).cpu().numpy()      # matrix-core kernel
+    assert _rel(y, oracle13.matmul(x16, idx, gain)) <= TOL
+    x300 = synth.activations(synth.rng_for(6, 6102), 100, K, "bf16")
+    y = gpu.llvq_matmul_coded(_dev(x300).to(torch.bfloat16), packed, N, KB, 48).cpu().numpy()   # strip kernel
+    assert _rel(y, oracle13.matmul(x300, idx, gain)) <= TOL
+
+
+def test_repack_empty_and_invalid(gpu):
+    import torch
+    from paper_2603_11021_amd import LLVQError
+    out = gpu.llvq_repack(torch.empty(0, dtype=torch.uint8, device="cuda:0"), torch.empty(0, dtype=torch.float16, device="cuda:0"))
+    assert out.numel() == 0
+    with pytest.raises(LLVQError):                            # no gain anywhere with 48-bit words: nothing to read it from
+        gpu.llvq_matmul_coded(torch.zeros(1, 24, dtype=torch.float16, device="cuda:0"),
+                              torch.zeros(6, dtype=torch.uint8, device="cuda:0"), 1, 1, 48)
