@@ -308,8 +308,8 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
 
 // ---- llvq_matmul, lane-per-block kernel ---------------------------------------------------------------
 // A workgroup owns `rows_per_wg` consecutive rows, i.e. a contiguous run of rows_per_wg*KB blocks of the
-// row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the 16
-// waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
+// row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the
+// THREADS/64 waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
 // gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
 constexpr int kMaxMChunk = 2;     // activation rows handled per pass over the indices
 constexpr int kRowsPerPass = 64;  // output rows accumulated in LDS at a time
@@ -328,8 +328,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // BIG_GLOBAL: only the small tables are copied into LDS and the Golay words and inner-word planes are read from global
 // memory (short launches, where the table copy is a visible share); otherwise the whole blob is copied (long launches).
-template <int FMT, typename X2, bool BIG_GLOBAL>
-__global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+template <int FMT, typename X2, bool BIG_GLOBAL, int THREADS>
+__global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
                                                           Code cd, uint32_t kb_magic, int rows_per_wg, int rows_per_pass, float* __restrict__ y) {
@@ -345,12 +345,12 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
-    // one workgroup per compute unit: the tables are copied once per launch and workgroup
+    // one or two workgroups per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
     float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     // the accumulators of the first pass are cleared here: the barrier that ends the table copy covers them too
-    for (int i = threadIdx.x; i < kRowsPerPass * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
-    load_tables(blob, table_bytes);
+    for (int i = threadIdx.x; i < kRowsPerPass * kMaxMChunk; i += THREADS) ysum[i] = 0.0f;
+    load_tables<THREADS>(blob, table_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
@@ -365,10 +365,10 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
             if (r0 != wg_r0 || m0 != 0) {
-                for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+                for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += THREADS) ysum[i] = 0.0f;
                 __syncthreads();
             }
-            // a wave takes every 16th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
+            // a wave takes every (THREADS/64)-th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
             // the next batch are requested before this one is decoded, and the next batch's class search and digit
             // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
             struct Fetch { RawBlock raw; uint32_t row, b; uint16_t g; bool live; };
@@ -390,7 +390,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 // gather pipe is as busy as the vector ALUs there, and three 16-byte gathers per block are a tenth of its load
                 return llvq::decode_front<BIG_GLOBAL, !BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
             };
-            const uint32_t stride = kWaves * 64;
+            const uint32_t stride = THREADS;
             uint32_t base = (uint32_t)wave * 64;
             Fetch cur, nxt;
             llvq::Front front_cur, front_nxt;
@@ -482,7 +482,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             }
             if (base < nblk) batch(std::false_type{});
             __syncthreads();
-            for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
+            for (int i = threadIdx.x; i < nrows * mc; i += THREADS) {
                 const int rr = i / mc, mi = i - rr * mc;
                 y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
             }
@@ -937,22 +937,32 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
 
 template <int FMT, typename X2>
 static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    // one persistent workgroup per compute unit (the tables fill its LDS), rows split evenly among them
-    int grid = ctx->num_cu < N ? ctx->num_cu : N;
+    // Three launch shapes, chosen by the batches of 64 blocks a compute unit gets (crossovers measured on Llama-3-8B
+    // and 70B shapes): up to 96 one workgroup of 1024 threads per compute unit with the two big tables left in global
+    // memory; up to 256 two workgroups of 768 threads (the kernel needs 80 registers, so six waves per SIMD fit, and
+    // two 66 KB table copies fit the LDS): more waves hide more of the table-lookup latency, but the table copy and
+    // the first-batch latency are paid twice; beyond that one workgroup with every table in LDS.
+    const size_t nbatch = (size_t)N * (size_t)KB / 64;
+    const bool big_global = nbatch < (size_t)ctx->num_cu * 256;
+    const bool two = big_global && nbatch >= (size_t)ctx->num_cu * 96;
+    const int slots = two ? 2 * ctx->num_cu : ctx->num_cu;
+    int grid = slots < N ? slots : N;
     const int rows = (N + grid - 1) / grid;
     grid = (N + rows - 1) / rows;
     const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
-    // from about 256 batches of 64 blocks per compute unit on, copying all tables into LDS pays (measured on Llama-3-70B shapes)
-    const bool big_global = (size_t)N * (size_t)KB < (size_t)ctx->num_cu * 64 * 256;
     const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
-    if (big_global) {
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true>, lds)) return rc;
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+    if (two) {
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true, 768>, lds)) return rc;
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true, 768>), dim3(grid), dim3(768), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
+    } else if (big_global) {
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true, kThreads>, lds)) return rc;
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true, kThreads>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
                            reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
     } else {
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, false>, lds)) return rc;
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, false, kThreads>, lds)) return rc;
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, false, kThreads>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
                            reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
     }
     hipError_t e = hipGetLastError();
