@@ -935,16 +935,41 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "dequant launch");
 }
 
+// Batches of 64 blocks that the busiest SIMD of a matmul_kernel workgroup works off: the workgroup takes `rows` rows
+// in passes of `rows_pass`, a pass deals its batches round-robin to `waves` waves, and wave w runs on SIMD w % 4.
+static uint64_t simd_batches(int rows, int rows_pass, int KB, int waves) {
+    auto pass = [&](int r) {
+        const uint64_t nb = ((uint64_t)r * (uint64_t)KB + 63) / 64;
+        uint64_t worst = 0;
+        for (int s = 0; s < 4; s++) {
+            uint64_t sum = 0;
+            for (int w = s; w < waves; w += 4) sum += nb > (uint64_t)w ? (nb - w + waves - 1) / waves : 0;
+            worst = std::max(worst, sum);
+        }
+        return worst;
+    };
+    const int full = rows / rows_pass, rest = rows % rows_pass;
+    return (uint64_t)full * pass(rows_pass) + (rest ? pass(rest) : 0);
+}
+
 template <int FMT, typename X2>
 static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    // Three launch shapes, chosen by the batches of 64 blocks a compute unit gets (crossovers measured on Llama-3-8B
-    // and 70B shapes): up to 96 one workgroup of 1024 threads per compute unit with the two big tables left in global
-    // memory; up to 256 two workgroups of 768 threads (the kernel needs 80 registers, so six waves per SIMD fit, and
-    // two 66 KB table copies fit the LDS): more waves hide more of the table-lookup latency, but the table copy and
-    // the first-batch latency are paid twice; beyond that one workgroup with every table in LDS.
+    // Three launch shapes.  From 256 batches of 64 blocks per compute unit on: one workgroup of 1024 threads with every
+    // table in LDS.  Below that the two big tables stay in global memory and the kernel needs 80 registers, so either one
+    // workgroup of 1024 threads per compute unit (four waves per SIMD) or two of 768 (six: more waves hide more of the
+    // table-lookup latency, but the table copy and the first-batch latency are paid twice, and the batches may deal
+    // less evenly).  The two are compared by a cost model fitted to launches of 4096..14336 x 4104: start-up plus the
+    // batches of the busiest SIMD times the time a SIMD takes per batch at that occupancy, in microseconds.
     const size_t nbatch = (size_t)N * (size_t)KB / 64;
     const bool big_global = nbatch < (size_t)ctx->num_cu * 256;
-    const bool two = big_global && nbatch >= (size_t)ctx->num_cu * 96;
+    bool two = false;
+    if (big_global && N >= 2 * ctx->num_cu) {
+        const int rows1 = (N + ctx->num_cu - 1) / ctx->num_cu, rows2 = (N + 2 * ctx->num_cu - 1) / (2 * ctx->num_cu);
+        const int rp = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));
+        const double t1 = 4.32 + 0.825 * (double)simd_batches(rows1, rp, KB, kThreads / 64);
+        const double t2 = 4.60 + 0.777 * 2.0 * (double)simd_batches(rows2, rp, KB, 768 / 64);
+        two = t2 < t1;
+    }
     const int slots = two ? 2 * ctx->num_cu : ctx->num_cu;
     int grid = slots < N ? slots : N;
     const int rows = (N + grid - 1) / grid;
