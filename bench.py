@@ -251,6 +251,25 @@ def extra_layer_set(q, synth, torch, dev):
             print("%s bulk decode of the block to bf16 (%d blocks): %.3f ms, %.2f G blocks/s, read+write %.1f GB/s" %
                   (label, tot, ms, tot / ms / 1e6, tot * 56 / ms / 1e6), file=sys.stderr)
             del outs
+            # decode-only throughput on more than 2^26 blocks in one call: the block's indices twice (union of shells), and
+            # as many indices uniform over the first shell (the distribution of the decode-unit configuration)
+            big = torch.cat([l[2] for l in layers] * 2)
+            nbig = big.numel() // 6
+            out8 = torch.empty((nbig, 24), dtype=torch.int8, device=dev)
+            first = synth.pack_u48(synth.rng_for(1, 7).integers(0, 196560, size=1 << 22, dtype=np.uint64)).reshape(-1)
+            first = torch.from_numpy(first).to(dev).repeat(nbig // (1 << 22) + 1)[:nbig * 6].contiguous()
+            for what, src in (("union of shells 2..13", big), ("first shell", first)):
+                q.llvq_decode_i8(src, out=out8)
+                torch.cuda.synchronize()
+                e0.record()
+                for _ in range(reps):
+                    q.llvq_decode_i8(src, out=out8)
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                print("decode to int8, %d blocks (%s) in one call: %.3f ms, %.2f G blocks/s, read+write %.1f GB/s" %
+                      (nbig, what, ms, nbig / ms / 1e6, nbig * 30 / ms / 1e6), file=sys.stderr)
+            del big, first, out8
         del layers
 
 
