@@ -29,7 +29,6 @@ using llvq::TableLayout;
 using llvq::TabPtrs;
 
 constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
@@ -308,8 +307,7 @@ __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(c
 
 // ---- llvq_matmul, lane-per-block kernel ---------------------------------------------------------------
 // A workgroup owns `rows_per_wg` consecutive rows, i.e. a contiguous run of rows_per_wg*KB blocks of the
-// row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt round-robin to the
-// THREADS/64 waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
+// row-major index and gain arrays; wave-batches of 64 consecutive blocks are dealt to the 16 waves.  Per block and activation row the 24 products are accumulated by v_dot2_f32_f16 in fp32, scaled by
 // gain/sqrt(16 m), reduced over the lanes that share an output row and added to that row's LDS accumulator.
 constexpr int kMaxMChunk = 2;     // activation rows handled per pass over the indices
 constexpr int kRowsPerPass = 64;  // output rows accumulated in LDS at a time
@@ -328,8 +326,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // BIG_GLOBAL: only the small tables are copied into LDS and the Golay words and inner-word planes are read from global
 // memory (short launches, where the table copy is a visible share); otherwise the whole blob is copied (long launches).
-template <int FMT, typename X2, bool BIG_GLOBAL, int THREADS>
-__global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+// DYNAMIC: after its first two batches a wave takes the next free batch instead of every 16th one (long launches: the
+// SIMDs do not get through their batches at the same rate; short ones are faster with the fixed deal).
+template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC>
+__global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
                                                           Code cd, uint32_t kb_magic, int rows_per_wg, int rows_per_pass, float* __restrict__ y) {
@@ -345,12 +345,16 @@ __global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_ke
         const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
         load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
-    // one or two workgroups per compute unit: the tables are copied once per launch and workgroup
+    // one workgroup per compute unit: the tables are copied once per launch and workgroup
     const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
     float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
+    // the first block number no wave has taken yet: the first two batches of a wave are fixed, after them it takes the
+    // next free one, so waves on a SIMD that gets through its batches sooner end up with more of them
+    uint32_t* next_free = reinterpret_cast<uint32_t*>(ysum + kRowsPerPass * kMaxMChunk);
     // the accumulators of the first pass are cleared here: the barrier that ends the table copy covers them too
-    for (int i = threadIdx.x; i < kRowsPerPass * kMaxMChunk; i += THREADS) ysum[i] = 0.0f;
-    load_tables<THREADS>(blob, table_bytes);
+    for (int i = threadIdx.x; i < kRowsPerPass * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+    if (DYNAMIC && threadIdx.x == 0) *next_free = 2 * kThreads;
+    load_tables(blob, table_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
@@ -365,10 +369,12 @@ __global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_ke
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
             if (r0 != wg_r0 || m0 != 0) {
-                for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += THREADS) ysum[i] = 0.0f;
+                for (int i = threadIdx.x; i < nrows * kMaxMChunk; i += kThreads) ysum[i] = 0.0f;
+                if (DYNAMIC && threadIdx.x == 0) *next_free = 2 * kThreads;
                 __syncthreads();
             }
-            // a wave takes every (THREADS/64)-th batch of 64 blocks.  Software pipeline over the batches: the indices and gains of
+            // a wave starts with batches `wave` and `wave + 16` and then takes every 16th batch of 64 blocks or (DYNAMIC)
+            // free batches one at a time, one batch ahead of the one it decodes.  Software pipeline over the batches: the indices and gains of
             // the next batch are requested before this one is decoded, and the next batch's class search and digit
             // extraction (a chain of dependent table reads) run before this batch's products, which hide their latency
             struct Fetch { RawBlock raw; uint32_t row, b; uint16_t g; bool live; };
@@ -390,8 +396,7 @@ __global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_ke
                 // gather pipe is as busy as the vector ALUs there, and three 16-byte gathers per block are a tenth of its load
                 return llvq::decode_front<BIG_GLOBAL, !BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
             };
-            const uint32_t stride = THREADS;
-            uint32_t base = (uint32_t)wave * 64;
+            uint32_t base = (uint32_t)wave * 64, next = base + kThreads, taken = 0;
             Fetch cur, nxt;
             llvq::Front front_cur, front_nxt;
             bool ok_cur = false, ok_nxt = false;
@@ -409,7 +414,10 @@ __global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_ke
             // wait count as if it had not been issued, i.e. wait for newer loads than it needs
             auto batch = [&](auto more_tag) {
                 constexpr bool kMore = decltype(more_tag)::value;
-                if constexpr (kMore) fetch(base + stride, nxt);
+                if constexpr (kMore) {
+                    fetch(next, nxt);
+                    if (DYNAMIC && lane == 0) taken = atomicAdd(next_free, 64u);      // the batch after that one
+                }
                 u32x4 xq[1][3];
                 {
                     const u32x4* xp = reinterpret_cast<const u32x4*>(reinterpret_cast<const unsigned char*>(x + (size_t)m0 * xpitch) + llvq::mul24(cur.b, 48u));
@@ -474,15 +482,17 @@ __global__ void __launch_bounds__(THREADS, THREADS < kThreads ? 6 : 4) matmul_ke
                     }
                 }
             };
-            for (; base + stride < nblk; base += stride) {
+            while (next < nblk) {
                 batch(std::true_type{});
                 cur = nxt;
                 front_cur = front_nxt;
                 ok_cur = ok_nxt;
+                base = next;
+                next = DYNAMIC ? __builtin_amdgcn_readfirstlane(taken) : next + kThreads;
             }
             if (base < nblk) batch(std::false_type{});
             __syncthreads();
-            for (int i = threadIdx.x; i < nrows * mc; i += THREADS) {
+            for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
                 const int rr = i / mc, mi = i - rr * mc;
                 y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
             }
@@ -935,61 +945,31 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "dequant launch");
 }
 
-// Batches of 64 blocks that the busiest SIMD of a matmul_kernel workgroup works off: the workgroup takes `rows` rows
-// in passes of `rows_pass`, a pass deals its batches round-robin to `waves` waves, and wave w runs on SIMD w % 4.
-static uint64_t simd_batches(int rows, int rows_pass, int KB, int waves) {
-    auto pass = [&](int r) {
-        const uint64_t nb = ((uint64_t)r * (uint64_t)KB + 63) / 64;
-        uint64_t worst = 0;
-        for (int s = 0; s < 4; s++) {
-            uint64_t sum = 0;
-            for (int w = s; w < waves; w += 4) sum += nb > (uint64_t)w ? (nb - w + waves - 1) / waves : 0;
-            worst = std::max(worst, sum);
-        }
-        return worst;
-    };
-    const int full = rows / rows_pass, rest = rows % rows_pass;
-    return (uint64_t)full * pass(rows_pass) + (rest ? pass(rest) : 0);
-}
-
 template <int FMT, typename X2>
 static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    // Three launch shapes.  From 256 batches of 64 blocks per compute unit on: one workgroup of 1024 threads with every
-    // table in LDS.  Below that the two big tables stay in global memory and the kernel needs 80 registers, so either one
-    // workgroup of 1024 threads per compute unit (four waves per SIMD) or two of 768 (six: more waves hide more of the
-    // table-lookup latency, but the table copy and the first-batch latency are paid twice, and the batches may deal
-    // less evenly).  The two are compared by a cost model fitted to launches of 4096..14336 x 4104: start-up plus the
-    // batches of the busiest SIMD times the time a SIMD takes per batch at that occupancy, in microseconds.
-    const size_t nbatch = (size_t)N * (size_t)KB / 64;
-    const bool big_global = nbatch < (size_t)ctx->num_cu * 256;
-    bool two = false;
-    if (big_global && N >= 2 * ctx->num_cu) {
-        const int rows1 = (N + ctx->num_cu - 1) / ctx->num_cu, rows2 = (N + 2 * ctx->num_cu - 1) / (2 * ctx->num_cu);
-        const int rp = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));
-        const double t1 = 4.32 + 0.825 * (double)simd_batches(rows1, rp, KB, kThreads / 64);
-        const double t2 = 4.60 + 0.777 * 2.0 * (double)simd_batches(rows2, rp, KB, 768 / 64);
-        two = t2 < t1;
-    }
-    const int slots = two ? 2 * ctx->num_cu : ctx->num_cu;
-    int grid = slots < N ? slots : N;
+    // one persistent workgroup per compute unit (the tables fill its LDS), rows split evenly among them
+    int grid = ctx->num_cu < N ? ctx->num_cu : N;
     const int rows = (N + grid - 1) / grid;
     grid = (N + rows - 1) / rows;
     const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
-    const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);
+    // by the batches of 64 blocks a compute unit gets (crossovers measured on Llama-3-8B and 70B shapes): from 256 on,
+    // copying all tables into LDS pays; from 56 on (3.5 per wave), dealing the batches to the waves as they finish does
+    const size_t nbatch = (size_t)N * (size_t)KB / 64;
+    const bool big_global = nbatch < (size_t)ctx->num_cu * 256;
+    const bool dynamic = nbatch >= (size_t)ctx->num_cu * 56;
+    const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;   // row sums + batch counter
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
-    if (two) {
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true, 768>, lds)) return rc;
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true, 768>), dim3(grid), dim3(768), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
-    } else if (big_global) {
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, true, kThreads>, lds)) return rc;
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, true, kThreads>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
-    } else {
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, false, kThreads>, lds)) return rc;
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, false, kThreads>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                           reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kb_magic, rows, rows_pass, d_y);
-    }
+#define LLVQ_LAUNCH_MATMUL(BG, DYN)                                                                                         \
+    do {                                                                                                                    \
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, BG, DYN>, lds)) return rc;                                         \
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, BG, DYN>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay,   \
+                           d_idx, reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N,  \
+                           KB, cd, kb_magic, rows, rows_pass, d_y);                                                         \
+    } while (0)
+    if (!big_global) LLVQ_LAUNCH_MATMUL(false, true);
+    else if (dynamic) LLVQ_LAUNCH_MATMUL(true, true);
+    else LLVQ_LAUNCH_MATMUL(true, false);
+#undef LLVQ_LAUNCH_MATMUL
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }
