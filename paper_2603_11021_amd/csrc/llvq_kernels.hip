@@ -178,6 +178,47 @@ __device__ __forceinline__ void finish_block(const RawBlock& r, const Code& cd, 
     I = (v & cd.mask) + cd.base;
 }
 
+// How the bulk-decode kernels hand blocks to their lanes.  Both forms keep the position of a wave's blocks wave-uniform
+// (`base`, a scalar) with the lane's block at base + t, and both walk the array grid-stride, so that the blocks in
+// flight on the chip at any time are neighbours in memory.
+//   fixed   (short launches): the workgroup takes every gridDim.x-th run of kThreads blocks; t = thread number
+//   dynamic (long launches):  the workgroup takes every gridDim.x-th batch of 64 blocks; a wave decodes the workgroup's
+//                             batches `wave` and `wave + 16` and then takes its next free one through a counter in LDS
+//                             (the 4 bytes behind the tables), one batch ahead of the one it decodes; t = lane.  The SIMDs
+//                             of a compute unit do not get through their batches at the same rate, and this evens it out.
+template <bool DYNAMIC>
+struct BatchDeal {
+    size_t base, next, end;
+    uint32_t t, taken;
+    uint32_t* next_free;
+    __device__ __forceinline__ size_t batch_start(uint32_t b) const { return ((size_t)b * gridDim.x + blockIdx.x) * 64; }
+    __device__ __forceinline__ BatchDeal(size_t n, uint32_t table_bytes) {
+        taken = 0;
+        end = n;
+        next_free = reinterpret_cast<uint32_t*>(g_lds + table_bytes);
+        if constexpr (DYNAMIC) {
+            const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+            t = threadIdx.x & 63;
+            base = batch_start(wave);
+            next = batch_start(wave + kThreads / 64);
+            if (threadIdx.x == 0) *next_free = 2 * kThreads / 64;                  // covered by the barrier of load_tables
+        } else {
+            t = threadIdx.x;
+            base = (size_t)blockIdx.x * kThreads;
+            next = base + (size_t)gridDim.x * kThreads;
+        }
+    }
+    // ask for the batch after `next` (its number arrives while this batch is decoded)
+    __device__ __forceinline__ void take() {
+        if constexpr (DYNAMIC) { if (t == 0) taken = atomicAdd(next_free, 1u); }
+    }
+    __device__ __forceinline__ void advance() {
+        base = next;
+        if constexpr (DYNAMIC) next = batch_start(__builtin_amdgcn_readfirstlane(taken));
+        else next += (size_t)gridDim.x * kThreads;
+    }
+};
+
 // ---- llvq_decode_i8 ---------------------------------------------------------------------------------
 // BIG_GLOBAL as in matmul_kernel below: with the two big tables in global memory the LDS part is 66 KB and two
 // workgroups share a compute unit (eight waves per SIMD, 64 registers per lane), which wins on launches that are not
@@ -186,23 +227,23 @@ template <int FMT, bool BIG_GLOBAL>
 __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                              const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
+    BatchDeal<!BIG_GLOBAL> deal(n, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    // A pass of the workgroup covers kThreads consecutive blocks from a wave-uniform position, so the streamed arrays
-    // are addressed as scalar base + 32-bit lane offset.  The next word is requested (always: past the end the last
-    // one is read again) before this block is decoded.
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    const uint32_t t = threadIdx.x;
+    // The streamed arrays are addressed as scalar base + 32-bit lane offset (BatchDeal).  The next word is requested
+    // (always: past the end the last one is read again) before this block is decoded.
+    const uint32_t t = deal.t;
     auto request = [&](size_t base, RawBlock& r) {
         const size_t b0 = base < n ? base : n - 1;
         const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + b0 * kWordBytes<FMT>;
         load_raw_near<FMT>(idx0, idx0, (uint32_t)min((size_t)t, n - 1 - b0), r);
     };
-    size_t base = (size_t)blockIdx.x * kThreads;
     RawBlock raw, raw_next;
-    if (base < n) request(base, raw);
-    for (; base < n; base += stride, raw = raw_next) {
-        request(base + stride, raw_next);
+    if (deal.base < deal.end) request(deal.base, raw);
+    for (; deal.base < deal.end; deal.advance(), raw = raw_next) {
+        request(deal.next, raw_next);
+        deal.take();
+        const size_t base = deal.base;
         uint64_t I;
         uint16_t gdummy;
         finish_block<FMT>(raw, cd, I, gdummy);
@@ -240,22 +281,23 @@ template <int FMT, int OUT, bool BIG_GLOBAL>
 __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) dequant_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                            const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                            Code cd, size_t n, void* __restrict__ out) {
+    BatchDeal<!BIG_GLOBAL> deal(n, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    // passes and addressing as in decode_i8_kernel; the next word and gain are requested before this block is decoded
-    const size_t stride = (size_t)gridDim.x * kThreads;
-    const uint32_t t = threadIdx.x;
+    // batches and addressing as in decode_i8_kernel; the next word and gain are requested before this block is decoded
+    const uint32_t t = deal.t;
     auto request = [&](size_t base, RawBlock& r) {
         const size_t b0 = base < n ? base : n - 1;
         const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + b0 * kWordBytes<FMT>;
         const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + b0) : idx0;
         load_raw_near<FMT>(idx0, gain0, (uint32_t)min((size_t)t, n - 1 - b0), r);
     };
-    size_t base = (size_t)blockIdx.x * kThreads;
     RawBlock raw, raw_next;
-    if (base < n) request(base, raw);
-    for (; base < n; base += stride, raw = raw_next) {
-        request(base + stride, raw_next);
+    if (deal.base < deal.end) request(deal.base, raw);
+    for (; deal.base < deal.end; deal.advance(), raw = raw_next) {
+        request(deal.next, raw_next);
+        deal.take();
+        const size_t base = deal.base;
         const bool live = base + t < n;
         uint64_t I;
         uint16_t gb;
@@ -912,7 +954,7 @@ static bool small_launch(const llvq_ctx* ctx, size_t n, size_t batches_per_cu) {
 template <int FMT>
 static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
     const bool small = small_launch(ctx, n, 768);
-    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
+    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes + 16;       // long launches: + the batch counter
     const int grid = grid_for(ctx, n, small ? 2 : 1);
     if (small) {
         if (int rc = set_lds(ctx, decode_i8_kernel<FMT, true>, lds)) return rc;
@@ -929,7 +971,7 @@ template <int FMT>
 static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, const Code& cd, size_t n, void* d_out, int out_dtype, hipStream_t st) {
     // fp32 output is bound by its stores: it always takes the one-workgroup variant
     const bool small = small_launch(ctx, n, 64) && out_dtype != LLVQ_F32;
-    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes;
+    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes + 16;       // long launches: + the batch counter
     const int grid = grid_for(ctx, n, small ? 2 : 1);
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
 #define LLVQ_LAUNCH_DQ(OUT, BG)                                                                                    \
@@ -1170,7 +1212,7 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     hipDeviceProp_t prop;
     if ((e = hipGetDeviceProperties(&prop, device)) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     ctx->num_cu = prop.multiProcessorCount;
-    constexpr size_t kScratch = (size_t)kRowsPerPass * kMaxMChunk * sizeof(float);    // the largest kernel scratch beside the tables
+    constexpr size_t kScratch = (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;    // the largest kernel scratch beside the tables (row sums + batch counter)
     if (tabs.lay.blob_bytes + kScratch > prop.sharedMemPerBlock && tabs.lay.blob_bytes + kScratch > (size_t)prop.sharedMemPerBlockOptin) { delete ctx; return LLVQ_ENOTIMPL; }
     if ((e = hipMalloc(&ctx->d_blob, tabs.blob.size())) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     if ((e = hipMalloc(&ctx->d_counter, sizeof(unsigned long long))) != hipSuccess) { (void)hipFree(ctx->d_blob); delete ctx; return LLVQ_EHIP; }
