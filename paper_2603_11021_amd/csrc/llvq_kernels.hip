@@ -223,11 +223,11 @@ struct BatchDeal {
 // BIG_GLOBAL as in matmul_kernel below: with the two big tables in global memory the LDS part is 66 KB and two
 // workgroups share a compute unit (eight waves per SIMD, 64 registers per lane), which wins on launches that are not
 // dominated by their HBM traffic
-template <int FMT, bool BIG_GLOBAL>
+template <int FMT, bool BIG_GLOBAL, bool DYNAMIC>
 __global__ void __launch_bounds__(kThreads, BIG_GLOBAL ? 8 : 4) decode_i8_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                              const void* __restrict__ idx, Code cd, size_t n,
                                                              uint32_t* __restrict__ out) {
-    BatchDeal<!BIG_GLOBAL> deal(n, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
+    BatchDeal<DYNAMIC> deal(n, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     load_tables(blob, BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     // The streamed arrays are addressed as scalar base + 32-bit lane offset (BatchDeal).  The next word is requested
@@ -837,21 +837,26 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
 
 // ---- llvq_encode --------------------------------------------------------------------------------------
 // One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
-template <int FMT>
+template <int FMT, bool DYNAMIC>
 __global__ void __launch_bounds__(kThreads, 8) encode_kernel(const unsigned char* __restrict__ blob, llvq::EncLayout lay,
                                                           const uint2* __restrict__ pts, size_t n, void* __restrict__ idx,
                                                           size_t out_stride) {
+    BatchDeal<DYNAMIC> deal(n, lay.bytes);
     load_tables(blob, lay.bytes);
     const llvq::EncPtrs T = llvq::make_enc_ptrs(lds_origin(), lay);
-    for (size_t k = (size_t)blockIdx.x * kThreads + threadIdx.x; k < n; k += (size_t)gridDim.x * kThreads) {
-        const uint2 p0 = pts[3 * k], p1 = pts[3 * k + 1], p2 = pts[3 * k + 2];
-        const uint32_t x[6] = {p0.x, p0.y, p1.x, p1.y, p2.x, p2.y};
-        const uint64_t I = llvq::encode_block(T, x);
-        if constexpr (FMT == LLVQ_IDX_U64) {
-            reinterpret_cast<uint64_t*>(idx)[k * out_stride] = I;
-        } else {
-            uint16_t* o = reinterpret_cast<uint16_t*>(idx) + 3 * k * out_stride;
-            o[0] = (uint16_t)I; o[1] = (uint16_t)(I >> 16); o[2] = (uint16_t)(I >> 32);
+    for (; deal.base < deal.end; deal.advance()) {
+        deal.take();
+        const size_t k = deal.base + deal.t;
+        if (k < n) {
+            const uint2 p0 = pts[3 * k], p1 = pts[3 * k + 1], p2 = pts[3 * k + 2];
+            const uint32_t x[6] = {p0.x, p0.y, p1.x, p1.y, p2.x, p2.y};
+            const uint64_t I = llvq::encode_block(T, x);
+            if constexpr (FMT == LLVQ_IDX_U64) {
+                reinterpret_cast<uint64_t*>(idx)[k * out_stride] = I;
+            } else {
+                uint16_t* o = reinterpret_cast<uint16_t*>(idx) + 3 * k * out_stride;
+                o[0] = (uint16_t)I; o[1] = (uint16_t)(I >> 16); o[2] = (uint16_t)(I >> 32);
+            }
         }
     }
 }
@@ -954,15 +959,20 @@ static bool small_launch(const llvq_ctx* ctx, size_t n, size_t batches_per_cu) {
 template <int FMT>
 static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, size_t n, int8_t* d_out, hipStream_t st) {
     const bool small = small_launch(ctx, n, 768);
-    const size_t lds = small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes + 16;       // long launches: + the batch counter
+    // from about 3.5 batches per wave on, dealing the batches to the waves as they finish pays
+    const bool dynamic = !small_launch(ctx, n, small ? 112 : 56);
+    const size_t lds = (small ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + 16;       // + the batch counter
     const int grid = grid_for(ctx, n, small ? 2 : 1);
-    if (small) {
-        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, true>, lds)) return rc;
-        hipLaunchKernelGGL((decode_i8_kernel<FMT, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
-    } else {
-        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, false>, lds)) return rc;
-        hipLaunchKernelGGL((decode_i8_kernel<FMT, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));
-    }
+#define LLVQ_LAUNCH_I8(BG, DYN)                                                                                              \
+    do {                                                                                                                     \
+        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, BG, DYN>, lds)) return rc;                                           \
+        hipLaunchKernelGGL((decode_i8_kernel<FMT, BG, DYN>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay,     \
+                           d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));                                                \
+    } while (0)
+    if (!small) LLVQ_LAUNCH_I8(false, true);
+    else if (dynamic) LLVQ_LAUNCH_I8(true, true);
+    else LLVQ_LAUNCH_I8(true, false);
+#undef LLVQ_LAUNCH_I8
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "decode_i8 launch");
 }
@@ -1036,13 +1046,20 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
 
 template <int FMT>
 static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st, size_t out_stride = 1) {
-    const size_t lds = ctx->enc_lay.bytes;
+    const size_t lds = ctx->enc_lay.bytes + 16;        // + the batch counter
     // the encoder's tables take 68.5 KB: two workgroups share a compute unit (64 vector registers per lane)
     const size_t wgs = (n + kThreads - 1) / kThreads;
     const int grid = (int)std::max<size_t>(1, std::min<size_t>(wgs, (size_t)2 * ctx->num_cu));
-    if (int rc = set_lds(ctx, encode_kernel<FMT>, lds)) return rc;
-    hipLaunchKernelGGL(encode_kernel<FMT>, dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
-                       reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
+    // from about 3.5 batches of 64 vectors per wave on, the waves take their batches as they finish
+    if (n >= (size_t)ctx->num_cu * 64 * 112) {
+        if (int rc = set_lds(ctx, encode_kernel<FMT, true>, lds)) return rc;
+        hipLaunchKernelGGL((encode_kernel<FMT, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
+                           reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
+    } else {
+        if (int rc = set_lds(ctx, encode_kernel<FMT, false>, lds)) return rc;
+        hipLaunchKernelGGL((encode_kernel<FMT, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
+                           reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "encode launch");
 }
