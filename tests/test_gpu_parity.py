@@ -119,6 +119,25 @@ def test_shape_gain_decode(gpu, oracle13, dtype):
     assert np.allclose(nrm, gain.astype(np.float64), rtol=4 * rel + 1e-6)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_shape_gain_decode_long_launch_ragged(gpu, oracle13, dtype):
+    """a size at which every output type takes the long-launch kernel (all tables in LDS, batches of 64 blocks dealt
+    to the waves as they finish), with a last batch of 7 blocks: every block against the oracle"""
+    import torch
+    n = 1200007
+    rng = synth.rng_for(5, 2)
+    idx = synth.indices(rng, n)
+    gain = synth.gains(rng, n)
+    want = oracle13.dequant(idx, gain)
+    tdt = {"f16": torch.float16, "f32": torch.float32}[dtype]
+    out = torch.full((n + 1, 24), 7.0, dtype=tdt, device="cuda:0")               # one guard block behind the output
+    gpu.llvq_decode(_dev(synth.pack_u48(idx).reshape(-1)), _dev(gain), out_dtype=tdt, out=out[:n])
+    assert bool((out[n] == 7.0).all())
+    got = out[:n].float().cpu().numpy().astype(np.float64)
+    rel = {"f16": 2.0 ** -11, "f32": 0.0}[dtype] + 3 * 2.0 ** -24
+    assert (np.abs(got - want) <= rel * np.abs(want) + 1e-30).all()
+
+
 def _matmul_case(gpu, oracle, config, ordinal, N, K, M, x_dtype=np.float16, sample_rows=None):
     import torch
     idx, gain, x = synth.layer(config, ordinal, N, K, M, x_dtype=x_dtype)
@@ -349,6 +368,14 @@ def test_matmul_many_rows_per_workgroup(gpu, oracle13, N, K, M):
     """more than 64 rows per workgroup (several passes over the LDS accumulators) and many rows per wave batch
     (the segmented row reduction), and the opposite: a few very long rows"""
     _matmul_case(gpu, oracle13, 6, 3000 + N % 97 + M, N, K, M)
+
+
+@pytest.mark.parametrize("N,K,M", [(25600, 960, 2), (70000, 1536, 1)])
+def test_matmul_long_launch_several_passes(gpu, oracle13, N, K, M):
+    """launches long enough that the waves take their batches from the workgroup's counter (the second one with all
+    tables in LDS), with 100 and 274 rows per workgroup, i.e. several passes that each restart the counter; sampled
+    rows against the oracle"""
+    _matmul_case(gpu, oracle13, 6, 4000 + M, N, K, M, sample_rows=3000)
 
 
 def test_matmul_random_small_shapes(gpu, oracle13):
