@@ -660,14 +660,21 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
             }
         };
 
-        for (uint32_t st = s0; st < s1; st++) {
-            const int row = (int)rt * 32 + col;
+        // the word and gain of the next step are requested before this step's block is decoded
+        const int row = (int)rt * 32 + col;
+        auto request = [&](uint32_t st, RawBlock& r) {
+            const size_t k = (size_t)min(row, N - 1) * KB + min(2 * st + half, (uint32_t)KB - 1);
+            load_raw<FMT>(idx, gain, cd.gain_array(), k, r);
+        };
+        RawBlock raw, raw_next;
+        request(s0, raw);
+        for (uint32_t st = s0; st < s1; st++, raw = raw_next) {
+            request(min(st + 1, s1 - 1), raw_next);
             const uint32_t b = 2 * st + half;
             const bool live = row < N && b < (uint32_t)KB;
-            const size_t k = (size_t)min(row, N - 1) * KB + min(b, (uint32_t)KB - 1);
             uint64_t I;
             uint16_t gb;
-            load_block<FMT>(idx, gain, cd, k, I, gb);
+            finish_block<FMT>(raw, cd, I, gb);
             const float g = __half2float(__ushort_as_half(gb));
             const bool ok = live && I < T.npoints;
             if (!ok) I = 0;
