@@ -1011,12 +1011,10 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     const int rows = (N + grid - 1) / grid;
     grid = (N + rows - 1) / rows;
     const uint32_t kb_magic = (KB > 1 && KB < 8192) ? (uint32_t)(((1ull << 32) + (uint64_t)KB - 1) / (uint64_t)KB) : 0u;
-    // by the batches of 64 blocks a compute unit gets (crossovers measured on Llama-3-8B and 70B shapes): from 256 on,
-    // copying all tables into LDS pays; from 56 on (3.5 per wave), dealing the batches to the waves as they finish does
-    const size_t nbatch = (size_t)N * (size_t)KB / 64;
-    const bool big_global = nbatch < (size_t)ctx->num_cu * 256;
-    const bool dynamic = nbatch >= (size_t)ctx->num_cu * 56;
-    const size_t lds = (big_global ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;   // row sums + batch counter
+    // from 64 batches of 64 blocks per compute unit on (four per wave; measured on Llama-3-8B and 70B shapes), copying
+    // all tables into LDS pays, and so does dealing the batches to the waves as they finish
+    const bool short_launch = (size_t)N * (size_t)KB / 64 < (size_t)ctx->num_cu * 64;
+    const size_t lds = (short_launch ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;   // row sums + batch counter
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
 #define LLVQ_LAUNCH_MATMUL(BG, DYN)                                                                                         \
     do {                                                                                                                    \
@@ -1025,9 +1023,8 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
                            d_idx, reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N,  \
                            KB, cd, kb_magic, rows, rows_pass, d_y);                                                         \
     } while (0)
-    if (!big_global) LLVQ_LAUNCH_MATMUL(false, true);
-    else if (dynamic) LLVQ_LAUNCH_MATMUL(true, true);
-    else LLVQ_LAUNCH_MATMUL(true, false);
+    if (short_launch) LLVQ_LAUNCH_MATMUL(true, false);
+    else LLVQ_LAUNCH_MATMUL(false, true);
 #undef LLVQ_LAUNCH_MATMUL
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
