@@ -212,6 +212,27 @@ def extra_layer_set(q, synth, torch, dev):
         ms = e0.elapsed_time(e1) / reps
         print("%s layer set x%d (%.1f MB packed): %.3f ms per pass, %.1f GB/s packed, %.2f G blocks/s" %
               (label, copies, tot * 8 / 1e6, ms, tot * 8 / ms / 1e6, tot / ms / 1e6), file=sys.stderr)
+        if copies > 1:
+            # the same layer set at batch 16 (the batched-decode kernel on the matrix cores)
+            x16 = {}
+            for (name, x, idx, gain, N, KB, y) in layers:
+                if KB not in x16:
+                    r = synth.rng_for(3, 900 + KB)
+                    x16[KB] = torch.from_numpy(synth.activations(r, 16, x.shape[1]).astype(np.float16)).to(dev)
+            y16 = [torch.empty((16, l[4]), dtype=torch.float32, device=dev) for l in layers]
+            for (l, yy) in zip(layers, y16):
+                q.llvq_matmul(x16[l[5]], l[2], l[3], l[4], l[5], out=yy)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                for (l, yy) in zip(layers, y16):
+                    q.llvq_matmul(x16[l[5]], l[2], l[3], l[4], l[5], out=yy)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            print("%s layer set x%d at batch 16: %.3f ms per pass, %.1f GB/s packed, %.2f G blocks/s" %
+                  (label, copies, ms, tot * 8 / ms / 1e6, tot / ms / 1e6), file=sys.stderr)
+            del x16, y16
         # the same weights with the layers that share their input stored as one matrix (q, k, v rows concatenated;
         # gate, up likewise): four launches per block instead of seven, same bytes
         fused = []
