@@ -671,6 +671,19 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
         for (uint32_t st = s0; st < s1; st++, raw = raw_next) {
             request(min(st + 1, s1 - 1), raw_next);
             const uint32_t b = 2 * st + half;
+            // this step's activation operands are requested before the block is decoded (each lane reads 48 bytes of a
+            // different token row: the slowest loads of the step)
+            const uint32_t bx = min(b, (uint32_t)KB - 1) * 12;
+            u32x4 xa[kTokTiles <= 2 ? kTokTiles : 1][3];
+            if constexpr (kTokTiles <= 2) {
+#pragma unroll
+                for (int t = 0; t < kTokTiles; t++) {
+                    if (t < ntile) {
+                        const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
+                        xa[t][0] = xp[0]; xa[t][1] = xp[1]; xa[t][2] = xp[2];
+                    }
+                }
+            }
             const bool live = row < N && b < (uint32_t)KB;
             uint64_t I;
             uint16_t gb;
@@ -690,15 +703,20 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
                 wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
                 wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
             }
-            const uint32_t bx = min(b, (uint32_t)KB - 1) * 12;
 #pragma unroll
             for (int t = 0; t < kTokTiles; t++) {
                 if (t < ntile) {
-                    const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
-                    const u32x4 xa[3] = {xp[0], xp[1], xp[2]};
+                    if constexpr (kTokTiles <= 2) {
 #pragma unroll
-                    for (int j = 0; j < 3; j++)
-                        acc[t] = Mma<X2>::mma(xa[j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
+                        for (int j = 0; j < 3; j++)
+                            acc[t] = Mma<X2>::mma(xa[t][j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
+                    } else {
+                        const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
+                        const u32x4 xl[3] = {xp[0], xp[1], xp[2]};
+#pragma unroll
+                        for (int j = 0; j < 3; j++)
+                            acc[t] = Mma<X2>::mma(xl[j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
+                    }
                 }
                 if (kTokTiles > 2 && (t & 1)) __builtin_amdgcn_sched_barrier(0);   // keep only two tiles of activations in flight
             }
