@@ -555,8 +555,15 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
+// 16-byte stores over the aligned middle of p[0..n), single floats at its ends
 __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (size_t)gridDim.x * blockDim.x;
+    const size_t head = min(n, (size_t)(((16 - (reinterpret_cast<uintptr_t>(p) & 15)) & 15) / 4));
+    float4* q = reinterpret_cast<float4*>(p + head);
+    const size_t n4 = (n - head) / 4, tail = n - head - 4 * n4;
+    for (size_t i = tid; i < n4; i += nthreads) q[i] = make_float4(v, v, v, v);
+    if (tid < head) p[tid] = v;
+    if (tid < tail) p[head + 4 * n4 + tid] = v;
 }
 
 template <typename X2> struct Mma;
@@ -1122,7 +1129,7 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
     ksplit = std::max(1u, std::min(ksplit, std::max(1u, spt / 8)));
     if (ksplit > 1) {
         const size_t ny = (size_t)M * N;
-        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     }
     const dim3 grid(strips, passes, ksplit);
     const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kTokens * kATokenPitch;
@@ -1138,7 +1145,7 @@ static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* 
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M > 64) return launch_prefill<FMT, X2, 8, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
-    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny + 255) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
 }
 

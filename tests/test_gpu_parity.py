@@ -378,6 +378,24 @@ def test_matmul_long_launch_several_passes(gpu, oracle13, N, K, M):
     _matmul_case(gpu, oracle13, 6, 4000 + M, N, K, M, sample_rows=3000)
 
 
+@pytest.mark.parametrize("M", [5, 70])
+def test_matmul_output_not_16_byte_aligned(gpu, oracle13, M):
+    """the split-K paths clear y first (16-byte stores over the aligned middle, single floats at the ends): an output
+    that starts one float into an allocation is cleared exactly, and its neighbours stay untouched"""
+    import torch
+    N, K = 77, 600
+    idx, gain, x = synth.layer(6, 5000 + M, N, K, M)
+    KB = idx.shape[1]
+    buf = torch.full((M * N + 2,), 3.0, dtype=torch.float32, device="cuda:0")
+    y = buf[1:1 + M * N].view(M, N)
+    assert y.data_ptr() % 16 == 4
+    gpu.llvq_matmul(_dev(x).to(torch.float16), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1)), N, KB, out=y)
+    assert float(buf[0]) == 3.0 and float(buf[-1]) == 3.0
+    ref = oracle13.matmul(x, idx, gain)
+    got = y.cpu().numpy().astype(np.float64)
+    assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL
+
+
 def test_matmul_random_small_shapes(gpu, oracle13):
     rng = np.random.default_rng(77)
     for case in range(24):
