@@ -171,7 +171,11 @@ def main():
         # cycle); the HBM view of the same launch (algorithmic bytes against 8 TB/s) rides along
         "roofline": {"bound": "alu", "achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
                      "unit": "T lane-ops/s", "frac": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12 / ALU_PEAK_TLOPS,
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH, "kernel": "matmul_kernel<U48,f16,BIG_GLOBAL>", "kernel_ms": kern_ms,
+                     # the counter figure was taken on the default 4096-row layer; the library's long-launch variant
+                     # (all tables in LDS, batches dealt through a counter) starts at 64 wave-batches per compute unit
+                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if N == 4096 else None,
+                     "kernel": "matmul_kernel<U48,f16,%s>" % ("short launch" if nblk // 64 < 64 * torch.cuda.get_device_properties(dev).multi_processor_count else "long launch"),
+                     "kernel_ms": kern_ms,
                      "valu_instructions_per_block": VALU_PER_BLOCK,
                      "hbm": {"achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
                              "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk}},
