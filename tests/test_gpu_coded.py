@@ -188,6 +188,48 @@ def test_packed_words_carry_index_and_gain(gpu, oracle13, src_fmt):
     assert _rel(y, oracle13.matmul(x300, idx, gain)) <= TOL
 
 
+def test_coded_formats_on_a_long_launch(gpu, oracle13):
+    """the three word formats on a layer long enough for the long-launch kernels (all tables in LDS, batches of 64
+    blocks taken from a counter): 24-bit single-shell words, packed 64-bit words, 47 + 1 bits in 48-bit words;
+    products on sampled rows and decoded blocks on sampled positions against the oracle"""
+    import torch
+    N, KB = 9000, 171                                  # 1,539,000 blocks: 94 wave-batches per compute unit
+    K = 24 * KB
+    rng = synth.rng_for(8, 99)
+    rows = np.sort(np.random.default_rng(5).choice(N, 1500, replace=False))
+    pos = np.sort(np.random.default_rng(6).choice(N * KB, 30000, replace=False))
+    x = synth.activations(rng, 1, K)
+    d_x = _dev(x).half()
+    gain = synth.gains(rng, (N, KB))
+    d_gain = _dev(gain.reshape(-1))
+    # 24-bit words over shell 3
+    base = gpu.llvq_shell_offset(3)
+    n3 = gpu.llvq_shell_offset(4) - base
+    words = synth.indices(rng, (N, KB), n3)
+    d24 = _dev(synth.pack_u24(words).reshape(-1))
+    y = gpu.llvq_matmul_coded(d_x, d24, N, KB, 24, base, gain=d_gain, fmt=LLVQ_IDX_U24).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x, words[rows] + np.uint64(base), gain[rows])) <= 1e-5
+    pts = gpu.llvq_decode_i8_coded(d24, 24, base, fmt=LLVQ_IDX_U24)
+    want, _ = oracle13.decode(words.reshape(-1)[pos] + np.uint64(base))
+    assert np.array_equal(pts[torch.from_numpy(pos).to("cuda:0")].cpu().numpy(), want)
+    # packed 64-bit words: index + fp16 gain
+    idx = synth.indices(rng, (N, KB))
+    packed = gpu.llvq_repack(_dev(synth.pack_u48(idx).reshape(-1)), d_gain)
+    y = gpu.llvq_matmul_coded(d_x, packed, N, KB, 48).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x, idx[rows], gain[rows])) <= 1e-5
+    w = gpu.llvq_decode_coded(packed, 48, out_dtype=torch.float32)
+    ref = oracle13.dequant(idx.reshape(-1)[pos], gain.reshape(-1)[pos])
+    got = w[torch.from_numpy(pos).to("cuda:0")].cpu().numpy().astype(np.float64)
+    assert (np.abs(got - ref) <= 3 * 2.0 ** -24 * np.abs(ref) + 1e-30).all()
+    # 47 shape bits + 1 gain bit in a 48-bit word
+    shape = synth.indices(rng, (N, KB), 1 << 47)
+    code = rng.integers(0, 2, size=(N, KB), dtype=np.uint64)
+    lut = synth.chi_gain_levels(1, scale=0.02)
+    d48 = _dev(synth.pack_u48((code << np.uint64(47)) | shape).reshape(-1))
+    y = gpu.llvq_matmul_coded(d_x, d48, N, KB, 47, gain_lut=_dev(lut)).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x, shape[rows], lut[code[rows].astype(np.int64)])) <= 1e-5
+
+
 def test_repack_empty_and_invalid(gpu):
     import torch
     from paper_2603_11021_amd import LLVQError
