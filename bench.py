@@ -261,6 +261,26 @@ def extra_layer_set(q, synth, torch, dev):
         print("%s layer set x%d, q/k/v and gate/up stored as one matrix each (4 launches per block): %.3f ms per pass, "
               "%.2f G blocks/s" % (label, copies, ms, tot / ms / 1e6), file=sys.stderr)
         del fused
+        # the same with the separate matrices left as they are and llvq_matmul_multi running q/k/v and gate/up in one launch each
+        multi = []
+        for rep in range(copies):
+            blk = {l[0]: l for l in layers[rep * per:(rep + 1) * per]}
+            for group in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",)):
+                ls = [blk[g] for g in group]
+                multi.append((ls[0][1], [l[2] for l in ls], [l[3] for l in ls], [l[4] for l in ls], ls[0][5], [l[6] for l in ls]))
+        for (x, idxs, gains, Ns, KB, ys) in multi:
+            q.llvq_matmul_multi(x, idxs, gains, Ns, KB, outs=ys)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            for (x, idxs, gains, Ns, KB, ys) in multi:
+                q.llvq_matmul_multi(x, idxs, gains, Ns, KB, outs=ys)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        print("%s layer set x%d, llvq_matmul_multi for q/k/v and for gate/up (4 launches per block, matrices stored separately): "
+              "%.3f ms per pass, %.2f G blocks/s" % (label, copies, ms, tot / ms / 1e6), file=sys.stderr)
+        del multi
         if copies == 1:
             outs = [torch.empty((N * KB, 24), dtype=torch.bfloat16, device=dev) for (_, _, _, _, N, KB, _) in layers]
             for (_, _, idx, gain, N, KB, _), o in zip(layers, outs):

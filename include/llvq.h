@@ -67,7 +67,7 @@ enum {
 
 /* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 13, on HIP device `device`.
  * Builds the constant tables (Golay words, class records, ranking tables) on the host and copies
- * them to the device.  The tables are immutable afterwards; llvq_decode*, llvq_matmul, llvq_matmul_coded, llvq_encode,
+ * them to the device.  The tables are immutable afterwards; llvq_decode*, llvq_matmul, llvq_matmul_multi, llvq_matmul_coded, llvq_encode,
  * llvq_repack, llvq_quantize and llvq_shell_offset may be called on one context from several threads.  llvq_matmul_ws,
  * llvq_gptq_quantize (they share the context's BLAS handle) and llvq_validate (its counter) may not.   */
 int llvq_create(llvq_ctx** out, int m_max, int device);
@@ -113,6 +113,17 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
                 float* d_y, void* stream);
+
+/* The products y_i = W_i x of n_items (1..4) matrices that share the activations x, K (KB blocks per row) and the word
+ * format: the q/k/v or the gate/up matrices of a transformer block (the fused product of paper App. C, several
+ * weight matrices per launch).  d_idx, d_gain, N and d_y are HOST arrays of n_items entries (device pointers and row
+ * counts, read during the call); every matrix and every output is laid out as for llvq_matmul (y_i is [M][N_i]).  For
+ * M <= 2 all products run in ONE launch, which pays the per-launch start-up once; for larger M the call is the same
+ * as n_items calls of llvq_matmul.  Requires (N_0 + .. + N_last)*KB < 2^32; arguments and errors otherwise as for
+ * llvq_matmul (LLVQ_EINVAL also for n_items outside 1..4).                                                   */
+int llvq_matmul_multi(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_items,
+                      const void* const* d_idx, int fmt, const void* const* d_gain, const int* N, int KB,
+                      float* const* d_y, void* stream);
 
 /* llvq_matmul with a caller-provided device workspace of ws_bytes >= N*KB*48 bytes (16-byte aligned).  For
  * M >= 96 the weights are then dequantised ONCE into the workspace in the activation type (the kernel of

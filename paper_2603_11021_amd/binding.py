@@ -52,6 +52,7 @@ def _load():
     lib.llvq_decode_i8.argtypes = [vp, vp, i32, sz, vp, vp]; lib.llvq_decode_i8.restype = i32
     lib.llvq_decode.argtypes = [vp, vp, i32, vp, sz, vp, i32, vp]; lib.llvq_decode.restype = i32
     lib.llvq_matmul.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp]; lib.llvq_matmul.restype = i32
+    lib.llvq_matmul_multi.argtypes = [vp, vp, i32, i32, i32, vp, i32, vp, vp, i32, vp, vp]; lib.llvq_matmul_multi.restype = i32
     lib.llvq_matmul_ws.argtypes = [vp, vp, i32, i32, vp, i32, vp, i32, i32, vp, vp, sz, vp]; lib.llvq_matmul_ws.restype = i32
     lib.llvq_shell_offset.argtypes = [vp, i32]; lib.llvq_shell_offset.restype = u64
     lib.llvq_decode_i8_coded.argtypes = [vp, vp, i32, i32, u64, sz, vp, vp]; lib.llvq_decode_i8_coded.restype = i32
@@ -163,6 +164,34 @@ class LLVQ:
         self._check(self._lib.llvq_matmul(self._h, x2.data_ptr(), code, M, idx.data_ptr(), fmt, gain.data_ptr(), N, KB,
                                           out.data_ptr(), _stream_handle(stream)), "llvq_matmul")
         return out
+
+    def llvq_matmul_multi(self, x, idxs, gains, Ns, KB, outs=None, stream=None):
+        """y_i = W_i x for up to four matrices that share x: lists of index tensors, gain tensors and row counts."""
+        import torch
+        n_items = len(idxs)
+        if not (len(gains) == len(Ns) == n_items) or (outs is not None and len(outs) != n_items):
+            raise LLVQError("idxs, gains, Ns and outs must have the same length")
+        code = {torch.float16: LLVQ_F16, torch.bfloat16: LLVQ_BF16}[x.dtype]
+        x2 = x.reshape(-1, 24 * KB)
+        M = x2.shape[0]
+        fmt = None
+        for idx, gain, N in zip(idxs, gains, Ns):
+            f, n = self._idx_fmt(idx)
+            if fmt is not None and f != fmt:
+                raise LLVQError("all matrices must use the same index format")
+            fmt = f
+            if n != N * KB or gain.numel() != N * KB or gain.dtype != torch.float16:
+                raise LLVQError("idx and gain must hold N*KB blocks; gain float16")
+        if outs is None:
+            outs = [torch.empty((M, N), dtype=torch.float32, device=x.device) for N in Ns]
+        P = ctypes.c_void_p * max(n_items, 1)
+        a_idx = P(*[t.data_ptr() for t in idxs])
+        a_gain = P(*[t.data_ptr() for t in gains])
+        a_y = P(*[t.data_ptr() for t in outs])
+        a_n = (ctypes.c_int * max(n_items, 1))(*[int(N) for N in Ns])
+        self._check(self._lib.llvq_matmul_multi(self._h, x2.data_ptr(), code, M, n_items, a_idx, fmt if fmt is not None else 0,
+                                                a_gain, a_n, KB, a_y, _stream_handle(stream)), "llvq_matmul_multi")
+        return outs
 
     # ---- coded words: shape index in the low shape_bits (+ base_index), gain code above them ------------------
     def llvq_decode_i8_coded(self, idx, shape_bits, base_index=0, fmt=None, out=None, stream=None):

@@ -370,21 +370,50 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // memory (short launches, where the table copy is a visible share); otherwise the whole blob is copied (long launches).
 // DYNAMIC: after its first two batches a wave takes the next free batch instead of every 16th one (long launches: the
 // SIMDs do not get through their batches at the same rate; short ones are faster with the fixed deal).
-template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC>
+// MULTI: the rows are those of up to four matrices that share x, K and the word format, one after the other (`items`);
+// a pass over the LDS accumulators never crosses from one matrix into the next.
+constexpr int kMaxItems = 4;
+struct MatItems {
+    const void* idx[kMaxItems];
+    const uint16_t* gain[kMaxItems];
+    float* y[kMaxItems];
+    int row_end[kMaxItems];        // rows of matrices 0..i together; entries past the last matrix repeat the total
+};
+
+template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC, bool MULTI = false>
 __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
                                                           const void* __restrict__ idx, const uint16_t* __restrict__ gain,
                                                           const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                          Code cd, uint32_t kb_magic, int rows_per_wg, int rows_per_pass, float* __restrict__ y) {
+                                                          Code cd, uint32_t kb_magic, int rows_per_wg, int rows_per_pass, MatItems items,
+                                                          float* __restrict__ y) {
     const int wg_r0 = blockIdx.x * rows_per_wg;
     const int wg_r1 = min(N, wg_r0 + rows_per_wg);
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: loop control below is wave-uniform
+    // The matrix that holds row r of the concatenation, and what a pass starting there works on: its arrays, its output,
+    // its first row and the number of rows the pass may take (all wave-uniform).
+    struct Pass { const void* idx; const uint16_t* gain; float* y; int first, rows, n_out; };
+    auto pass_at = [&](int r) {
+        Pass p = {idx, gain, y, 0, min(rows_per_pass, wg_r1 - r), N};
+        if constexpr (MULTI) {
+            int it = 0;
+#pragma unroll
+            for (int i = 0; i + 1 < kMaxItems; i++) {
+                if (r >= items.row_end[i]) { it = i + 1; p.first = items.row_end[i]; }
+            }
+            p.idx = items.idx[it]; p.gain = items.gain[it]; p.y = items.y[it];
+            p.rows = min(p.rows, items.row_end[it] - r);
+            p.n_out = items.row_end[it] - p.first;
+        }
+        return p;
+    };
     // the words of this wave's first batch are requested now: their trip from HBM overlaps the table copy below
     RawBlock first_raw;
     {
-        const uint32_t nblk = (uint32_t)min(rows_per_pass, wg_r1 - wg_r0) * (uint32_t)KB;
-        const size_t blk0 = (size_t)wg_r0 * KB;
-        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
-        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
+        const Pass p = pass_at(wg_r0);
+        const uint32_t nblk = (uint32_t)p.rows * (uint32_t)KB;
+        const size_t blk0 = (size_t)(wg_r0 - p.first) * KB;
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(p.idx) + blk0 * kWordBytes<FMT>;
+        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(p.gain + blk0) : idx0;
         load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
@@ -401,13 +430,15 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     // rows_per_pass <= kRowsPerPass keeps a pass below 2^24 blocks (block numbers inside a pass go through 24-bit multiplies)
-    for (int r0 = wg_r0; r0 < wg_r1; r0 += rows_per_pass) {
-        const int nrows = min(rows_per_pass, wg_r1 - r0);
+    int nrows = 0;
+    for (int r0 = wg_r0; r0 < wg_r1; r0 += nrows) {
+        const Pass ps = pass_at(r0);
+        nrows = ps.rows;
         const uint32_t nblk = (uint32_t)nrows * (uint32_t)KB;
-        const size_t blk0 = (size_t)r0 * KB;
+        const size_t blk0 = (size_t)(r0 - ps.first) * KB;
         // wave-uniform starts of this pass in the index and gain arrays (gains from a table: any readable address)
-        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(idx) + blk0 * kWordBytes<FMT>;
-        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(gain + blk0) : idx0;
+        const unsigned char* idx0 = reinterpret_cast<const unsigned char*>(ps.idx) + blk0 * kWordBytes<FMT>;
+        const unsigned char* gain0 = cd.gain_array() ? reinterpret_cast<const unsigned char*>(ps.gain + blk0) : idx0;
         for (int m0 = 0; m0 < M; m0 += kMaxMChunk) {
             const int mc = min(kMaxMChunk, M - m0);
             if (r0 != wg_r0 || m0 != 0) {
@@ -536,7 +567,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
             __syncthreads();
             for (int i = threadIdx.x; i < nrows * mc; i += kThreads) {
                 const int rr = i / mc, mi = i - rr * mc;
-                y[(size_t)(m0 + mi) * N + r0 + rr] = ysum[rr * kMaxMChunk + mi];
+                ps.y[(size_t)(m0 + mi) * ps.n_out + (r0 - ps.first) + rr] = ysum[rr * kMaxMChunk + mi];
             }
             __syncthreads();
         }
@@ -1029,8 +1060,10 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "dequant launch");
 }
 
-template <int FMT, typename X2>
-static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
+// MULTI: N is the number of rows of all matrices of `items` together; d_idx, d_gain and d_y are not used
+template <int FMT, typename X2, bool MULTI = false>
+static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st,
+                         const MatItems& items = MatItems{}) {
     // one persistent workgroup per compute unit (the tables fill its LDS), rows split evenly among them
     int grid = ctx->num_cu < N ? ctx->num_cu : N;
     const int rows = (N + grid - 1) / grid;
@@ -1043,10 +1076,10 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
 #define LLVQ_LAUNCH_MATMUL(BG, DYN)                                                                                         \
     do {                                                                                                                    \
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, BG, DYN>, lds)) return rc;                                         \
-        hipLaunchKernelGGL((matmul_kernel<FMT, X2, BG, DYN>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay,   \
-                           d_idx, reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N,  \
-                           KB, cd, kb_magic, rows, rows_pass, d_y);                                                         \
+        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, BG, DYN, MULTI>, lds)) return rc;                                  \
+        hipLaunchKernelGGL((matmul_kernel<FMT, X2, BG, DYN, MULTI>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob,      \
+                           ctx->lay, d_idx, reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), \
+                           M, N, KB, cd, kb_magic, rows, rows_pass, items, d_y);                                             \
     } while (0)
     if (short_launch) LLVQ_LAUNCH_MATMUL(true, false);
     else LLVQ_LAUNCH_MATMUL(false, true);
@@ -1223,6 +1256,43 @@ int matmul_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* 
     return LLVQ_BY_FMT(fmt, (launch_any_matmul<F, bf16x2_t>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st)));
 }
 
+int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_items, const void* const* d_idx, int fmt,
+                      const void* const* d_gain, const int* N, int KB, float* const* d_y, void* stream) {
+    if (!d_x || !d_idx || !d_gain || !N || !d_y) return LLVQ_EINVAL;
+    if (n_items < 1 || n_items > kMaxItems || M < 1 || M > 1024 || KB < 1 || KB >= (1 << 24)) return LLVQ_EINVAL;
+    if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
+    if (!aligned(d_x, 16)) return LLVQ_EALIGN;
+    const Code cd = plain_code(fmt);
+    size_t total = 0;
+    for (int i = 0; i < n_items; i++) {
+        if (!d_gain[i] || !d_y[i] || N[i] < 1) return LLVQ_EINVAL;
+        if (int rc = check_idx(d_idx[i], fmt)) return rc;
+        if (!aligned(d_gain[i], 2) || !aligned(d_y[i], 4)) return LLVQ_EALIGN;
+        total += (size_t)N[i];
+    }
+    if (total * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
+    if (n_items == 1 || M >= kMfmaMinM) {
+        // one matrix, or a batch that takes the matrix-core kernels: one product after the other
+        for (int i = 0; i < n_items; i++)
+            if (int rc = matmul_impl(ctx, d_x, x_dtype, M, d_idx[i], fmt, d_gain[i], cd, N[i], KB, d_y[i], stream)) return rc;
+        return LLVQ_OK;
+    }
+    MatItems items;
+    int rows = 0;
+    for (int i = 0; i < kMaxItems; i++) {
+        const int k = i < n_items ? i : n_items - 1;
+        if (i < n_items) rows += N[i];
+        items.idx[i] = d_idx[k];
+        items.gain[i] = reinterpret_cast<const uint16_t*>(d_gain[k]);
+        items.y[i] = d_y[k];
+        items.row_end[i] = rows;
+    }
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (x_dtype == LLVQ_F16)
+        return LLVQ_BY_FMT(fmt, (launch_matmul<F, half2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+    return LLVQ_BY_FMT(fmt, (launch_matmul<F, bf16x2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+}
+
 bool plain_fmt(int fmt) { return fmt == LLVQ_IDX_U48 || fmt == LLVQ_IDX_U64 || fmt == LLVQ_IDX_U24; }
 
 }  // namespace
@@ -1328,6 +1398,13 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* 
                 int N, int KB, float* d_y, void* stream) {
     if (!ctx || !d_gain || !plain_fmt(fmt)) return LLVQ_EINVAL;
     return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, plain_code(fmt), N, KB, d_y, stream);
+}
+
+int llvq_matmul_multi(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_items, const void* const* d_idx, int fmt,
+                      const void* const* d_gain, const int* N, int KB, float* const* d_y, void* stream) {
+    if (!ctx) return LLVQ_EINVAL;
+    if (!plain_fmt(fmt)) return LLVQ_EINVAL;
+    return matmul_multi_impl(ctx, d_x, x_dtype, M, n_items, d_idx, fmt, d_gain, N, KB, d_y, stream);
 }
 
 int llvq_decode_i8_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index, size_t n_blocks,

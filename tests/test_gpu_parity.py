@@ -396,6 +396,62 @@ def test_matmul_output_not_16_byte_aligned(gpu, oracle13, M):
     assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL
 
 
+@pytest.mark.parametrize("Ns,K,M", [((300, 77, 77), 600, 1), ((64, 1, 130, 5), 24 * 40, 2), ((50,), 480, 1),
+                                    ((200, 40), 24 * 9, 16)])
+def test_matmul_multi_small(gpu, oracle13, Ns, K, M):
+    """several matrices that share x in one call (one launch for M <= 2): each output against the oracle; row counts
+    chosen so that workgroups and passes straddle the boundaries between matrices"""
+    import torch
+    rng = synth.rng_for(6, 7000 + len(Ns) + M)
+    KB = synth.blocks_per_row(K)
+    x = synth.activations(rng, M, K)
+    idx = [synth.indices(rng, (N, KB)) for N in Ns]
+    gain = [synth.gains(rng, (N, KB)) for N in Ns]
+    ys = gpu.llvq_matmul_multi(_dev(x).to(torch.float16), [_dev(synth.pack_u48(i).reshape(-1)) for i in idx],
+                               [_dev(g.reshape(-1)) for g in gain], list(Ns), KB)
+    for y, i, g, N in zip(ys, idx, gain, Ns):
+        assert y.shape == (M, N)
+        ref = oracle13.matmul(x, i, g)
+        assert np.abs(y.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max() <= TOL
+
+
+def test_matmul_multi_llama3_8b_qkv_and_gate_up(gpu, oracle13):
+    """q/k/v (4096 + 1024 + 1024 rows: a short launch) and gate/up (2 x 14336 rows: a long launch) of a
+    Llama-3-8B-shaped block in one call each, sampled rows against the oracle"""
+    import torch
+    K = 4096
+    KB = synth.blocks_per_row(K)
+    for ordinal, Ns in ((7100, (4096, 1024, 1024)), (7200, (14336, 14336))):
+        rng = synth.rng_for(3, ordinal)
+        x = synth.activations(rng, 1, K)
+        idx = [synth.indices(rng, (N, KB)) for N in Ns]
+        gain = [synth.gains(rng, (N, KB)) for N in Ns]
+        ys = gpu.llvq_matmul_multi(_dev(x).to(torch.float16), [_dev(synth.pack_u48(i).reshape(-1)) for i in idx],
+                                   [_dev(g.reshape(-1)) for g in gain], list(Ns), KB)
+        for y, i, g, N in zip(ys, idx, gain, Ns):
+            rows = np.sort(np.random.default_rng(N + ordinal).choice(N, 600, replace=False))
+            rows[0], rows[-1] = 0, N - 1
+            ref = oracle13.matmul(x, i[rows], g[rows])
+            assert np.abs(y[:, rows].cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max() <= TOL
+
+
+def test_matmul_multi_invalid_arguments(gpu):
+    import torch
+    from paper_2603_11021_amd import LLVQError
+    KB = 2
+    x = torch.zeros((1, 48), dtype=torch.float16, device="cuda:0")
+    idx = torch.zeros(3 * KB * 6, dtype=torch.uint8, device="cuda:0")
+    gain = torch.ones(3 * KB, dtype=torch.float16, device="cuda:0")
+    with pytest.raises(LLVQError):
+        gpu.llvq_matmul_multi(x, [], [], [], KB)
+    with pytest.raises(LLVQError):
+        gpu.llvq_matmul_multi(x, [idx] * 5, [gain] * 5, [3] * 5, KB)
+    with pytest.raises(LLVQError):
+        gpu.llvq_matmul_multi(x, [idx, idx], [gain], [3, 3], KB)
+    ys = gpu.llvq_matmul_multi(x, [idx] * 4, [gain] * 4, [3] * 4, KB)
+    assert len(ys) == 4 and all(float(y.abs().max()) == 0.0 for y in ys)
+
+
 def test_matmul_random_small_shapes(gpu, oracle13):
     rng = np.random.default_rng(77)
     for case in range(24):
