@@ -236,7 +236,30 @@ def extra_layer_set(q, synth, torch, dev):
             ms = e0.elapsed_time(e1) / reps
             print("%s layer set x%d at batch 16: %.3f ms per pass, %.1f GB/s packed, %.2f G blocks/s" %
                   (label, copies, ms, tot * 8 / ms / 1e6, tot / ms / 1e6), file=sys.stderr)
-            del x16, y16
+            # and with q/k/v and gate/up going through llvq_matmul_multi (one batched-decode launch each)
+            per16 = len(shapes)
+            multi16 = []
+            for rep in range(copies):
+                ls_all = layers[rep * per16:(rep + 1) * per16]
+                ys_all = y16[rep * per16:(rep + 1) * per16]
+                blk = {l[0]: (l, yy) for l, yy in zip(ls_all, ys_all)}
+                for group in (("q", "k", "v"), ("o",), ("gate", "up"), ("down",)):
+                    ls = [blk[g][0] for g in group]
+                    multi16.append((x16[ls[0][5]], [l[2] for l in ls], [l[3] for l in ls], [l[4] for l in ls], ls[0][5],
+                                    [blk[g][1] for g in group]))
+            for (xx, idxs, gains, Ns, KB, ys) in multi16:
+                q.llvq_matmul_multi(xx, idxs, gains, Ns, KB, outs=ys)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                for (xx, idxs, gains, Ns, KB, ys) in multi16:
+                    q.llvq_matmul_multi(xx, idxs, gains, Ns, KB, outs=ys)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            print("%s layer set x%d at batch 16, llvq_matmul_multi for q/k/v and for gate/up: %.3f ms per pass, %.2f G blocks/s" %
+                  (label, copies, ms, tot / ms / 1e6), file=sys.stderr)
+            del x16, y16, multi16
         # the same weights with the layers that share their input stored as one matrix (q, k, v rows concatenated;
         # gate, up likewise): four launches per block instead of seven, same bytes
         fused = []

@@ -378,6 +378,7 @@ struct MatItems {
     const uint16_t* gain[kMaxItems];
     float* y[kMaxItems];
     int row_end[kMaxItems];        // rows of matrices 0..i together; entries past the last matrix repeat the total
+    int tile_end[kMaxItems];       // the same in tiles of 32 rows, every matrix rounded up (mfma_kernel)
 };
 
 template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC, bool MULTI = false>
@@ -597,6 +598,20 @@ __global__ void fill_kernel(float* __restrict__ p, size_t n, float v) {
     if (tid < tail) p[head + 4 * n4 + tid] = v;
 }
 
+// the same for the outputs of several matrices: blockIdx.y picks the matrix, M * (its rows) floats each
+__global__ void fill_multi_kernel(MatItems items, int M, float v) {
+    const int it = blockIdx.y;
+    float* p = items.y[it];
+    const size_t n = (size_t)M * (size_t)(items.row_end[it] - (it ? items.row_end[it - 1] : 0));
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x, nthreads = (size_t)gridDim.x * blockDim.x;
+    const size_t head = min(n, (size_t)(((16 - (reinterpret_cast<uintptr_t>(p) & 15)) & 15) / 4));
+    float4* q = reinterpret_cast<float4*>(p + head);
+    const size_t n4 = (n - head) / 4, tail = n - head - 4 * n4;
+    for (size_t i = tid; i < n4; i += nthreads) q[i] = make_float4(v, v, v, v);
+    if (tid < head) p[tid] = v;
+    if (tid < tail) p[head + 4 * n4 + tid] = v;
+}
+
 template <typename X2> struct Mma;
 template <> struct Mma<half2_t> {
     static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
@@ -627,11 +642,12 @@ constexpr int kGemmMinM = 96;       // from this many activation rows on, llvq_m
 constexpr int kMfmaMinM = 3;        // from this many activation rows on, llvq_matmul uses the MFMA kernel
 // THREADS x TOKTILES: more token tiles per pass over the weights need more accumulator registers, i.e. fewer
 // waves per SIMD.  Used as 1024 threads x 2 tiles (64 tokens per pass) for 3 <= M <= 64; larger M takes prefill_kernel.
-template <int FMT, typename X2, int THREADS, int kTokTiles>
+// MULTI: the row tiles are those of up to four matrices that share x, one matrix after the other (`items`).
+template <int FMT, typename X2, int THREADS, int kTokTiles, bool MULTI = false>
 __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
-                                                        const void* __restrict__ idx, const uint16_t* __restrict__ gain,
-                                                        const uint32_t* __restrict__ x, int M, int N, int KB,
-                                                        Code cd, uint32_t kranges, float* __restrict__ y) {
+                                                        const void* __restrict__ idx_in, const uint16_t* __restrict__ gain_in,
+                                                        const uint32_t* __restrict__ x, int M, int N_in, int KB,
+                                                        Code cd, uint32_t kranges, MatItems items, float* __restrict__ y_in) {
     constexpr int kWavesHere = THREADS / 64;
     load_tables<THREADS>(blob, lay.blob_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
@@ -642,11 +658,27 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
     // vector cache serves fifteen of sixteen requests.  (Dealing the steps to the waves as one contiguous sequence made
     // every wave fetch its own activations from L2: at M = 64 that traffic, not the decode, set the time.)
     const uint32_t spt = ((uint32_t)KB + 1) / 2;                         // steps (block pairs) per row tile
-    const uint32_t n_rt = ((uint32_t)N + 31) / 32;
-    const uint32_t rt = (uint32_t)blockIdx.x * kWavesHere + wave;
+    const uint32_t n_rt = MULTI ? (uint32_t)items.tile_end[kMaxItems - 1] : ((uint32_t)N_in + 31) / 32;
+    const uint32_t rt_all = (uint32_t)blockIdx.x * kWavesHere + wave;
     const uint32_t s0 = (uint32_t)(((uint64_t)spt * blockIdx.y) / kranges);
     const uint32_t s1 = (uint32_t)(((uint64_t)spt * (blockIdx.y + 1)) / kranges);
-    if (rt >= n_rt || s0 >= s1) return;
+    if (rt_all >= n_rt || s0 >= s1) return;
+    // the matrix this wave's row tile belongs to (wave-uniform) and the tile's number inside it
+    const void* idx = idx_in;
+    const uint16_t* gain = gain_in;
+    float* y = y_in;
+    int N = N_in;
+    uint32_t rt = rt_all;
+    if constexpr (MULTI) {
+        int it = 0, first_tile = 0, first_row = 0;
+#pragma unroll
+        for (int i = 0; i + 1 < kMaxItems; i++) {
+            if (rt_all >= (uint32_t)items.tile_end[i]) { it = i + 1; first_tile = items.tile_end[i]; first_row = items.row_end[i]; }
+        }
+        idx = items.idx[it]; gain = items.gain[it]; y = items.y[it];
+        N = items.row_end[it] - first_row;
+        rt = rt_all - (uint32_t)first_tile;
+    }
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
 
     for (int m0 = 0; m0 < M; m0 += 32 * kTokTiles) {
@@ -1088,20 +1120,21 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "matmul launch");
 }
 
-template <int FMT, typename X2, int THREADS, int TOKTILES>
-static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
+template <int FMT, typename X2, int THREADS, int TOKTILES, bool MULTI = false>
+static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st,
+                           const MatItems& items = MatItems{}) {
     // workgroups = groups of row tiles (one tile per wave) x ranges of block pairs; enough ranges to fill the chip, but
     // at least two steps each to amortise the write-back of a partial tile
     constexpr uint32_t wpg = THREADS / 64;
-    const uint32_t n_rt = (uint32_t)((N + 31) / 32), spt = (uint32_t)((KB + 1) / 2);
+    const uint32_t n_rt = MULTI ? (uint32_t)items.tile_end[kMaxItems - 1] : (uint32_t)((N + 31) / 32), spt = (uint32_t)((KB + 1) / 2);
     const uint32_t groups = (n_rt + wpg - 1) / wpg;
     uint32_t kranges = (uint32_t)ctx->num_cu / groups;
     kranges = std::max(1u, std::min(kranges, std::max(1u, spt / 2)));
     kranges = std::min(kranges, 65535u);
     const size_t lds = ctx->lay.blob_bytes;
-    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES>, lds)) return rc;
-    hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES>), dim3(groups, kranges), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kranges, d_y);
+    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES, MULTI>, lds)) return rc;
+    hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES, MULTI>), dim3(groups, kranges), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kranges, items, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
 }
@@ -1271,23 +1304,42 @@ int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
         total += (size_t)N[i];
     }
     if (total * (size_t)KB >= (1ull << 32)) return LLVQ_EINVAL;
-    if (n_items == 1 || M >= kMfmaMinM) {
-        // one matrix, or a batch that takes the matrix-core kernels: one product after the other
+    if (M >= kMfmaMinM) {
+        size_t tiles = 0;
+        for (int i = 0; i < n_items; i++) {
+            if ((size_t)M * (size_t)N[i] >= (1ull << 32)) return LLVQ_EINVAL;
+            tiles += (size_t)((N[i] + 31) / 32);
+        }
+        if (tiles * (size_t)((KB + 1) / 2) >= (1ull << 32) || (size_t)M * (size_t)KB * 12 >= (1ull << 32)) return LLVQ_EINVAL;
+    }
+    if (n_items == 1 || M > 64) {
+        // one matrix, or a batch that takes the strip kernel: one product after the other
         for (int i = 0; i < n_items; i++)
             if (int rc = matmul_impl(ctx, d_x, x_dtype, M, d_idx[i], fmt, d_gain[i], cd, N[i], KB, d_y[i], stream)) return rc;
         return LLVQ_OK;
     }
     MatItems items;
-    int rows = 0;
+    int rows = 0, tiles = 0;
     for (int i = 0; i < kMaxItems; i++) {
         const int k = i < n_items ? i : n_items - 1;
-        if (i < n_items) rows += N[i];
+        if (i < n_items) { rows += N[i]; tiles += (N[i] + 31) / 32; }
         items.idx[i] = d_idx[k];
         items.gain[i] = reinterpret_cast<const uint16_t*>(d_gain[k]);
         items.y[i] = d_y[k];
         items.row_end[i] = rows;
+        items.tile_end[i] = tiles;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (M >= kMfmaMinM) {
+        // the batched-decode kernel over the row tiles of all matrices; the outputs are cleared by one launch as well
+        int widest = 0;
+        for (int i = 0; i < n_items; i++) widest = std::max(widest, N[i]);
+        const size_t ny = (size_t)M * (size_t)widest;
+        hipLaunchKernelGGL(fill_multi_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 2048), (unsigned)n_items), dim3(256), 0, st, items, M, 0.0f);
+        if (x_dtype == LLVQ_F16)
+            return LLVQ_BY_FMT(fmt, (launch_mfma_cfg<F, half2_t, 1024, 2, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+        return LLVQ_BY_FMT(fmt, (launch_mfma_cfg<F, bf16x2_t, 1024, 2, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+    }
     if (x_dtype == LLVQ_F16)
         return LLVQ_BY_FMT(fmt, (launch_matmul<F, half2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
     return LLVQ_BY_FMT(fmt, (launch_matmul<F, bf16x2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));

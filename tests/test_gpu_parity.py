@@ -397,7 +397,7 @@ def test_matmul_output_not_16_byte_aligned(gpu, oracle13, M):
 
 
 @pytest.mark.parametrize("Ns,K,M", [((300, 77, 77), 600, 1), ((64, 1, 130, 5), 24 * 40, 2), ((50,), 480, 1),
-                                    ((200, 40), 24 * 9, 16)])
+                                    ((200, 40), 24 * 9, 16), ((33, 1, 64, 95), 24 * 31, 37), ((70, 45), 24 * 11, 100)])
 def test_matmul_multi_small(gpu, oracle13, Ns, K, M):
     """several matrices that share x in one call (one launch for M <= 2): each output against the oracle; row counts
     chosen so that workgroups and passes straddle the boundaries between matrices"""
@@ -415,15 +415,17 @@ def test_matmul_multi_small(gpu, oracle13, Ns, K, M):
         assert np.abs(y.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max() <= TOL
 
 
-def test_matmul_multi_llama3_8b_qkv_and_gate_up(gpu, oracle13):
+@pytest.mark.parametrize("M", [1, 16])
+def test_matmul_multi_llama3_8b_qkv_and_gate_up(gpu, oracle13, M):
     """q/k/v (4096 + 1024 + 1024 rows: a short launch) and gate/up (2 x 14336 rows: a long launch) of a
-    Llama-3-8B-shaped block in one call each, sampled rows against the oracle"""
+    Llama-3-8B-shaped block in one call each, at batch 1 (vector-ALU kernel) and 16 (matrix-core kernel); sampled rows
+    against the oracle"""
     import torch
     K = 4096
     KB = synth.blocks_per_row(K)
-    for ordinal, Ns in ((7100, (4096, 1024, 1024)), (7200, (14336, 14336))):
+    for ordinal, Ns in ((7100 + M, (4096, 1024, 1024)), (7200 + M, (14336, 14336))):
         rng = synth.rng_for(3, ordinal)
-        x = synth.activations(rng, 1, K)
+        x = synth.activations(rng, M, K)
         idx = [synth.indices(rng, (N, KB)) for N in Ns]
         gain = [synth.gains(rng, (N, KB)) for N in Ns]
         ys = gpu.llvq_matmul_multi(_dev(x).to(torch.float16), [_dev(synth.pack_u48(i).reshape(-1)) for i in idx],
