@@ -363,6 +363,48 @@ def test_matmul_calls_can_be_captured_in_a_graph(gpu, oracle13):
             assert np.abs(got.cpu().numpy() - c[6]).max() / np.abs(c[6]).max() <= TOL
 
 
+@pytest.mark.parametrize("M", [1, 16])
+def test_matmul_multi_can_be_captured_in_a_graph(gpu, oracle13, M):
+    """llvq_matmul_multi reads its host arrays during the call and enqueues kernels only: recorded into a HIP graph,
+    every replay reproduces the eager outputs (up to the order of the fp32 atomic adds) and matches the oracle"""
+    import torch
+    Ns, K = (200, 77, 130), 24 * 50
+    KB = synth.blocks_per_row(K)
+    rng = synth.rng_for(6, 7300 + M)
+    x = synth.activations(rng, M, K)
+    idx = [synth.indices(rng, (N, KB)) for N in Ns]
+    gain = [synth.gains(rng, (N, KB)) for N in Ns]
+    d_x = _dev(x).half()
+    d_idx = [_dev(synth.pack_u48(i).reshape(-1)) for i in idx]
+    d_gain = [_dev(g.reshape(-1)) for g in gain]
+    ys = [torch.empty((M, N), dtype=torch.float32, device="cuda:0") for N in Ns]
+    refs = [oracle13.matmul(x, i, g) for i, g in zip(idx, gain)]
+
+    def run():
+        gpu.llvq_matmul_multi(d_x, d_idx, d_gain, list(Ns), KB, outs=ys)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [y.clone() for y in ys]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for rep in range(3):
+        for y in ys:
+            y.fill_(float(rep + 1))                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for want, y, ref in zip(eager, ys, refs):
+            assert float((y - want).abs().max()) <= 2e-6 * float(want.abs().max())
+            assert np.abs(y.cpu().numpy() - ref).max() / np.abs(ref).max() <= TOL
+
+
 @pytest.mark.parametrize("N,K,M", [(20000, 48, 1), (17000, 24, 2), (33000, 72, 1), (70, 24 * 300, 2), (16385, 96, 1)])
 def test_matmul_many_rows_per_workgroup(gpu, oracle13, N, K, M):
     """more than 64 rows per workgroup (several passes over the LDS accumulators) and many rows per wave batch
