@@ -479,6 +479,30 @@ def test_matmul_multi_llama3_8b_qkv_and_gate_up(gpu, oracle13, M):
             assert np.abs(y[:, rows].cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max() <= TOL
 
 
+@pytest.mark.parametrize("M", [2, 5])
+def test_matmul_multi_bf16_activations_and_u64_indices(gpu, oracle13, M):
+    import torch
+    Ns, K = (90, 33), 24 * 21
+    KB = synth.blocks_per_row(K)
+    rng = synth.rng_for(6, 7400 + M)
+    x = synth.activations(rng, M, K, "bf16")
+    idx = [synth.indices(rng, (N, KB)) for N in Ns]
+    gain = [synth.gains(rng, (N, KB)) for N in Ns]
+    ys = gpu.llvq_matmul_multi(_dev(x).to(torch.bfloat16), [_dev(i.astype(np.int64).reshape(-1)) for i in idx],
+                               [_dev(g.reshape(-1)) for g in gain], list(Ns), KB)
+    for y, i, g, N in zip(ys, idx, gain, Ns):
+        got = y.cpu().numpy().astype(np.float64)
+        if M <= 2:                                       # vector-ALU kernel: exact weights
+            ref = oracle13.matmul(x, i, g)
+            assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL
+        else:
+            # matrix-core kernel: weights enter rounded to bf16 (2^-9 each, which a sum over only 21 blocks does not
+            # average out below the 2e-3 bar), so the check is against the oracle with weights rounded the same way
+            W = _round_to(oracle13.dequant(i.reshape(-1), g.reshape(-1)).reshape(N, KB * 24), "bf16")
+            ref2 = x.astype(np.float64) @ W.T
+            assert np.abs(got - ref2).max() / np.abs(ref2).max() <= 5e-4
+
+
 def test_matmul_multi_invalid_arguments(gpu):
     import torch
     from paper_2603_11021_amd import LLVQError
