@@ -209,6 +209,20 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                   uint64_t* h_bad, void* stream);
 
+/* llvq_validate for callers that cannot allocate or synchronise: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The count goes to DEVICE memory, nothing synchronises, and the call
+ * allocates nothing: the per-workgroup partial counts live in a 4 KB device array that is part of the library
+ * (every GPU the library runs on holds its copy until the process ends).
+ *   d_bad : DEVICE pointer, 8-byte aligned: receives the number of indices >= N(m_max) once the stream gets there
+ * n_blocks > LLVQ_VALIDATE_STATIC_MAX_BLOCKS is refused with LLVQ_EINVAL (llvq_last_hip_error names the limit):
+ * a workgroup's partial count has 32 bits.  n_blocks == 0 writes 0.  Every call on one GPU uses that GPU's one
+ * array, whatever the context: calls that overlap in time on one GPU (different streams, different threads)
+ * race and may report wrong counts; calls ordered on one stream are safe (each overwrites the partial counts
+ * it then adds, nothing needs clearing in between).                                                      */
+#define LLVQ_VALIDATE_STATIC_MAX_BLOCKS ((size_t)1 << 32)
+int llvq_validate_static(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
+                         uint64_t* d_bad, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

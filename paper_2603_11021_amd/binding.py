@@ -64,6 +64,7 @@ def _load():
     lib.llvq_gptq_workspace_bytes.argtypes = [i32]; lib.llvq_gptq_workspace_bytes.restype = sz
     lib.llvq_gptq_quantize.argtypes = [vp, vp, i32, i32, sz, vp, vp, i32, vp, vp, sz, vp]; lib.llvq_gptq_quantize.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
+    lib.llvq_validate_static.argtypes = [vp, vp, i32, sz, vp, vp]; lib.llvq_validate_static.restype = i32
     _lib = lib
     return lib
 
@@ -311,3 +312,14 @@ class LLVQ:
         self._check(self._lib.llvq_validate(self._h, idx.data_ptr(), fmt, n, ctypes.byref(bad), _stream_handle(stream)),
                     "llvq_validate")
         return int(bad.value)
+
+    def llvq_validate_static(self, idx, out=None, stream=None):
+        """Count of out-of-range indices into a one-element int64 device tensor; no synchronisation, no allocation
+        inside the library (`out` is allocated here when the caller passes none)."""
+        import torch
+        fmt, n = self._idx_fmt(idx)
+        if out is None:
+            out = torch.empty(1, dtype=torch.int64, device=idx.device)
+        self._check(self._lib.llvq_validate_static(self._h, idx.data_ptr(), fmt, n, out.data_ptr(), _stream_handle(stream)),
+                    "llvq_validate_static")
+        return out

@@ -979,6 +979,47 @@ __global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t
     if ((threadIdx.x & 63) == 0 && local) atomicAdd(bad, local);
 }
 
+// ---- llvq_validate_static: the same count without any allocation ----------------------------------------
+// Partial counts, one per workgroup, live in a device array of the library itself.  Host code never passes the
+// array by name: llvq_create asks the runtime for its address on the context's device and the launches pass that.
+constexpr int kValidateStaticMaxWg = 1024;
+constexpr int kValidateStaticThreads = 256;
+static __device__ __align__(256) unsigned int g_validate_scratch[kValidateStaticMaxWg];
+
+// every workgroup overwrites its own slot, so nothing has to be cleared between calls
+template <int FMT>
+__global__ void __launch_bounds__(kValidateStaticThreads) validate_partial_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints,
+                                                                                  unsigned int* __restrict__ partial) {
+    __shared__ unsigned int wave_count[kValidateStaticThreads / 64];
+    unsigned int local = 0;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
+        local += (load_index<FMT>(idx, k) & 0xFFFFFFFFFFFFull) >= npoints;
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
+    if ((threadIdx.x & 63) == 0) wave_count[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned int total = 0;
+        for (int w = 0; w < kValidateStaticThreads / 64; w++) total += wave_count[w];
+        partial[blockIdx.x] = total;
+    }
+}
+
+// one workgroup adds the first `nparts` partial counts (in a fixed order) and writes the total
+__global__ void __launch_bounds__(kValidateStaticThreads) validate_sum_kernel(const unsigned int* __restrict__ partial, int nparts,
+                                                                              unsigned long long* __restrict__ d_bad) {
+    __shared__ unsigned long long wave_sum[kValidateStaticThreads / 64];
+    unsigned long long local = 0;
+    for (int i = threadIdx.x; i < nparts; i += kValidateStaticThreads) local += partial[i];
+    for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
+    if ((threadIdx.x & 63) == 0) wave_sum[threadIdx.x >> 6] = local;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned long long total = 0;
+        for (int w = 0; w < kValidateStaticThreads / 64; w++) total += wave_sum[w];
+        *d_bad = total;
+    }
+}
+
 }  // namespace
 
 // ---- C ABI -------------------------------------------------------------------------------------------
@@ -997,6 +1038,7 @@ struct llvq_ctx {
     uint4* d_tile_a = nullptr;              // matrix-core operands of the class tiles
     float* d_tile_scale = nullptr;          // per-class factor and offset in accumulator order
     unsigned long long* d_counter = nullptr;
+    unsigned int* d_validate_scratch = nullptr;   // address of g_validate_scratch on this context's device (not owned)
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     std::string hip_error;
 };
@@ -1175,6 +1217,12 @@ static int launch_search(llvq_ctx* ctx, int metric, const float* d_w, size_t ldw
 template <int FMT>
 static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n, hipStream_t st) {
     hipLaunchKernelGGL(validate_kernel<FMT>, dim3(grid), dim3(256), 0, st, d_idx, n, ctx->lay.npoints, ctx->d_counter);
+    return 0;
+}
+
+template <int FMT>
+static int launch_validate_partial(int grid, const void* d_idx, size_t n, uint64_t npoints, unsigned int* partial, hipStream_t st) {
+    hipLaunchKernelGGL(validate_partial_kernel<FMT>, dim3(grid), dim3(kValidateStaticThreads), 0, st, d_idx, n, npoints, partial);
     return 0;
 }
 
@@ -1385,6 +1433,10 @@ int llvq_create(llvq_ctx** out, int m_max, int device) {
     if ((e = hipMalloc(&ctx->d_blob, tabs.blob.size())) != hipSuccess) { delete ctx; return LLVQ_EHIP; }
     if ((e = hipMalloc(&ctx->d_counter, sizeof(unsigned long long))) != hipSuccess) { (void)hipFree(ctx->d_blob); delete ctx; return LLVQ_EHIP; }
     if ((e = hipMemcpy(ctx->d_blob, tabs.blob.data(), tabs.blob.size(), hipMemcpyHostToDevice)) != hipSuccess) {
+        (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
+    }
+    // this device's copy of the library's own scratch array (llvq_validate_static)
+    if ((e = hipGetSymbolAddress(reinterpret_cast<void**>(&ctx->d_validate_scratch), HIP_SYMBOL(g_validate_scratch))) != hipSuccess) {
         (void)hipFree(ctx->d_blob); (void)hipFree(ctx->d_counter); delete ctx; return LLVQ_EHIP;
     }
     ctx->enc_lay = tabs.enc_lay;
@@ -1604,6 +1656,30 @@ int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, ui
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return hip_fail(ctx, e, "validate sync");
     *h_bad = got;
     return LLVQ_OK;
+}
+
+int llvq_validate_static(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, uint64_t* d_bad, void* stream) {
+    if (!ctx || !d_bad || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    if (n_blocks > LLVQ_VALIDATE_STATIC_MAX_BLOCKS) {
+        ctx->hip_error = "llvq_validate_static: n_blocks exceeds LLVQ_VALIDATE_STATIC_MAX_BLOCKS";
+        return LLVQ_EINVAL;
+    }
+    if (!aligned(d_bad, 8)) return LLVQ_EALIGN;
+    if (n_blocks) { if (int rc = check_idx(d_idx, fmt)) return rc; }
+    if (!ctx->d_validate_scratch) return LLVQ_EHIP;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int grid = 0;
+    if (n_blocks) {
+        const size_t wgs = (n_blocks + kValidateStaticThreads - 1) / kValidateStaticThreads;
+        grid = (int)std::min<size_t>(wgs, (size_t)std::min(kValidateStaticMaxWg, 4 * ctx->num_cu));
+        LLVQ_BY_FMT(fmt, launch_validate_partial<F>(grid, d_idx, n_blocks, ctx->lay.npoints, ctx->d_validate_scratch, st));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(ctx, e, "validate_static launch");
+    }
+    hipLaunchKernelGGL(validate_sum_kernel, dim3(1), dim3(kValidateStaticThreads), 0, st, ctx->d_validate_scratch, grid,
+                       reinterpret_cast<unsigned long long*>(d_bad));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "validate_static sum launch");
 }
 
 }  // extern "C"
