@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
-"""Benchmark of the LLVQ hot path on one MI355X: fused dequant-GEMV at batch 1 (paper App. C).
+"""Benchmark of the LLVQ hot path on one MI355X: fused dequant-GEMV at batch 1 (paper App. C) over the seven linear
+layers of a Llama-3-8B-shaped transformer block.
 
-A step = one call of llvq_matmul (index fetch, class lookup, unflatten, placement, signs, shape-gain scale,
-24-wide dot products, row reduction) over one synthetic 4096 x 4104 layer at ~2 bits/weight (48-bit index +
-fp16 gain per block of 24 weights), inputs resident in HBM.  Steps cycle through a ring of distinct layers
-larger than the last-level cache, so the packed weights really stream from HBM.
+A step = one pass of the whole hot path (index fetch, class lookup, unflatten, placement, signs, shape-gain scale,
+24-wide dot products, row reduction) over the block's layers at ~2 bits/weight (48-bit index + fp16 gain per block of
+24 weights): q/k/v in one llvq_matmul_multi launch, o, gate/up in one llvq_matmul_multi launch, down -- four launches,
+9,103,360 blocks, 72.8 MB of packed weights, inputs resident in HBM.  Steps cycle through a ring of distinct
+transformer blocks larger than the last-level cache, so the packed weights really stream from HBM.
 
-Prints ONE JSON line: whole-job packed-weight GB/s, the HBM roofline of the matmul kernel (algorithmic bytes:
-8 per block), and the oracle timed on the host CPU on the same workload.
+Prints ONE JSON line: whole-job packed-weight GB/s, the HBM roofline of the matmul kernel (algorithmic bytes: 8 per
+block, against its HIP-event time), the vector-ALU view of the same launches, the single 4096 x 4104 layer of the
+paper's own timing table, and the oracle timed on the host CPU on a sample of the same workload.
 """
 import argparse
 import json
@@ -22,21 +25,38 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 BYTES_PER_BLOCK = 8            # 6-byte index + 2-byte gain
 ALU_PEAK_TLOPS = 39.3          # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, one vector instruction per lane and cycle
-VALU_PER_BLOCK = 364           # SQ_INSTS_VALU per wave / 64 blocks, from profiles/matmul_gemv_4096x4104.txt
-TRAFFIC_BYTES_PER_LAUNCH = 7200973  # HBM bytes per launch: rocprofv3 FETCH_SIZE + WRITE_SIZE scaled by a copy kernel, see profiles/
+COUNTER_SUMMARY = os.path.join(ROOT, "profiles", "matmul_llama3_8b_layer_set_counters.txt")
+GROUPS = (("q", "k", "v"), ("o",), ("gate", "up"), ("down",))      # launches of a step: matrices that share their input
+
+
+def read_counter_summary(path=COUNTER_SUMMARY):
+    """`key = number` lines of the machine-written counter summary (paper_2603_11021_amd/profile_summary.py)."""
+    vals = {}
+    try:
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                try:
+                    vals[k.strip()] = float(v.split()[0])
+                except (ValueError, IndexError):
+                    pass
+    except OSError:
+        pass
+    return vals
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--layers", type=int, default=96, help="distinct layers in the ring (96 x 5.6 MB = 538 MB)")
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--ring", type=int, default=4, help="distinct transformer blocks in the ring (4 x 72.8 MB = 291 MB)")
+    ap.add_argument("--single-layers", type=int, default=48, help="distinct layers in the ring of the single-layer figure (48 x 5.6 MB = 269 MB)")
     ap.add_argument("--rows", type=int, default=4096,
-                    help="output rows N of the timed layer; 4096 is the headline workload, larger values amortise the per-launch "
-                         "fixed cost (used for the per-block instruction counts in profiles/)")
+                    help="output rows N of the single-layer figure; larger values amortise the per-launch fixed cost")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--extra", action="store_true", help="also time the Llama-3-8B-shaped layer set, batch 16, prefill and bulk decode (stderr)")
+    ap.add_argument("--no-single", action="store_true", help="skip the single 4096 x 4104 layer figure")
+    ap.add_argument("--extra", action="store_true", help="also time the layer sets launch by launch, batch 16, prefill and bulk decode (stderr)")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batch-1 product over a range of sizes, 320 launches each (stderr); under "
                          "rocprofv3 --kernel-trace the dispatches appear in this order")
@@ -54,30 +74,38 @@ def main():
         sys.exit("bench.py: no GPU visible; the library has no CPU path")
     dev = torch.device("cuda:0")
     q = LLVQ(13, 0)
+    M = 1
 
-    N, K, M = args.rows, 4096, 1
-    KB = synth.blocks_per_row(K)            # 171 blocks, K_pad = 4104
-    nblk = N * KB
-    # ring of distinct layers: uniform indices over the union of shells 2..13, log-normal gains
-    rng = synth.rng_for(2, 0)
-    idx0 = synth.indices(rng, (N, KB))
-    gain0 = synth.gains(rng, (N, KB))
-    x0 = synth.activations(rng, M, K)
-    ring_idx, ring_gain = [], []
-    for l in range(args.layers):
-        if l == 0:
-            idx, gain = idx0, gain0
-        else:
-            r = synth.rng_for(2, l)
+    # ring of distinct Llama-3-8B-shaped transformer blocks: uniform indices over the union of shells 2..13, log-normal gains
+    shapes = synth.LLAMA3_8B
+    host0 = {}                                   # block 0 stays on the host for the parity check and the CPU baseline
+    ring = []
+    nblk = 0
+    for b in range(args.ring):
+        mats = {}
+        for i, (name, (N, K)) in enumerate(shapes.items()):
+            KB = synth.blocks_per_row(K)
+            r = synth.rng_for(3, 10 * b + i)
             idx, gain = synth.indices(r, (N, KB)), synth.gains(r, (N, KB))
-        ring_idx.append(torch.from_numpy(synth.pack_u48(idx).reshape(-1)).to(dev))
-        ring_gain.append(torch.from_numpy(gain.reshape(-1)).to(dev))
-    d_x = torch.from_numpy(x0.astype(np.float16)).to(dev)
-    y = torch.empty((M, N), dtype=torch.float32, device=dev)
+            if b == 0:
+                host0[name] = (idx, gain)
+                nblk += N * KB
+            mats[name] = (torch.from_numpy(synth.pack_u48(idx).reshape(-1)).to(dev), torch.from_numpy(gain.reshape(-1)).to(dev), N, KB)
+        launches = []
+        for group in GROUPS:
+            ms = [mats[g] for g in group]
+            launches.append((group, [m[0] for m in ms], [m[1] for m in ms], [m[2] for m in ms], ms[0][3],
+                             [torch.empty((M, m[2]), dtype=torch.float32, device=dev) for m in ms]))
+        ring.append(launches)
+    x_host = {}
+    for K in sorted({K for (_, K) in shapes.values()}):
+        x_host[synth.blocks_per_row(K)] = synth.activations(synth.rng_for(3, 900 + K % 997), M, K)
+    d_x = {KB: torch.from_numpy(x.astype(np.float16)).to(dev) for KB, x in x_host.items()}
+    n_launch = len(GROUPS)
 
     def step(i):
-        l = i % args.layers
-        q.llvq_matmul(d_x, ring_idx[l], ring_gain[l], N, KB, out=y)
+        for (_, idxs, gains, Ns, KB, ys) in ring[i % args.ring]:
+            q.llvq_matmul_multi(d_x[KB], idxs, gains, Ns, KB, outs=ys)
 
     for i in range(args.warmup):
         step(i)
@@ -90,32 +118,41 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    kern_ms = e0.elapsed_time(e1) / args.steps          # HIP events on the launch stream: avg per launch
+    ev_ms = e0.elapsed_time(e1) / args.steps            # HIP events on the launch stream: all launches of a step
     ms_per_step = wall * 1e3 / args.steps
     gbs = BYTES_PER_BLOCK * nblk / (ms_per_step * 1e-3) / 1e9
-    ach = BYTES_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e9
+    ach = BYTES_PER_BLOCK * nblk / (ev_ms * 1e-3) / 1e9
 
-    # parity of the timed configuration against the oracle on sampled rows (layer 0)
+    # parity of the timed configuration against the oracle on sampled rows of every layer of block 0
     from oracle.llvq_oracle import Oracle
     oracle = Oracle(13)
     step(0)
-    rows = np.arange(0, N, 64)
-    ref = oracle.matmul(x0, idx0[rows], gain0[rows])
-    err = float(np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - ref).max() / np.abs(ref).max())
+    torch.cuda.synchronize()
+    err = 0.0
+    for (group, _, _, Ns, KB, ys) in ring[0]:
+        for name, N, y in zip(group, Ns, ys):
+            rows = np.arange(0, N, 64)
+            idx, gain = host0[name]
+            ref = oracle.matmul(x_host[KB], idx[rows], gain[rows])
+            err = max(err, float(np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - ref).max() / np.abs(ref).max()))
 
     cpu = None
     if not args.no_cpu_baseline:
+        # the oracle on one layer of the step (q of block 0: 4096 x 4104, 700,416 blocks), one thread, then all cores
+        idx0, gain0 = host0["q"]
+        x0 = x_host[idx0.shape[1]]
+        nq = idx0.size
         t = time.perf_counter()
         reps = 0
         while time.perf_counter() - t < 10.0:
             oracle.matmul(x0, idx0, gain0)
             reps += 1
         dt = (time.perf_counter() - t) / reps
-        # the same oracle on all host cores this job may use: rows split among threads (the C routine holds no lock and
-        # writes only its own output slice; ctypes releases the interpreter lock during the call)
+        # rows split among threads (the C routine holds no lock and writes only its own output slice; ctypes releases
+        # the interpreter lock during the call)
         from concurrent.futures import ThreadPoolExecutor
         ncores = max(1, min(16, os.cpu_count() or 1))
-        bounds = np.linspace(0, N, ncores + 1).astype(int)
+        bounds = np.linspace(0, idx0.shape[0], ncores + 1).astype(int)
         with ThreadPoolExecutor(ncores) as pool:
             t = time.perf_counter()
             reps_all = 0
@@ -123,11 +160,16 @@ def main():
                 list(pool.map(lambda i: oracle.matmul(x0, idx0[bounds[i]:bounds[i + 1]], gain0[bounds[i]:bounds[i + 1]]), range(ncores)))
                 reps_all += 1
             dt_all = (time.perf_counter() - t) / reps_all
-        cpu = {"value": BYTES_PER_BLOCK * nblk / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-               "all_cores": {"value": BYTES_PER_BLOCK * nblk / dt_all / 1e9, "unit": "GB/s", "cores": ncores,
-                             "blocks_per_s": nblk / dt_all},
-               "sample": "full %dx4104 batch-1 layer (%d blocks), %d repetitions, single thread" % (N, nblk, reps),
-               "blocks_per_s": nblk / dt}
+        cpu = {"value": BYTES_PER_BLOCK * nq / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+               "all_cores": {"value": BYTES_PER_BLOCK * nq / dt_all / 1e9, "unit": "GB/s", "cores": ncores,
+                             "blocks_per_s": nq / dt_all},
+               "sample": "the q layer of the step (4096x4104, %d of the step's %d blocks), batch 1, %d repetitions, single thread" % (nq, nblk, reps),
+               "blocks_per_s": nq / dt}
+
+    # the single layer of the paper's own timing table (App. C: 4096 x 4104), ring of distinct layers, one launch per step
+    single = None
+    if not args.no_single:
+        single = single_layer(q, synth, torch, dev, args, oracle)
 
     # what a plain device copy reaches on this machine: 1 GiB read + 1 GiB written, HIP events, best of five
     csrc = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
@@ -155,33 +197,95 @@ def main():
             dst.copy_(src)                       # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
 
+    # instruction and traffic counts of these launches come from the tracked counter summary (rocprofv3 --pmc runs of
+    # this script, condensed by paper_2603_11021_amd/profile_summary.py); absent file: the fields are null
+    cs = read_counter_summary()
+    valu_per_block = cs.get("valu_instructions_per_block")
+    traffic = cs.get("hbm_traffic_bytes_per_step")
+    alu = None
+    if valu_per_block:
+        lane_ops = valu_per_block * nblk / (ev_ms * 1e-3) / 1e12
+        alu = {"valu_instructions_per_block": valu_per_block, "lds_instructions_per_block": cs.get("lds_instructions_per_block"),
+               "achieved": lane_ops, "peak": ALU_PEAK_TLOPS, "unit": "T lane-ops/s", "valu_issue_frac": lane_ops / ALU_PEAK_TLOPS,
+               "source": os.path.relpath(COUNTER_SUMMARY, ROOT)}
     out = {
         "metric": "LLVQ dequant-GEMV GB/s (packed weights)", "value": gbs, "unit": "GB/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
-        "config": {"workload": "dequant-GEMV batch 1, W %dx4104 (171 blocks of 24 per row), 48-bit indices uniform over "
-                               "Lambda24(13) + fp16 gain per block, x fp16, y fp32; ring of %d distinct layers" % (N, args.layers),
-                   "N": N, "K_pad": 24 * KB, "M": M, "blocks_per_step": nblk},
+        "config": {"workload": "Llama-3-8B-shaped layer set, dequant-GEMV batch 1: q/o 4096x4096, k/v 1024x4096, gate/up 14336x4096, "
+                               "down 4096x14336 (K padded to a multiple of 24), 48-bit indices uniform over Lambda24(13) + fp16 gain per "
+                               "block, x fp16, y fp32; q/k/v and gate/up through llvq_matmul_multi (4 launches per step); ring of %d "
+                               "distinct transformer blocks (%.0f MB)" % (args.ring, args.ring * nblk * 8 / 1e6),
+                   "M": M, "blocks_per_step": nblk, "launches_per_step": n_launch, "packed_bytes_per_step": BYTES_PER_BLOCK * nblk},
         "pct_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "hbm_copy_measured_GBs": copy_gbs, "pct_of_measured_copy": 100.0 * gbs / copy_gbs,
         "decoded_weights_per_s": 24.0 * nblk / (ms_per_step * 1e-3),
+        "blocks_per_s": nblk / (ev_ms * 1e-3),
         "max_rel_err_vs_oracle": err,
-        # the kernel is bound by the vector-ALU (and LDS-gather) work of the index decode, not by HBM: the roofline is the
-        # ALU one (vector instructions per block, measured, x blocks / kernel time against one instruction per lane and
-        # cycle); the HBM view of the same launch (algorithmic bytes against 8 TB/s) rides along
-        "roofline": {"bound": "alu", "achieved": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12, "peak": ALU_PEAK_TLOPS,
-                     "unit": "T lane-ops/s", "frac": VALU_PER_BLOCK * nblk / (kern_ms * 1e-3) / 1e12 / ALU_PEAK_TLOPS,
-                     # the counter figure was taken on the default 4096-row layer; the library's long-launch variant
-                     # (all tables in LDS, batches dealt through a counter) starts at 64 wave-batches per compute unit
-                     "traffic": TRAFFIC_BYTES_PER_LAUNCH if N == 4096 else None,
-                     "kernel": "matmul_kernel<U48,f16,%s>" % ("short launch" if nblk // 64 < 64 * torch.cuda.get_device_properties(dev).multi_processor_count else "long launch"),
-                     "kernel_ms": kern_ms,
-                     "valu_instructions_per_block": VALU_PER_BLOCK,
-                     "hbm": {"achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-                             "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk}},
+        # HBM roofline of the matmul kernel: algorithmic bytes (8 per block) of the launches of a step against their
+        # HIP-event time, per launch.  The kernel is in fact bound by the vector-ALU and LDS-gather work of the index
+        # decode, far below this roof: that view of the same launches is under "alu".
+        "roofline": {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": (traffic / n_launch) if traffic else None,
+                     "kernel": "matmul_kernel<U48,f16> (the four launches of a step: q/k/v, o, gate/up, down)",
+                     "kernel_ms": ev_ms / n_launch,
+                     "algorithmic_bytes_per_launch": BYTES_PER_BLOCK * nblk / n_launch,
+                     "launches_timed": args.steps * n_launch,
+                     "alu": alu},
+        "single_layer_4096x4104": single,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def single_layer(q, synth, torch, dev, args, oracle):
+    """llvq_matmul at batch 1 on one rows x 4104 layer (the shape of the paper's App. C table), ring of distinct layers."""
+    import numpy as np
+    N, K = args.rows, 4096
+    KB = synth.blocks_per_row(K)
+    nblk = N * KB
+    rng = synth.rng_for(2, 0)
+    idx0 = synth.indices(rng, (N, KB))
+    gain0 = synth.gains(rng, (N, KB))
+    x0 = synth.activations(rng, 1, K)
+    ring_idx, ring_gain = [], []
+    for l in range(args.single_layers):
+        if l == 0:
+            idx, gain = idx0, gain0
+        else:
+            r = synth.rng_for(2, l)
+            idx, gain = synth.indices(r, (N, KB)), synth.gains(r, (N, KB))
+        ring_idx.append(torch.from_numpy(synth.pack_u48(idx).reshape(-1)).to(dev))
+        ring_gain.append(torch.from_numpy(gain.reshape(-1)).to(dev))
+    d_x = torch.from_numpy(x0.astype(np.float16)).to(dev)
+    y = torch.empty((1, N), dtype=torch.float32, device=dev)
+    steps, warmup = max(args.steps, 20), max(args.warmup, 5)
+
+    def step(i):
+        l = i % args.single_layers
+        q.llvq_matmul(d_x, ring_idx[l], ring_gain[l], N, KB, out=y)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(steps):
+        step(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_us = (time.perf_counter() - t0) * 1e6 / steps
+    ev_us = e0.elapsed_time(e1) * 1e3 / steps
+    step(0)
+    rows = np.arange(0, N, 64)
+    ref = oracle.matmul(x0, idx0[rows], gain0[rows])
+    err = float(np.abs(y.cpu().numpy().astype(np.float64)[:, rows] - ref).max() / np.abs(ref).max())
+    return {"workload": "dequant-GEMV batch 1, W %dx4104, ring of %d distinct layers, one llvq_matmul launch per step" % (N, args.single_layers),
+            "steps": steps, "warmup": warmup, "us_per_launch_wall": wall_us, "us_per_launch_events": ev_us,
+            "packed_GBs_events": BYTES_PER_BLOCK * nblk / ev_us / 1e3, "hbm_frac_events": BYTES_PER_BLOCK * nblk / ev_us / 1e3 / HBM_PEAK_GBS,
+            "blocks": nblk, "max_rel_err_vs_oracle": err,
+            "paper_context": "the paper's App. C prints 11.94 us for a single-shell 24-bit code of this shape on an unnamed NVIDIA GPU"}
 
 
 def extra_layer_set(q, synth, torch, dev):

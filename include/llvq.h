@@ -74,7 +74,9 @@ int llvq_create(llvq_ctx** out, int m_max, int device);
 void llvq_destroy(llvq_ctx* ctx);
 
 const char* llvq_strerror(int rc);
-/* text of the last HIP error seen by this context ("" if none) */
+/* Text of the last failure seen by this context ("" if none).  The text is written under a lock, so calls that fail
+ * on several threads at once do not corrupt it, but it is one buffer per context: read it before another call on the
+ * same context can fail.                                                                                   */
 const char* llvq_last_hip_error(const llvq_ctx* ctx);
 
 /* N(m_max) = |Lambda_24(m_max)| (paper Table 1): 280,974,212,784,720 for m_max = 13. */
@@ -87,12 +89,13 @@ int llvq_num_classes(const llvq_ctx* ctx);
 uint64_t llvq_shell_offset(const llvq_ctx* ctx, int m);
 
 /* Dequantiser of paper App. A: d_out[k][0..23] = integer coordinates of index k, int8.
- * d_idx: n_blocks indices in format `fmt`.                                                        */
+ * d_idx: n_blocks indices in format `fmt`.  d_out must be 8-byte aligned (LLVQ_EALIGN otherwise).  */
 int llvq_decode_i8(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                    int8_t* d_out, void* stream);
 
 /* Shape-gain reconstruction (paper App. E): d_out[k][i] = g_k * x_i / sqrt(16 m_k), computed in
- * fp32 and rounded to out_dtype (LLVQ_F16, LLVQ_BF16 or LLVQ_F32).  d_gain: n_blocks fp16 gains.  */
+ * fp32 and rounded to out_dtype (LLVQ_F16, LLVQ_BF16 or LLVQ_F32).  d_gain: n_blocks fp16 gains
+ * (2-byte aligned).  d_out must be 16-byte aligned (LLVQ_EALIGN otherwise).                       */
 int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks,
                 void* d_out, int out_dtype, void* stream);
 

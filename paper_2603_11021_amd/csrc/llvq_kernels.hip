@@ -16,6 +16,7 @@
 #include <new>
 #include <atomic>
 #include <string>
+#include <mutex>
 
 #include "../../include/llvq.h"
 #include "llvq_decode_core.h"
@@ -1040,13 +1041,19 @@ struct llvq_ctx {
     unsigned long long* d_counter = nullptr;
     unsigned int* d_validate_scratch = nullptr;   // address of g_validate_scratch on this context's device (not owned)
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
-    std::string hip_error;
+    // text of the last failure: written under the lock (calls may fail on several threads at once), read without it
+    std::mutex err_mu;
+    char err[256] = {0};
+    void set_error(const std::string& text) {
+        std::lock_guard<std::mutex> hold(err_mu);
+        std::snprintf(err, sizeof err, "%s", text.c_str());
+    }
 };
 
 namespace {
 
 int hip_fail(llvq_ctx* ctx, hipError_t e, const char* what) {
-    if (ctx) ctx->hip_error = std::string(what) + ": " + hipGetErrorString(e);
+    if (ctx) ctx->set_error(std::string(what) + ": " + hipGetErrorString(e));
     return LLVQ_EHIP;
 }
 
@@ -1061,22 +1068,27 @@ int check_idx(const void* d_idx, int fmt) {
 }
 
 // Sets the dynamic LDS size of a kernel.  The kernels address their tables from LDS address 0 (lds_origin), which
-// holds only while a kernel declares no static LDS: checked here once per kernel.
-template <typename K>
-int set_lds(llvq_ctx* ctx, K kernel, size_t bytes) {
-    static std::atomic<int> static_lds_checked{0};       // one per kernel instantiation
-    if (!static_lds_checked.load(std::memory_order_relaxed)) {
-        hipFuncAttributes attr;
-        hipError_t q = hipFuncGetAttributes(&attr, reinterpret_cast<const void*>(kernel));
-        if (q != hipSuccess) return hip_fail(ctx, q, "hipFuncGetAttributes");
-        if (attr.sharedSizeBytes != 0) {
-            if (ctx) ctx->hip_error = "a kernel that addresses its tables from LDS address 0 declares static LDS";
-            return LLVQ_EHIP;
-        }
-        static_lds_checked.store(1, std::memory_order_relaxed);
+// holds only while a kernel declares no static LDS.  The kernel is a template argument, so the state below exists
+// once per kernel instantiation: the static-LDS check runs at that kernel's first launch on a device, and the
+// attribute is set again only when the size asked for changes.
+constexpr int kMaxDevices = 64;
+template <auto Kernel>
+int set_lds(llvq_ctx* ctx, size_t bytes) {
+    static std::atomic<size_t> configured[kMaxDevices];      // bytes + 1 of the last successful call on the device, 0: none yet
+    const int dev = ctx->device;
+    if (dev < kMaxDevices && configured[dev].load(std::memory_order_acquire) == bytes + 1) return LLVQ_OK;
+    const void* fn = reinterpret_cast<const void*>(Kernel);
+    hipFuncAttributes attr;
+    hipError_t q = hipFuncGetAttributes(&attr, fn);
+    if (q != hipSuccess) return hip_fail(ctx, q, "hipFuncGetAttributes");
+    if (attr.sharedSizeBytes != 0) {
+        ctx->set_error("a kernel that addresses its tables from LDS address 0 declares static LDS");
+        return LLVQ_EHIP;
     }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "hipFuncSetAttribute");
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e != hipSuccess) return hip_fail(ctx, e, "hipFuncSetAttribute");
+    if (dev < kMaxDevices) configured[dev].store(bytes + 1, std::memory_order_release);
+    return LLVQ_OK;
 }
 
 int grid_for(const llvq_ctx* ctx, size_t n, int per_cu = 1) {
@@ -1102,7 +1114,7 @@ static int launch_decode_i8(llvq_ctx* ctx, const void* d_idx, const Code& cd, si
     const int grid = grid_for(ctx, n, small ? 2 : 1);
 #define LLVQ_LAUNCH_I8(BG, DYN)                                                                                              \
     do {                                                                                                                     \
-        if (int rc = set_lds(ctx, decode_i8_kernel<FMT, BG, DYN>, lds)) return rc;                                           \
+        if (int rc = set_lds<decode_i8_kernel<FMT, BG, DYN>>(ctx, lds)) return rc;                                           \
         hipLaunchKernelGGL((decode_i8_kernel<FMT, BG, DYN>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay,     \
                            d_idx, cd, n, reinterpret_cast<uint32_t*>(d_out));                                                \
     } while (0)
@@ -1123,7 +1135,7 @@ static int launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, 
     const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
 #define LLVQ_LAUNCH_DQ(OUT, BG)                                                                                    \
     do {                                                                                                              \
-        if (int rc = set_lds(ctx, dequant_kernel<FMT, OUT, BG>, lds)) return rc;                                      \
+        if (int rc = set_lds<dequant_kernel<FMT, OUT, BG>>(ctx, lds)) return rc;                                      \
         hipLaunchKernelGGL((dequant_kernel<FMT, OUT, BG>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx, g, cd, n, d_out); \
     } while (0)
     if (out_dtype == LLVQ_F16) { if (small) LLVQ_LAUNCH_DQ(LLVQ_F16, true); else LLVQ_LAUNCH_DQ(LLVQ_F16, false); }
@@ -1150,7 +1162,7 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
 #define LLVQ_LAUNCH_MATMUL(BG, DYN)                                                                                         \
     do {                                                                                                                    \
-        if (int rc = set_lds(ctx, matmul_kernel<FMT, X2, BG, DYN, MULTI>, lds)) return rc;                                  \
+        if (int rc = set_lds<matmul_kernel<FMT, X2, BG, DYN, MULTI>>(ctx, lds)) return rc;                                  \
         hipLaunchKernelGGL((matmul_kernel<FMT, X2, BG, DYN, MULTI>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob,      \
                            ctx->lay, d_idx, reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), \
                            M, N, KB, cd, kb_magic, rows, rows_pass, items, d_y);                                             \
@@ -1174,7 +1186,7 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
     kranges = std::max(1u, std::min(kranges, std::max(1u, spt / 2)));
     kranges = std::min(kranges, 65535u);
     const size_t lds = ctx->lay.blob_bytes;
-    if (int rc = set_lds(ctx, mfma_kernel<FMT, X2, THREADS, TOKTILES, MULTI>, lds)) return rc;
+    if (int rc = set_lds<mfma_kernel<FMT, X2, THREADS, TOKTILES, MULTI>>(ctx, lds)) return rc;
     hipLaunchKernelGGL((mfma_kernel<FMT, X2, THREADS, TOKTILES, MULTI>), dim3(groups, kranges), dim3(THREADS), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, kranges, items, d_y);
     hipError_t e = hipGetLastError();
@@ -1189,11 +1201,11 @@ static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx
     const int grid = (int)std::max<size_t>(1, std::min<size_t>(wgs, (size_t)2 * ctx->num_cu));
     // from about 3.5 batches of 64 vectors per wave on, the waves take their batches as they finish
     if (n >= (size_t)ctx->num_cu * 64 * 112) {
-        if (int rc = set_lds(ctx, encode_kernel<FMT, true>, lds)) return rc;
+        if (int rc = set_lds<encode_kernel<FMT, true>>(ctx, lds)) return rc;
         hipLaunchKernelGGL((encode_kernel<FMT, true>), dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
                            reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
     } else {
-        if (int rc = set_lds(ctx, encode_kernel<FMT, false>, lds)) return rc;
+        if (int rc = set_lds<encode_kernel<FMT, false>>(ctx, lds)) return rc;
         hipLaunchKernelGGL((encode_kernel<FMT, false>), dim3(grid), dim3(kThreads), lds, st, ctx->d_enc_blob, ctx->enc_lay,
                            reinterpret_cast<const uint2*>(d_x), n, d_idx, out_stride);
     }
@@ -1247,7 +1259,7 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
     }
     const dim3 grid(strips, passes, ksplit);
     const size_t lds = ctx->lay.lds_bytes + 2 * (size_t)kTokens * kATokenPitch;
-    if (int rc = set_lds(ctx, prefill_kernel<FMT, X2, WAVES, TT>, lds)) return rc;
+    if (int rc = set_lds<prefill_kernel<FMT, X2, WAVES, TT>>(ctx, lds)) return rc;
     hipLaunchKernelGGL((prefill_kernel<FMT, X2, WAVES, TT>), grid, dim3(64 * WAVES), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, d_y);
     hipError_t e = hipGetLastError();
@@ -1410,7 +1422,7 @@ const char* llvq_strerror(int rc) {
     }
 }
 
-const char* llvq_last_hip_error(const llvq_ctx* ctx) { return ctx ? ctx->hip_error.c_str() : ""; }
+const char* llvq_last_hip_error(const llvq_ctx* ctx) { return ctx ? ctx->err : ""; }
 
 int llvq_create(llvq_ctx** out, int m_max, int device) {
     if (!out || m_max < 2 || m_max > 13 || device < 0) return LLVQ_EINVAL;
@@ -1582,8 +1594,8 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
     if (int rc = check_idx(d_idx, fmt)) return rc;
     if (!aligned(d_W, 4) || !aligned(d_U, 4) || !aligned(d_gain, 2) || !aligned(d_ws, 16)) return LLVQ_EALIGN;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->hip_error = "rocblas_create_handle failed"; return LLVQ_EHIP; }
-    if (rocblas_set_stream(ctx->blas, st) != rocblas_status_success) { ctx->hip_error = "rocblas_set_stream failed"; return LLVQ_EHIP; }
+    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->set_error("rocblas_create_handle failed"); return LLVQ_EHIP; }
+    if (rocblas_set_stream(ctx->blas, st) != rocblas_status_success) { ctx->set_error("rocblas_set_stream failed"); return LLVQ_EHIP; }
     float* d_E = reinterpret_cast<float*>(d_ws);                                             // [N][24]
     int8_t* d_pts = reinterpret_cast<int8_t*>(d_ws) + (((size_t)N * 24 * sizeof(float) + 255) & ~(size_t)255);   // [N][24]
     const size_t K = (size_t)24 * KB;
@@ -1610,7 +1622,7 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
         if (bs == rocblas_status_success)
             bs = rocblas_sgemm(ctx->blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)(K - r0), N, 24, &minus_one,
                                d_U + (size_t)24 * t * K + r0, (rocblas_int)K, d_E, 24, &one, d_W + r0, (rocblas_int)ldw);
-        if (bs != rocblas_status_success) { ctx->hip_error = std::string("rocblas: ") + rocblas_status_to_string(bs); return LLVQ_EHIP; }
+        if (bs != rocblas_status_success) { ctx->set_error(std::string("rocblas: ") + rocblas_status_to_string(bs)); return LLVQ_EHIP; }
     }
     return LLVQ_OK;
 }
@@ -1626,8 +1638,8 @@ int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const voi
     // step 1: shape-gain reconstruction of the whole matrix into the workspace, in the activation type
     if (int rc = llvq_decode(ctx, d_idx, fmt, d_gain, (size_t)N * KB, d_ws, x_dtype, stream)) return rc;
     // step 2: plain dense GEMM y[M][N] = x[M][K] * W[N][K]^T on the matrix cores (library routine), fp32 accumulate
-    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->hip_error = "rocblas_create_handle failed"; return LLVQ_EHIP; }
-    if (rocblas_set_stream(ctx->blas, reinterpret_cast<hipStream_t>(stream)) != rocblas_status_success) { ctx->hip_error = "rocblas_set_stream failed"; return LLVQ_EHIP; }
+    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->set_error("rocblas_create_handle failed"); return LLVQ_EHIP; }
+    if (rocblas_set_stream(ctx->blas, reinterpret_cast<hipStream_t>(stream)) != rocblas_status_success) { ctx->set_error("rocblas_set_stream failed"); return LLVQ_EHIP; }
     const float alpha = 1.0f, beta = 0.0f;
     const int K = 24 * KB;
     const rocblas_datatype ab = x_dtype == LLVQ_F16 ? rocblas_datatype_f16_r : rocblas_datatype_bf16_r;
@@ -1635,7 +1647,7 @@ int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const voi
     const rocblas_status st = rocblas_gemm_ex(ctx->blas, rocblas_operation_transpose, rocblas_operation_none, N, M, K, &alpha,
                                               d_ws, ab, K, d_x, ab, K, &beta, d_y, rocblas_datatype_f32_r, N,
                                               d_y, rocblas_datatype_f32_r, N, rocblas_datatype_f32_r, rocblas_gemm_algo_standard, 0, 0);
-    if (st != rocblas_status_success) { ctx->hip_error = std::string("rocblas_gemm_ex: ") + rocblas_status_to_string(st); return LLVQ_EHIP; }
+    if (st != rocblas_status_success) { ctx->set_error(std::string("rocblas_gemm_ex: ") + rocblas_status_to_string(st)); return LLVQ_EHIP; }
     return LLVQ_OK;
 }
 
@@ -1661,7 +1673,7 @@ int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, ui
 int llvq_validate_static(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, uint64_t* d_bad, void* stream) {
     if (!ctx || !d_bad || !plain_fmt(fmt)) return LLVQ_EINVAL;
     if (n_blocks > LLVQ_VALIDATE_STATIC_MAX_BLOCKS) {
-        ctx->hip_error = "llvq_validate_static: n_blocks exceeds LLVQ_VALIDATE_STATIC_MAX_BLOCKS";
+        ctx->set_error("llvq_validate_static: n_blocks exceeds LLVQ_VALIDATE_STATIC_MAX_BLOCKS");
         return LLVQ_EINVAL;
     }
     if (!aligned(d_bad, 8)) return LLVQ_EALIGN;

@@ -183,14 +183,14 @@ def test_matmul_u64_indices(gpu, oracle13):
     assert np.abs(y64.cpu().numpy() - ref).max() / np.abs(ref).max() <= TOL
 
 
-@pytest.mark.parametrize("name", ["k", "gate", "down"])
+@pytest.mark.parametrize("name", ["q", "k", "gate", "down"])
 def test_llama3_8b_layer_shapes_batch1_and_16(gpu, oracle13, name):
     N, K = synth.LLAMA3_8B[name]
     for M in (1, 16):
         _matmul_case(gpu, oracle13, 3, _ordinal(name, M), N, K, M, sample_rows=256)
 
 
-@pytest.mark.parametrize("name", ["q", "down"])
+@pytest.mark.parametrize("name", ["q", "k", "gate", "down"])
 def test_llama3_70b_layer_shapes_batch1(gpu, oracle13, name):
     N, K = synth.LLAMA3_70B[name]
     _matmul_case(gpu, oracle13, 5, _ordinal(name), N, K, 1, sample_rows=128)
