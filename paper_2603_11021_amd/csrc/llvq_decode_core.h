@@ -294,40 +294,42 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
         const bool odd = (f0 >> F0_ODD) & 1u;
         const bool outer_all = (f0 >> F0_OUTER_ALL) & 1u;
         const uint32_t cw = F.c;
-        const uint32_t cm = ((f0 >> F0_F1DIRECT) & 1u) ? cw : 0u;           // slots of the direct F1 word
         const uint32_t om = outer_all ? 0xFFFFFFu : (~cw & 0xFFFFFFu);      // positions of the outer domain
         const uint32_t sm = odd ? 0xFFFFFFu : cw;                           // positions taking a bit of sb
         const uint32_t sb = odd ? cw : s1;                                  // odd: the word itself flips signs
         const uint32_t dkeep = outer_all ? 0x04044444u : 0u;                // keep U as the domain bit
+        // The planes of the direct F1 word go through the same mask as the sign bits: where there is such a word
+        // (even class, 0 < w <= 16) both masks are the Golay word; everywhere else the planes are zero (the class
+        // points at an all-zero table entry), so only the mask bit of their entries has to be dropped.
+        const uint32_t f1keep = ((f0 >> F0_F1DIRECT) & 1u) ? 0x04044444u : 0u;
 
         // the running bit offsets start from a zero the compiler does not see through: with a literal 0 it rewrites the
         // first chunk's bit-field extracts into shift-and-mask forms that cost one more instruction per table address
         uint32_t zero = 0;
         keep_product(zero);
-        uint32_t o1 = zero, o0 = zero, os = zero, ou = zero;
+        uint32_t o0 = zero, os = zero, ou = zero;
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
             const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, omk * kPdepPitch + bfe6(U, ou));   // U in absolute positions
             ou += popc32(omk);
-            const uint32_t cmk = bfe6(cm, 6 * k), smk = bfe6(sm, 6 * k);
-            uint32_t cx = cmk * (4u * kSpreadPitch), ux = uk * (4u * kSpreadPitch), sx = smk * (4u * kSpreadPitch);
-            keep_product(cx); keep_product(ux);
-            const uint32_t gA1 = spread6_at(T, cx, a1, o1);
-            const uint32_t gB1 = spread6_at(T, cx, b1, o1);
-            o1 += popc32(cmk);
+            const uint32_t smk = bfe6(sm, 6 * k);
+            uint32_t ux = uk * (4u * kSpreadPitch), sx = smk * (4u * kSpreadPitch);
+            keep_product(sx); keep_product(ux);
+            const uint32_t gA1 = spread6_at(T, sx, a1, os);
+            const uint32_t gB1 = spread6_at(T, sx, b1, os);
+            const uint32_t gS1 = spread6_at(T, sx, sb, os);
+            os += popc32(smk);
             const uint32_t gA0 = spread6_at(T, ux, a0, o0);
             const uint32_t gB0 = spread6_at(T, ux, b0, o0);
             const uint32_t gS0 = spread6_at(T, ux, s0, o0);
             o0 += popc32(uk);
-            const uint32_t gS1 = spread6_at(T, sx, sb, os);
-            os += popc32(smk);
             // an entry holds the deposited bits in bit 0 and the mask in bit 2 of its nibbles
             const uint32_t ones = 0x01011111u;
             const uint32_t ta = lut3<0xE0>(ones, gA1, gA0), tb = lut3<0xE0>(ones, gB1, gB0), ts = lut3<0xE0>(ones, gS1, gS0);
             uint32_t v = (tb << 1) | ta;
             v = (ts << 3) | v;
-            v = (gA1 & 0x04044444u) | v;
+            v = (gA1 & f1keep) | v;
             w[k] = lut3<0xEA>(gA0, dkeep, v);
         }
     }

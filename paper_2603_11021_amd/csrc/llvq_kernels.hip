@@ -78,6 +78,18 @@ __device__ __forceinline__ float wave_sum_to_last(float v) {
 }
 
 
+// LDS atomics issued by one lane of a wave.  With an address the compiler can prove wave-uniform it first combines
+// the values of all active lanes (a scan over the exec mask, a dozen instructions) before one lane performs the
+// operation; here a single lane is active by construction, so the address is made to look lane-dependent and the
+// operation compiles to the one LDS instruction.
+__device__ __forceinline__ uint32_t lane_zero() {
+    uint32_t z = 0;
+    asm volatile("" : "+v"(z));
+    return z;
+}
+__device__ __forceinline__ void lds_add_one_lane(float* p, float v) { atomicAdd(p + lane_zero(), v); }
+__device__ __forceinline__ uint32_t lds_fetch_add_one_lane(uint32_t* p, uint32_t v) { return atomicAdd(p + lane_zero(), v); }
+
 template <int FMT>
 __device__ __forceinline__ uint64_t load_index(const void* __restrict__ idx, size_t k) {
     if constexpr (FMT == LLVQ_IDX_U64) {
@@ -211,7 +223,7 @@ struct BatchDeal {
     }
     // ask for the batch after `next` (its number arrives while this batch is decoded)
     __device__ __forceinline__ void take() {
-        if constexpr (DYNAMIC) { if (t == 0) taken = atomicAdd(next_free, 1u); }
+        if constexpr (DYNAMIC) { if (t == 0) taken = lds_fetch_add_one_lane(next_free, 1u); }
     }
     __device__ __forceinline__ void advance() {
         base = next;
@@ -491,7 +503,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 constexpr bool kMore = decltype(more_tag)::value;
                 if constexpr (kMore) {
                     fetch(next, nxt);
-                    if (DYNAMIC && lane == 0) taken = atomicAdd(next_free, 64u);      // the batch after that one
+                    if (DYNAMIC && lane == 0) taken = lds_fetch_add_one_lane(next_free, 64u);      // the batch after that one
                 }
                 u32x4 xq[1][3];
                 {
@@ -534,13 +546,13 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                         float p = cur.live ? acc * scale : 0.0f;
                         if (row_hi == row_lo) {                                  // the whole batch lies in one row
                             const float s_all = wave_sum_to_last(p);
-                            if (lane == 63) atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_all);
+                            if (lane == 63) lds_add_one_lane(&ysum[row_lo * kMaxMChunk + mi], s_all);
                         } else if (two_rows) {
                             const float p_lo = row == row_lo ? p : 0.0f;
                             const float s_lo = wave_sum_to_last(p_lo), s_hi = wave_sum_to_last(p - p_lo);
                             if (lane == 63) {
-                                atomicAdd(&ysum[row_lo * kMaxMChunk + mi], s_lo);
-                                atomicAdd(&ysum[row_hi * kMaxMChunk + mi], s_hi);
+                                lds_add_one_lane(&ysum[row_lo * kMaxMChunk + mi], s_lo);
+                                lds_add_one_lane(&ysum[row_hi * kMaxMChunk + mi], s_hi);
                             }
                         } else {
                             // general case: segmented suffix sum over lanes of equal row
