@@ -308,11 +308,18 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
         uint32_t zero = 0;
         keep_product(zero);
         uint32_t o0 = zero, os = zero, ou = zero;
+        // U in absolute positions, all four chunks first: their table reads depend on nothing the chunk loop computes,
+        // and issued together they cost one trip to LDS instead of one per chunk
+        uint32_t uks[4];
 #pragma unroll
         for (int k = 0; k < 4; k++) {
             const uint32_t omk = bfe6(om, 6 * k);
-            const uint32_t uk = tab_at<uint8_t, kOffPdep6>(T, omk * kPdepPitch + bfe6(U, ou));   // U in absolute positions
+            uks[k] = tab_at<uint8_t, kOffPdep6>(T, omk * kPdepPitch + bfe6(U, ou));
             ou += popc32(omk);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; k++) {
+            const uint32_t uk = uks[k];
             const uint32_t smk = bfe6(sm, 6 * k);
             uint32_t ux = uk * (4u * kSpreadPitch), sx = smk * (4u * kSpreadPitch);
             keep_product(sx); keep_product(ux);

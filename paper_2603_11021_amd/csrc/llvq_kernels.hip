@@ -392,6 +392,7 @@ struct MatItems {
     float* y[kMaxItems];
     int row_end[kMaxItems];        // rows of matrices 0..i together; entries past the last matrix repeat the total
     int tile_end[kMaxItems];       // the same in tiles of 32 rows, every matrix rounded up (mfma_kernel)
+    int tile16_end[kMaxItems];     // the same in tiles of 16 rows (tile_kernel)
 };
 
 template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC, bool MULTI = false>
@@ -808,6 +809,204 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
     }
 }
 
+// ---- llvq_matmul, batched decode (3 <= M <= 32): a row tile belongs to one workgroup, K is reduced inside it ------
+// A step = 16 weight rows x 4 neighbouring blocks of 24 input channels: lane l decodes block 4 s + l / 16 of row l % 16
+// of the tile.  The decoded block, scaled by gain / sqrt(16 m) and rounded to the activation type, is what
+// v_mfma_f32_16x16x32 expects from that lane as its B operand (k = 8 (l / 16) .. + 7 of column l % 16); the A operand
+// (16 tokens x the same channels) comes from global memory; three MFMAs consume the 24 channels of the four blocks.
+// A workgroup owns whole row tiles, so every channel of a row is seen inside it: the steps of up to kTilePassSlots
+// tiles (a pass) are dealt round-robin to the sixteen waves, each wave keeps the running 16 x 16 tile in its matrix-core
+// accumulators and, when it leaves a row tile, stores it into a slot of its own in LDS; after a barrier the slots of a
+// tile are added in a fixed order and y is written once with plain stores.  Nothing is cleared beforehand, nothing is
+// combined with atomics, and the result does not depend on timing.  Only the small tables are kept in LDS (the Golay
+// words and inner-word planes are read from global memory), which leaves 64 KB for the slots.
+// bf16 activations: the scaled weight is split into two bf16 terms (its bf16 rounding and the bf16 rounding of the
+// remainder, together 16 significant bits), six MFMAs per step: a single bf16 term (8 bits) would put 2^-9 per weight
+// into y.
+constexpr int kTileRows = 16;
+constexpr int kTilePassSlots = 4;               // 16 x 16 tiles a wave can park in LDS per pass: 4 row tiles x 1 token tile or 2 x 2
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+template <typename X2> struct Mma16;
+template <> struct Mma16<half2_t> {
+    static constexpr int kTerms = 1;
+    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[1]) { out[0] = Mma<half2_t>::scaled(fp8, hi, scale); }
+    // c += A B over 32 values of k: lane l holds k = 8 (l / 16) .. + 7 of row (A) or column (B) l % 16
+    static __device__ __forceinline__ float4_t mma(u32x4 a, u32x4 b, float4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma16<bf16x2_t> {
+    static constexpr int kTerms = 2;
+    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[2]) {
+        typedef float float2_t __attribute__((ext_vector_type(2)));
+        float2_t f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(fp8, true) : __builtin_amdgcn_cvt_pk_f32_fp8(fp8, false);
+        f *= scale;
+        const bf16x2_t top = __builtin_convertvector(f, bf16x2_t);                       // round to nearest even
+        const float2_t rest = f - __builtin_convertvector(top, float2_t);               // exact
+        out[0] = __builtin_bit_cast(uint32_t, top);
+        out[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
+    }
+    static __device__ __forceinline__ float4_t mma(u32x4 a, u32x4 b, float4_t c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+
+// TT: token tiles of 16 (M <= 16 TT); MULTI: the row tiles are those of up to four matrices that share x (`items`).
+template <int FMT, typename X2, int TT, bool MULTI = false>
+__global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                        const void* __restrict__ idx_in, const uint16_t* __restrict__ gain_in,
+                                                        const uint32_t* __restrict__ x, int M, int N_in, int KB, Code cd,
+                                                        int n_tiles, int tiles_per_wg, MatItems items, float* __restrict__ y_in) {
+    constexpr int kWaves = kThreads / 64;
+    constexpr int kPassTiles = kTilePassSlots / TT;                      // row tiles per pass
+    constexpr int kTerms = Mma16<X2>::kTerms;
+    load_tables(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
+    float* slots = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kWaves][kPassTiles][TT][256]
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int col = lane & 15, kgrp = lane >> 4;
+    const uint32_t S = ((uint32_t)KB + 3) / 4;                            // steps per row tile
+    const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
+    const int wg_t0 = blockIdx.x * tiles_per_wg, wg_t1 = min(n_tiles, wg_t0 + tiles_per_wg);
+    // activation rows of this lane as dword offsets, one per token tile (clamped: tokens past M are never stored)
+    uint32_t xoff[TT];
+#pragma unroll
+    for (int t = 0; t < TT; t++) xoff[t] = (uint32_t)min(M - 1, 16 * t + col) * (uint32_t)xpitch;
+
+    // the matrix a row tile belongs to and the tile's first row inside it (wave-uniform)
+    struct Mat { const void* idx; const uint16_t* gain; float* y; int N, row0; };
+    auto mat_of = [&](int tile) {
+        Mat m = {idx_in, gain_in, y_in, N_in, tile * kTileRows};
+        if constexpr (MULTI) {
+            int it = 0, first_tile = 0, first_row = 0;
+#pragma unroll
+            for (int i = 0; i + 1 < kMaxItems; i++) {
+                if (tile >= items.tile16_end[i]) { it = i + 1; first_tile = items.tile16_end[i]; first_row = items.row_end[i]; }
+            }
+            m.idx = items.idx[it]; m.gain = items.gain[it]; m.y = items.y[it];
+            m.N = items.row_end[it] - first_row;
+            m.row0 = (tile - first_tile) * kTileRows;
+        }
+        return m;
+    };
+
+    for (int pt0 = wg_t0; pt0 < wg_t1; pt0 += kPassTiles) {
+        const int np = min(kPassTiles, wg_t1 - pt0);
+        const uint32_t nsteps = (uint32_t)np * S;
+        // this wave's steps: e = wave, wave + 16, ...; step e is step e % S of pass tile e / S
+        uint32_t e = (uint32_t)wave, tl = e / S, st = e - tl * S;
+        float4_t acc[TT];
+#pragma unroll
+        for (int t = 0; t < TT; t++) acc[t] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+        struct Blk { RawBlock raw; bool live; };
+        auto fetch_blk = [&](uint32_t tile_local, uint32_t step, Blk& q) {
+            const Mat m = mat_of(pt0 + (int)tile_local);
+            const int row = m.row0 + col;
+            const uint32_t b = 4 * step + (uint32_t)kgrp;
+            q.live = row < m.N && b < (uint32_t)KB;
+            const size_t k = (size_t)min(row, m.N - 1) * KB + min(b, (uint32_t)KB - 1);
+            load_raw<FMT>(m.idx, m.gain, cd.gain_array(), k, q.raw);
+        };
+        auto front_of = [&](const Blk& q, bool& ok, uint16_t& gb) {
+            uint64_t I;
+            finish_block<FMT>(q.raw, cd, I, gb);
+            ok = q.live && I < T.npoints;
+            return llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
+        };
+        Blk cur_blk, nxt_blk;
+        llvq::Front F, Fn;
+        bool ok_cur = false, ok_nxt = false;
+        uint16_t g_cur = 0, g_nxt = 0;
+        if (e < nsteps) {
+            fetch_blk(tl, st, cur_blk);
+            F = front_of(cur_blk, ok_cur, g_cur);
+        }
+        // one step; kMore: another step of this wave follows in the pass (two copies of the code, so that each is
+        // straight-line with respect to its memory operations, as in matmul_kernel)
+        auto step = [&](auto more_tag, uint32_t tl_n, uint32_t st_n) {
+            constexpr bool kMore = decltype(more_tag)::value;
+            if constexpr (kMore) fetch_blk(tl_n, st_n, nxt_blk);
+            const uint32_t bx = min(4 * st + (uint32_t)kgrp, (uint32_t)KB - 1) * 12;
+            u32x4 xa[TT][3];
+#pragma unroll
+            for (int t = 0; t < TT; t++) {
+                const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
+                xa[t][0] = xp[0]; xa[t][1] = xp[1]; xa[t][2] = xp[2];
+            }
+            uint32_t w[4];
+            const llvq::BlockInfo bi = llvq::decode_back(T, F, w);
+            const float scale = ok_cur ? __half2float(__ushort_as_half(g_cur)) * bi.rnorm : 0.0f;
+            uint32_t wt[kTerms][12];
+#pragma unroll
+            for (int c = 0; c < 4; c++) {
+                uint32_t fe, fo, o[kTerms];
+                chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
+                Mma16<X2>::weights(fe, false, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 0] = o[r];
+                Mma16<X2>::weights(fo, false, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 1] = o[r];
+                Mma16<X2>::weights(fe, true, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
+            }
+            if constexpr (kMore) Fn = front_of(nxt_blk, ok_nxt, g_nxt);
+#pragma unroll
+            for (int j = 0; j < 3; j++) {
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) {
+                    const u32x4 bw = {wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]};
+#pragma unroll
+                    for (int t = 0; t < TT; t++) acc[t] = Mma16<X2>::mma(xa[t][j], bw, acc[t]);
+                }
+            }
+            // leaving this row tile (or the pass): park the accumulated tile in this wave's slot and start from zero
+            if (!kMore || tl_n != tl) {
+                float* dst = slots + ((size_t)(wave * kPassTiles + (int)tl) * TT) * 256 + lane * 4;
+#pragma unroll
+                for (int t = 0; t < TT; t++) {
+                    *reinterpret_cast<float4_t*>(dst + t * 256) = acc[t];
+                    acc[t] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+            }
+        };
+        while (e < nsteps) {
+            // the wave's next step (wave-uniform scalars)
+            const uint32_t e_n = e + kWaves;
+            uint32_t tl_n = tl, st_n = st + kWaves;
+            while (st_n >= S) { st_n -= S; tl_n++; }
+            if (e_n < nsteps) {
+                step(std::true_type{}, tl_n, st_n);
+                F = Fn; ok_cur = ok_nxt; g_cur = g_nxt;
+            } else {
+                step(std::false_type{}, tl_n, st_n);
+            }
+            e = e_n; tl = tl_n; st = st_n;
+        }
+        __syncthreads();
+        // tile tau of the pass got a partial tile from the waves (tau S + i) % 16, i < min(S, 16): added in that order.
+        // Thread r of a group of 256 writes token r / 16, weight row r % 16 (neighbouring threads, neighbouring addresses).
+        for (int u = threadIdx.x; u < np * TT * 256; u += kThreads) {
+            const int tau = u / (TT * 256), rem = u - tau * (TT * 256), t = rem >> 8, r = rem & 255;
+            const int tok_l = r >> 4, c = r & 15;
+            const int src = (((tok_l >> 2) << 4) + c) * 4 + (tok_l & 3);        // lane (4 (tok / 4) ... ) register tok % 4
+            const uint32_t first = (uint32_t)tau * S, cnt = min(S, (uint32_t)kWaves);
+            float sum = 0.0f;
+            for (uint32_t i = 0; i < cnt; i++) {
+                const int wv = (int)((first + i) & (kWaves - 1));
+                sum += slots[((size_t)(wv * kPassTiles + tau) * TT + t) * 256 + src];
+            }
+            const Mat m = mat_of(pt0 + tau);
+            const int row = m.row0 + c, tok = 16 * t + tok_l;
+            if (row < m.N && tok < M) m.y[(size_t)tok * m.N + row] = sum;
+        }
+        __syncthreads();
+    }
+}
+
 // ---- llvq_matmul, prefill kernel for large M: activations shared through LDS, no split along K -----------------
 // A workgroup of eight waves owns a strip of 256 weight rows (wave w: rows 32 w .. 32 w + 31 of the strip) and a pass of
 // 256 tokens, and walks all block pairs of the rows.  Per step the activation tile of the step (256 tokens x 48 channels)
@@ -1205,6 +1404,24 @@ static int launch_mfma_cfg(llvq_ctx* ctx, const void* d_x, int M, const void* d_
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "mfma matmul launch");
 }
 
+constexpr int kTileMaxM = 32;       // up to this many activation rows the batched-decode kernel with row tiles per workgroup is used
+
+template <int FMT, typename X2, int TT, bool MULTI = false>
+static int launch_tile(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st,
+                       const MatItems& items = MatItems{}) {
+    // persistent workgroups, whole row tiles split evenly among them
+    const int n_tiles = MULTI ? items.tile16_end[kMaxItems - 1] : (N + kTileRows - 1) / kTileRows;
+    int grid = std::min(ctx->num_cu, n_tiles);
+    const int per_wg = (n_tiles + grid - 1) / grid;
+    grid = (n_tiles + per_wg - 1) / per_wg;
+    const size_t lds = ctx->lay.lds_bytes + (size_t)(kThreads / 64) * kTilePassSlots * 256 * sizeof(float);
+    if (int rc = set_lds<tile_kernel<FMT, X2, TT, MULTI>>(ctx, lds)) return rc;
+    hipLaunchKernelGGL((tile_kernel<FMT, X2, TT, MULTI>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, n_tiles, per_wg, items, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "tile matmul launch");
+}
+
 template <int FMT>
 static int launch_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n, void* d_idx, hipStream_t st, size_t out_stride = 1) {
     const size_t lds = ctx->enc_lay.bytes + 16;        // + the batch counter
@@ -1282,6 +1499,8 @@ template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M > 64) return launch_prefill<FMT, X2, 8, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    if (M <= 16) return launch_tile<FMT, X2, 1>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    if (M <= kTileMaxM) return launch_tile<FMT, X2, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     const size_t ny = (size_t)M * N;
     hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
     return launch_mfma_cfg<FMT, X2, 1024, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
@@ -1391,10 +1610,11 @@ int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
         return LLVQ_OK;
     }
     MatItems items;
-    int rows = 0, tiles = 0;
+    int rows = 0, tiles = 0, tiles16 = 0;
     for (int i = 0; i < kMaxItems; i++) {
         const int k = i < n_items ? i : n_items - 1;
-        if (i < n_items) { rows += N[i]; tiles += (N[i] + 31) / 32; }
+        if (i < n_items) { rows += N[i]; tiles += (N[i] + 31) / 32; tiles16 += (N[i] + kTileRows - 1) / kTileRows; }
+        items.tile16_end[i] = tiles16;
         items.idx[i] = d_idx[k];
         items.gain[i] = reinterpret_cast<const uint16_t*>(d_gain[k]);
         items.y[i] = d_y[k];
@@ -1402,6 +1622,15 @@ int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
         items.tile_end[i] = tiles;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (M >= kMfmaMinM && M <= kTileMaxM) {
+        // row tiles of all matrices in one launch, each tile reduced inside its workgroup
+        if (x_dtype == LLVQ_F16) {
+            if (M <= 16) return LLVQ_BY_FMT(fmt, (launch_tile<F, half2_t, 1, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+            return LLVQ_BY_FMT(fmt, (launch_tile<F, half2_t, 2, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+        }
+        if (M <= 16) return LLVQ_BY_FMT(fmt, (launch_tile<F, bf16x2_t, 1, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+        return LLVQ_BY_FMT(fmt, (launch_tile<F, bf16x2_t, 2, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items)));
+    }
     if (M >= kMfmaMinM) {
         // the batched-decode kernel over the row tiles of all matrices; the outputs are cleared by one launch as well
         int widest = 0;
