@@ -626,8 +626,14 @@ __global__ void fill_multi_kernel(MatItems items, int M, float v) {
     if (tid < tail) p[head + 4 * n4 + tid] = v;
 }
 
+// Mma<X2>::weights turns a pair of fp8-coded coordinates into kTerms dwords of scaled weights in the activation type.
+// fp16: one term (11 significant bits).  bf16: two terms, the bf16 rounding of the fp32 product and the bf16 rounding of
+// what that leaves (16 significant bits together; one term alone would put 2^-9 per weight into y), each contracted by
+// its own MFMA against the same activations.
 template <typename X2> struct Mma;
 template <> struct Mma<half2_t> {
+    static constexpr int kTerms = 1;
+    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[1]) { out[0] = scaled(fp8, hi, scale); }
     static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
         const half2_t h = fp8x2_to_f16(fp8, hi);
         const _Float16 sh = (_Float16)scale;
@@ -640,12 +646,16 @@ template <> struct Mma<half2_t> {
     }
 };
 template <> struct Mma<bf16x2_t> {
-    static __device__ __forceinline__ uint32_t scaled(uint32_t fp8, bool hi, float scale) {
-        // fp8 pair -> fp32 pair, scale in fp32, round to nearest even with the hardware conversion
+    static constexpr int kTerms = 2;
+    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[2]) {
+        // fp8 pair -> fp32 pair, scale in fp32, round to nearest even with the hardware conversion; the remainder is exact
         typedef float float2_t __attribute__((ext_vector_type(2)));
         float2_t f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(fp8, true) : __builtin_amdgcn_cvt_pk_f32_fp8(fp8, false);
         f *= scale;
-        return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+        const bf16x2_t top = __builtin_convertvector(f, bf16x2_t);
+        const float2_t rest = f - __builtin_convertvector(top, float2_t);
+        out[0] = __builtin_bit_cast(uint32_t, top);
+        out[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
     }
     static __device__ __forceinline__ float16_t mma(u32x4 a, u32x4 b, float16_t c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
@@ -778,28 +788,41 @@ __global__ void __launch_bounds__(THREADS) mfma_kernel(const unsigned char* __re
             uint32_t w[4];
             const llvq::BlockInfo bi = llvq::decode_block(T, I, w);
             const float scale = ok ? g * bi.rnorm : 0.0f;
-            uint32_t wt[12];
+            constexpr int kTerms = Mma<X2>::kTerms;
+            uint32_t wt[kTerms][12];
 #pragma unroll
             for (int c = 0; c < 4; c++) {
-                uint32_t fe, fo;
+                uint32_t fe, fo, o[kTerms];
                 chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
-                wt[3 * c + 0] = Mma<X2>::scaled(fe, false, scale);
-                wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
-                wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
+                Mma<X2>::weights(fe, false, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 0] = o[r];
+                Mma<X2>::weights(fo, false, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 1] = o[r];
+                Mma<X2>::weights(fe, true, scale, o);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
             }
 #pragma unroll
             for (int t = 0; t < kTokTiles; t++) {
                 if (t < ntile) {
                     if constexpr (kTokTiles <= 2) {
 #pragma unroll
-                        for (int j = 0; j < 3; j++)
-                            acc[t] = Mma<X2>::mma(xa[t][j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
+                        for (int j = 0; j < 3; j++) {
+#pragma unroll
+                            for (int r = 0; r < kTerms; r++)
+                                acc[t] = Mma<X2>::mma(xa[t][j], u32x4{wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]}, acc[t]);
+                        }
                     } else {
                         const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
                         const u32x4 xl[3] = {xp[0], xp[1], xp[2]};
 #pragma unroll
-                        for (int j = 0; j < 3; j++)
-                            acc[t] = Mma<X2>::mma(xl[j], u32x4{wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]}, acc[t]);
+                        for (int j = 0; j < 3; j++) {
+#pragma unroll
+                            for (int r = 0; r < kTerms; r++)
+                                acc[t] = Mma<X2>::mma(xl[j], u32x4{wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]}, acc[t]);
+                        }
                     }
                 }
                 if (kTokTiles > 2 && (t & 1)) __builtin_amdgcn_sched_barrier(0);   // keep only two tiles of activations in flight
@@ -829,24 +852,12 @@ typedef float float4_t __attribute__((ext_vector_type(4)));
 
 template <typename X2> struct Mma16;
 template <> struct Mma16<half2_t> {
-    static constexpr int kTerms = 1;
-    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[1]) { out[0] = Mma<half2_t>::scaled(fp8, hi, scale); }
     // c += A B over 32 values of k: lane l holds k = 8 (l / 16) .. + 7 of row (A) or column (B) l % 16
     static __device__ __forceinline__ float4_t mma(u32x4 a, u32x4 b, float4_t c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, a), __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
     }
 };
 template <> struct Mma16<bf16x2_t> {
-    static constexpr int kTerms = 2;
-    static __device__ __forceinline__ void weights(uint32_t fp8, bool hi, float scale, uint32_t (&out)[2]) {
-        typedef float float2_t __attribute__((ext_vector_type(2)));
-        float2_t f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(fp8, true) : __builtin_amdgcn_cvt_pk_f32_fp8(fp8, false);
-        f *= scale;
-        const bf16x2_t top = __builtin_convertvector(f, bf16x2_t);                       // round to nearest even
-        const float2_t rest = f - __builtin_convertvector(top, float2_t);               // exact
-        out[0] = __builtin_bit_cast(uint32_t, top);
-        out[1] = __builtin_bit_cast(uint32_t, __builtin_convertvector(rest, bf16x2_t));
-    }
     static __device__ __forceinline__ float4_t mma(u32x4 a, u32x4 b, float4_t c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
     }
@@ -860,7 +871,7 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
                                                         int n_tiles, int tiles_per_wg, MatItems items, float* __restrict__ y_in) {
     constexpr int kWaves = kThreads / 64;
     constexpr int kPassTiles = kTilePassSlots / TT;                      // row tiles per pass
-    constexpr int kTerms = Mma16<X2>::kTerms;
+    constexpr int kTerms = Mma<X2>::kTerms;
     load_tables(blob, lay.lds_bytes);
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
     float* slots = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kWaves][kPassTiles][TT][256]
@@ -943,13 +954,13 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
             for (int c = 0; c < 4; c++) {
                 uint32_t fe, fo, o[kTerms];
                 chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
-                Mma16<X2>::weights(fe, false, scale, o);
+                Mma<X2>::weights(fe, false, scale, o);
 #pragma unroll
                 for (int r = 0; r < kTerms; r++) wt[r][3 * c + 0] = o[r];
-                Mma16<X2>::weights(fo, false, scale, o);
+                Mma<X2>::weights(fo, false, scale, o);
 #pragma unroll
                 for (int r = 0; r < kTerms; r++) wt[r][3 * c + 1] = o[r];
-                Mma16<X2>::weights(fe, true, scale, o);
+                Mma<X2>::weights(fe, true, scale, o);
 #pragma unroll
                 for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
             }
@@ -1098,14 +1109,21 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
         uint32_t w[4];
         const llvq::BlockInfo bi = llvq::decode_back(T, F, w);
         const float scale = ok_cur ? __half2float(__ushort_as_half(g_cur)) * bi.rnorm : 0.0f;
-        uint32_t wt[12];
+        constexpr int kTerms = Mma<X2>::kTerms;
+        uint32_t wt[kTerms][12];
 #pragma unroll
         for (int c = 0; c < 4; c++) {
-            uint32_t fe, fo;
+            uint32_t fe, fo, o[kTerms];
             chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
-            wt[3 * c + 0] = Mma<X2>::scaled(fe, false, scale);
-            wt[3 * c + 1] = Mma<X2>::scaled(fo, false, scale);
-            wt[3 * c + 2] = Mma<X2>::scaled(fe, true, scale);
+            Mma<X2>::weights(fe, false, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 0] = o[r];
+            Mma<X2>::weights(fo, false, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 1] = o[r];
+            Mma<X2>::weights(fe, true, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
         }
         Fn = front_of(nxt_blk, ok_nxt, g_nxt);
         // A operands from the staged tile: token 32 t + col, the lane half's block (48 bytes), k group j
@@ -1113,11 +1131,12 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
         // k group outermost: consecutive MFMAs go to different accumulators and do not wait for each other
 #pragma unroll
         for (int j = 0; j < 3; j++) {
-            const u32x4 bw = {wt[4 * j], wt[4 * j + 1], wt[4 * j + 2], wt[4 * j + 3]};
 #pragma unroll
             for (int t = 0; t < TT; t++) {
                 const u32x4 a = *reinterpret_cast<const u32x4*>(arow + (uint32_t)t * 32u * kATokenPitch + (uint32_t)j * 16u);
-                acc[t] = Mma<X2>::mma(a, bw, acc[t]);
+#pragma unroll
+                for (int r = 0; r < kTerms; r++)
+                    acc[t] = Mma<X2>::mma(a, u32x4{wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]}, acc[t]);
             }
         }
         stage_store((st + 1) & 1u, nextv);

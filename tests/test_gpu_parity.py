@@ -232,9 +232,10 @@ def _round_to(a, kind):
                                        # enough workgroups for the strip kernel (activations shared through LDS)
                                        ("gate", 1024, "bf16"), ("gate", 520, "f16"), ("down", 700, "bf16")])
 def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
-    """Config 4: the matrix-core path.  Weights enter the MFMA scaled and rounded to the activation type, so two
-    errors are checked: against the exact fp64 oracle (the 2e-3 bar) and against the oracle whose dequantised
-    weights are rounded to that type first, which isolates kernel mistakes from format rounding."""
+    """Config 4: the matrix-core path.  fp16: weights enter the MFMA scaled and rounded to fp16, so two errors are
+    checked: against the exact fp64 oracle (the 2e-3 bar) and against the oracle whose dequantised weights are rounded
+    to fp16 first, which isolates kernel mistakes from format rounding.  bf16: the weights enter as two bf16 terms
+    (16 significant bits), so the exact oracle is met to 1e-4."""
     import torch
     N, K = synth.LLAMA3_8B[name]
     x_dtype = "bf16" if xd == "bf16" else np.float16
@@ -249,13 +250,21 @@ def test_prefill_mfma_llama3_8b_shapes(gpu, oracle13, name, M, xd):
     ref2 = x.astype(np.float64) @ W.T
     err2 = np.abs(y[:, rows] - ref2).max() / np.abs(ref2).max()
     print("prefill %s M=%d %s: err vs exact %.2e, vs rounded-weight oracle %.2e" % (name, M, xd, err, err2))
-    assert err <= TOL, err
-    assert err2 <= 5e-4, err2
+    if xd == "bf16":
+        assert err <= 1e-4, err
+    else:
+        assert err <= TOL, err
+        assert err2 <= 5e-4, err2
 
 
 @pytest.mark.parametrize("N,K,M", [(33, 48, 3), (31, 24, 40), (100, 72, 65), (257, 24 * 7, 130), (64, 24 * 9, 300)])
-def test_mfma_ragged_shapes(gpu, oracle13, N, K, M):
-    _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M)
+@pytest.mark.parametrize("xd", ["f16", "bf16"])
+def test_mfma_ragged_shapes(gpu, oracle13, N, K, M, xd):
+    """every matrix-core kernel (row tiles, split-K tiles, strips) on short ragged rows, both activation types, against
+    the EXACT oracle: bf16 weights enter as two bf16 terms, so rows this short (1-9 blocks) need no averaging"""
+    err = _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M, x_dtype=np.float16 if xd == "f16" else "bf16")
+    if xd == "bf16":
+        assert err <= 1e-4, err
 
 
 @pytest.mark.parametrize("N,K,M", [(33, 48, 3), (17, 24, 16), (100, 72, 5), (257, 24 * 7, 12), (64, 24 * 9, 32), (1000, 999, 17)])
