@@ -67,6 +67,51 @@ def test_nearest_is_the_brute_force_optimum_on_shells_2_and_3(o3, metric):
     assert bad == 0
 
 
+def test_nearest_is_the_brute_force_optimum_on_shells_2_to_4():
+    """All 415,003,680 points of Lambda_24(4) (Table 1: 196,560 + 16,773,120 + 398,034,000), one pass for both metrics,
+    in slices dealt to the host cores.  Shell 4 is the first with a weight-16 class, classes of weight 0 that hold an
+    8, and supports carrying two different values (6 and 2), so this pass exercises the parity repair on a position
+    that is not interchangeable with the others, which shells 2 and 3 cannot."""
+    from concurrent.futures import ThreadPoolExecutor
+    o4 = Oracle(4)
+    assert o4.num_points == 415003680
+    rng = np.random.default_rng(54)
+    w = rng.standard_normal((16, 24))
+    w[0] = 0.0; w[0, 5] = 3.0                                    # one coordinate: the (8, 0^23) class
+    w[1] = 0.0; w[1, [2, 9, 17, 20]] = [1.0, -1.0, 1.0, 1.0]     # (4^4, 0^20)
+    w[2] = np.round(w[2])                                        # ties
+    w[3] = np.abs(w[3]) * np.where(np.arange(24) < 8, 3.0, 0.3)  # mass on eight coordinates: (6, 2^7, ...) candidates
+    w[4, :12] *= 4.0
+    inputs = {"angular": w, "euclidean": w * sqrt(56.0 / 24.0)}
+    w32 = {k: v.astype(np.float32) for k, v in inputs.items()}
+    step = 1 << 21
+    firsts = list(range(0, o4.num_points, step))
+
+    def slice_best(first):
+        n = min(step, o4.num_points - first)
+        pts, bad = o4.decode_range(first, n)
+        assert bad == 0
+        P = pts.astype(np.float32)
+        n2 = (P.astype(np.float64) ** 2).sum(axis=1)
+        ang = ((w32["angular"] @ P.T).astype(np.float64) / np.sqrt(n2)[None, :]).max(axis=1)
+        euc = ((w32["euclidean"] @ P.T).astype(np.float64) - 0.5 * n2[None, :]).max(axis=1)
+        return ang, euc
+
+    best = {k: np.full(16, -np.inf) for k in inputs}
+    with ThreadPoolExecutor(max(1, min(8, os.cpu_count() or 1))) as pool:
+        for ang, euc in pool.map(slice_best, firsts):
+            best["angular"] = np.maximum(best["angular"], ang)
+            best["euclidean"] = np.maximum(best["euclidean"], euc)
+    for metric, wm in inputs.items():
+        got, sc = o4.nearest(wm, metric)
+        assert np.allclose(sc, best[metric], rtol=2e-6, atol=2e-6)          # the brute force above runs in fp32
+        G = got.astype(np.float64)
+        mine = (wm * G).sum(axis=1) / np.sqrt((G ** 2).sum(axis=1)) if metric == "angular" else (wm * G).sum(axis=1) - 0.5 * (G ** 2).sum(axis=1)
+        assert np.allclose(mine, sc, rtol=1e-12, atol=1e-12)
+        _, bad = o4.encode(got)
+        assert bad == 0
+
+
 def test_a_lattice_point_is_its_own_nearest_direction(oracle13):
     """input = positive multiple of a point of the cut: cosine 1, answer on the same ray (v and 2v can both be in the cut)"""
     rng = np.random.default_rng(53)
