@@ -208,6 +208,32 @@ size_t llvq_gptq_workspace_bytes(int N);
 int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U,
                        void* d_idx, int fmt, void* d_gain, void* d_ws, size_t ws_bytes, void* stream);
 
+/* llvq_gptq_quantize with the optional scalar gain quantiser of paper App. B, Alg. 1 (the line "optionally: Q_gain"):
+ * the gain of a block is the nearest of the n_levels reconstruction levels d_gain_levels (DEVICE, fp16, ascending,
+ * 1 <= n_levels <= 4096; ties go to the lower level) instead of the rounded norm, and the error that is propagated
+ * includes that choice.  d_gain receives the chosen level of every block.  d_gain_levels == NULL: exactly
+ * llvq_gptq_quantize.  Everything else as for llvq_gptq_quantize.                                            */
+int llvq_gptq_quantize_levels(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U,
+                              void* d_idx, int fmt, void* d_gain, const void* d_gain_levels, int n_levels,
+                              void* d_ws, size_t ws_bytes, void* stream);
+
+/* Closed-form group scales after the block loop (paper App. J, algorithm "Spherically projected GPTQ with group
+ * scales", final per-row block-scale refinement in the Hessian metric): with the directions fixed, every row i gets the
+ * gains s_i = (M_i + lambda I)^-1 r_i, M_i[p][q] = Wq_{i,p} H_{pq} Wq_{i,q}^T, r_i[p] = Wq_{i,p} H_{p,:} W0_i^T, i.e. the
+ * minimiser of (W0_i - sum_p s_p Wq_{i,p}) H (...)^T + lambda |s|^2.
+ *   d_Wq  : [N][ldw] fp32, in: the quantised layer (as written by llvq_gptq_quantize), out: the refined layer
+ *   d_W0  : [N][ldw] fp32, the original weights;  d_H: [K][K] fp32, symmetric positive definite, K = 24*KB <= 24576
+ *   d_gain: [N][KB] fp16, in: the gains of the quantised layer, out: gain * s rounded to fp16; every block of d_Wq is
+ *           rescaled by exactly the ratio of the two fp16 gains, so that it stays what llvq_decode reconstructs
+ *   d_s   : [N][KB] fp32, written: the scales (NULL: not wanted);  lambda >= 0
+ *   d_ws  : workspace of at least llvq_gptq_group_scales_workspace_bytes(N, KB) bytes, 16-byte aligned
+ * Arithmetic in fp32 (dense products by library BLAS calls, one Cholesky factorisation per row in a kernel of this
+ * library); a row whose system is not positive definite in fp32 is left unchanged (s = 1).                      */
+size_t llvq_gptq_group_scales_workspace_bytes(int N, int KB);
+int llvq_gptq_group_scales(llvq_ctx* ctx, float* d_Wq, const float* d_W0, int N, int KB, size_t ldw,
+                           const float* d_H, float lambda, void* d_gain, float* d_s,
+                           void* d_ws, size_t ws_bytes, void* stream);
+
 /* Count indices that are not below N(m_max).  Synchronises the stream; *h_bad is a HOST pointer.  */
 int llvq_validate(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks,
                   uint64_t* h_bad, void* stream);

@@ -63,6 +63,9 @@ def _load():
     lib.llvq_quantize.argtypes = [vp, vp, sz, i32, vp, vp, i32, vp, vp]; lib.llvq_quantize.restype = i32
     lib.llvq_gptq_workspace_bytes.argtypes = [i32]; lib.llvq_gptq_workspace_bytes.restype = sz
     lib.llvq_gptq_quantize.argtypes = [vp, vp, i32, i32, sz, vp, vp, i32, vp, vp, sz, vp]; lib.llvq_gptq_quantize.restype = i32
+    lib.llvq_gptq_quantize_levels.argtypes = [vp, vp, i32, i32, sz, vp, vp, i32, vp, vp, i32, vp, sz, vp]; lib.llvq_gptq_quantize_levels.restype = i32
+    lib.llvq_gptq_group_scales_workspace_bytes.argtypes = [i32, i32]; lib.llvq_gptq_group_scales_workspace_bytes.restype = sz
+    lib.llvq_gptq_group_scales.argtypes = [vp, vp, vp, i32, i32, sz, vp, ctypes.c_float, vp, vp, vp, sz, vp]; lib.llvq_gptq_group_scales.restype = i32
     lib.llvq_validate.argtypes = [vp, vp, i32, sz, ctypes.POINTER(u64), vp]; lib.llvq_validate.restype = i32
     lib.llvq_validate_static.argtypes = [vp, vp, i32, sz, vp, vp]; lib.llvq_validate_static.restype = i32
     _lib = lib
@@ -289,7 +292,7 @@ class LLVQ:
                                             _stream_handle(stream)), "llvq_quantize")
         return pts, idx, score
 
-    def llvq_gptq_quantize(self, W, U, fmt=LLVQ_IDX_U48, stream=None):
+    def llvq_gptq_quantize(self, W, U, fmt=LLVQ_IDX_U48, gain_levels=None, stream=None):
         """W: float32 [N, 24*KB], overwritten with the quantised layer; U: float32 [K, K] upper factor of H^-1.
         Returns (indices [N, KB(, 6)], gains float16 [N, KB])."""
         import torch
@@ -301,10 +304,33 @@ class LLVQ:
                else torch.empty((N, KB), dtype=torch.int64, device=W.device))
         gain = torch.empty((N, KB), dtype=torch.float16, device=W.device)
         ws = torch.empty(int(self._lib.llvq_gptq_workspace_bytes(N)), dtype=torch.uint8, device=W.device)
-        self._check(self._lib.llvq_gptq_quantize(self._h, W.data_ptr(), N, KB, K, U.data_ptr(), idx.data_ptr(), fmt,
-                                                 gain.data_ptr(), ws.data_ptr(), ws.numel(), _stream_handle(stream)),
-                    "llvq_gptq_quantize")
+        if gain_levels is not None:
+            if gain_levels.dtype != torch.float16 or not gain_levels.is_contiguous():
+                raise LLVQError("gain_levels must be a contiguous float16 tensor (ascending levels)")
+            self._check(self._lib.llvq_gptq_quantize_levels(self._h, W.data_ptr(), N, KB, K, U.data_ptr(), idx.data_ptr(), fmt,
+                                                            gain.data_ptr(), gain_levels.data_ptr(), gain_levels.numel(), ws.data_ptr(),
+                                                            ws.numel(), _stream_handle(stream)), "llvq_gptq_quantize_levels")
+        else:
+            self._check(self._lib.llvq_gptq_quantize(self._h, W.data_ptr(), N, KB, K, U.data_ptr(), idx.data_ptr(), fmt,
+                                                     gain.data_ptr(), ws.data_ptr(), ws.numel(), _stream_handle(stream)),
+                        "llvq_gptq_quantize")
         return idx, gain
+
+    def llvq_gptq_group_scales(self, Wq, W0, H, gain, lam=0.0, stream=None):
+        """closed-form group scales in place on Wq and gain; returns the scales s [N, KB] (float32)"""
+        import torch
+        N, K = Wq.shape
+        if (Wq.dtype != torch.float32 or W0.dtype != torch.float32 or H.dtype != torch.float32 or gain.dtype != torch.float16 or K % 24
+                or tuple(W0.shape) != (N, K) or tuple(H.shape) != (K, K) or tuple(gain.shape) != (N, K // 24)
+                or not (Wq.is_contiguous() and W0.is_contiguous() and H.is_contiguous() and gain.is_contiguous())):
+            raise LLVQError("Wq, W0 contiguous float32 [N, 24*KB], H float32 [K, K], gain float16 [N, KB]")
+        KB = K // 24
+        s = torch.empty((N, KB), dtype=torch.float32, device=Wq.device)
+        ws = torch.empty(int(self._lib.llvq_gptq_group_scales_workspace_bytes(N, KB)), dtype=torch.uint8, device=Wq.device)
+        self._check(self._lib.llvq_gptq_group_scales(self._h, Wq.data_ptr(), W0.data_ptr(), N, KB, K, H.data_ptr(), float(lam),
+                                                     gain.data_ptr(), s.data_ptr(), ws.data_ptr(), ws.numel(), _stream_handle(stream)),
+                    "llvq_gptq_group_scales")
+        return s
 
     def llvq_validate(self, idx, stream=None):
         fmt, n = self._idx_fmt(idx)

@@ -1848,7 +1848,14 @@ size_t llvq_gptq_workspace_bytes(int N) { return N < 1 ? 0 : (size_t)N * (24 * s
 
 int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U, void* d_idx, int fmt,
                        void* d_gain, void* d_ws, size_t ws_bytes, void* stream) {
+    return llvq_gptq_quantize_levels(ctx, d_W, N, KB, ldw, d_U, d_idx, fmt, d_gain, nullptr, 0, d_ws, ws_bytes, stream);
+}
+
+int llvq_gptq_quantize_levels(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U, void* d_idx, int fmt,
+                              void* d_gain, const void* d_gain_levels, int n_levels, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx || !d_W || !d_U || !d_gain || !d_ws || N < 1 || KB < 1 || ldw < (size_t)24 * KB) return LLVQ_EINVAL;
+    if (d_gain_levels && (n_levels < 1 || n_levels > 4096)) return LLVQ_EINVAL;
+    if (!aligned(d_gain_levels, 2)) return LLVQ_EALIGN;
     if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
     if (ws_bytes < llvq_gptq_workspace_bytes(N)) return LLVQ_EINVAL;
     if (int rc = check_idx(d_idx, fmt)) return rc;
@@ -1870,7 +1877,7 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
                                            : launch_encode<LLVQ_IDX_U64>(ctx, d_pts, (size_t)N, idx_t, st, (size_t)KB);
         if (rc) return rc;
         hipLaunchKernelGGL(retract_kernel, dim3((N + 255) / 256), dim3(256), 0, st, Wq, ldw, d_pts, N, d_E,
-                           reinterpret_cast<uint16_t*>(d_gain) + t, (size_t)KB);
+                           reinterpret_cast<uint16_t*>(d_gain) + t, (size_t)KB, reinterpret_cast<const uint16_t*>(d_gain_levels), n_levels);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(ctx, e, "gptq step launch");
         const size_t r0 = (size_t)24 * (t + 1);
@@ -1883,6 +1890,59 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
             bs = rocblas_sgemm(ctx->blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)(K - r0), N, 24, &minus_one,
                                d_U + (size_t)24 * t * K + r0, (rocblas_int)K, d_E, 24, &one, d_W + r0, (rocblas_int)ldw);
         if (bs != rocblas_status_success) { ctx->set_error(std::string("rocblas: ") + rocblas_status_to_string(bs)); return LLVQ_EHIP; }
+    }
+    return LLVQ_OK;
+}
+
+// rows of a chunk of llvq_gptq_group_scales (one KB x KB system per row is held in the workspace)
+static int group_chunk_rows(int N) { return N < 128 ? N : 128; }
+
+size_t llvq_gptq_group_scales_workspace_bytes(int N, int KB) {
+    if (N < 1 || KB < 1) return 0;
+    const size_t K = (size_t)24 * KB, C = (size_t)group_chunk_rows(N);
+    return sizeof(float) * ((size_t)N * K + C * K + C * KB * KB + (size_t)N * KB) + 1024;
+}
+
+int llvq_gptq_group_scales(llvq_ctx* ctx, float* d_Wq, const float* d_W0, int N, int KB, size_t ldw, const float* d_H, float lambda,
+                           void* d_gain, float* d_s, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!ctx || !d_Wq || !d_W0 || !d_H || !d_gain || !d_ws || N < 1 || KB < 1 || KB > 1024 || ldw < (size_t)24 * KB) return LLVQ_EINVAL;
+    if (!(lambda >= 0.0f)) return LLVQ_EINVAL;
+    if (ws_bytes < llvq_gptq_group_scales_workspace_bytes(N, KB)) return LLVQ_EINVAL;
+    if (!aligned(d_Wq, 4) || !aligned(d_W0, 4) || !aligned(d_H, 4) || !aligned(d_gain, 2) || !aligned(d_s, 4) || !aligned(d_ws, 16)) return LLVQ_EALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!ctx->blas && rocblas_create_handle(&ctx->blas) != rocblas_status_success) { ctx->set_error("rocblas_create_handle failed"); return LLVQ_EHIP; }
+    if (rocblas_set_stream(ctx->blas, st) != rocblas_status_success) { ctx->set_error("rocblas_set_stream failed"); return LLVQ_EHIP; }
+    const size_t K = (size_t)24 * KB;
+    const int C = group_chunk_rows(N);
+    auto up = [](size_t v) { return (v + 63) & ~(size_t)63; };
+    float* d_T = reinterpret_cast<float*>(d_ws);                       // [N][K]  = W0 H
+    float* d_Z = d_T + up((size_t)N * K);                              // [C][K]  = Wq[rows, block p] H[block p, :]
+    float* d_M = d_Z + up((size_t)C * K);                              // [C][KB][KB]
+    float* d_r = d_M + up((size_t)C * KB * KB);                        // [N][KB]
+    const float one = 1.0f, zero = 0.0f;
+    // T = W0 H.  Row-major arrays seen column-major: T^T (K x N) = H (K x K, symmetric) * W0^T (K x N, leading dimension ldw)
+    rocblas_status bs = rocblas_sgemm(ctx->blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)K, N, (rocblas_int)K, &one,
+                                      d_H, (rocblas_int)K, d_W0, (rocblas_int)ldw, &zero, d_T, (rocblas_int)K);
+    if (bs != rocblas_status_success) { ctx->set_error(std::string("rocblas: ") + rocblas_status_to_string(bs)); return LLVQ_EHIP; }
+    {
+        const size_t n = (size_t)N * KB;
+        hipLaunchKernelGGL(group_rhs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_Wq, ldw, d_T, K, N, KB, d_r);
+    }
+    for (int row0 = 0; row0 < N; row0 += C) {
+        const int c = std::min(C, N - row0);
+        for (int p = 0; p < KB; p++) {
+            // Z^T (K x c) = H[block p, :]^T (K x 24) * Wq[rows, block p]^T (24 x c)
+            bs = rocblas_sgemm(ctx->blas, rocblas_operation_none, rocblas_operation_none, (rocblas_int)K, c, 24, &one,
+                               d_H + (size_t)24 * p * K, (rocblas_int)K, d_Wq + (size_t)row0 * ldw + (size_t)24 * p, (rocblas_int)ldw, &zero,
+                               d_Z, (rocblas_int)K);
+            if (bs != rocblas_status_success) { ctx->set_error(std::string("rocblas: ") + rocblas_status_to_string(bs)); return LLVQ_EHIP; }
+            const size_t n = (size_t)c * KB;
+            hipLaunchKernelGGL(group_gram_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, d_Wq, ldw, d_Z, K, row0, c, KB, p, d_M);
+        }
+        hipLaunchKernelGGL(group_solve_kernel, dim3(c), dim3(kGroupSolveThreads), 0, st, d_M, d_r, lambda, row0, c, KB, d_Wq, ldw,
+                           reinterpret_cast<uint16_t*>(d_gain), d_s);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(ctx, e, "group scales launch");
     }
     return LLVQ_OK;
 }

@@ -300,8 +300,11 @@ __global__ void __launch_bounds__(kMfmaSearchThreads, 4) search_mfma_kernel(cons
 // One step of the block-wise loop of paper App. B (Alg. 1): for every row the block v = W[row][0..23] has been
 // given its nearest direction x (pts); the block is replaced by g * x / ||x|| with g = ||v|| rounded to fp16 (the
 // norm-preserving "gain reset" of paper Sec. 3.3), and the error E = v - g x/||x|| is kept for the propagation.
+// levels != nullptr: the optional scalar gain quantiser of App. B Alg. 1 -- g is the nearest of n_levels fp16
+// reconstruction levels (ascending; ties go to the lower level) instead of the rounded norm.
 __global__ void retract_kernel(float* __restrict__ W, size_t ldw, const int8_t* __restrict__ pts, int N,
-                               float* __restrict__ E, uint16_t* __restrict__ gain, size_t gain_stride) {
+                               float* __restrict__ E, uint16_t* __restrict__ gain, size_t gain_stride,
+                               const uint16_t* __restrict__ levels, int n_levels) {
     const int row = blockIdx.x * blockDim.x + threadIdx.x;
     if (row >= N) return;
     float v[24], x[24], n2 = 0.0f, x2 = 0.0f;
@@ -312,7 +315,16 @@ __global__ void retract_kernel(float* __restrict__ W, size_t ldw, const int8_t* 
         n2 = fmaf(v[i], v[i], n2);
         x2 = fmaf(x[i], x[i], x2);
     }
-    const __half gh = __float2half_rn(sqrtf(n2));
+    const float norm = sqrtf(n2);
+    __half gh = __float2half_rn(norm);
+    if (levels) {
+        float best = INFINITY;
+        for (int k = 0; k < n_levels; k++) {
+            const __half lv = __ushort_as_half(levels[k]);
+            const float d = fabsf(norm - __half2float(lv));
+            if (d < best) { best = d; gh = lv; }
+        }
+    }
     const float scale = __half2float(gh) / sqrtf(x2);
 #pragma unroll
     for (int i = 0; i < 24; i++) {
@@ -321,6 +333,102 @@ __global__ void retract_kernel(float* __restrict__ W, size_t ldw, const int8_t* 
         E[(size_t)row * 24 + i] = v[i] - q;
     }
     gain[(size_t)row * gain_stride] = __half_as_ushort(gh);
+}
+
+// ---- closed-form group scales (paper App. J): per row, the Hessian-weighted least-squares gains of the fixed blocks ----
+// r[i][p] = sum over the channels a of block p of Wq[i][a] * T[i][a], T = W0 H
+__global__ void group_rhs_kernel(const float* __restrict__ Wq, size_t ldw, const float* __restrict__ T, size_t ldt, int N, int KB,
+                                 float* __restrict__ r) {
+    const size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= (size_t)N * KB) return;
+    const size_t i = u / KB, p = u - i * KB;
+    const float* a = Wq + i * ldw + 24 * p;
+    const float* t = T + i * ldt + 24 * p;
+    float acc = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 24; k++) acc = fmaf(a[k], t[k], acc);
+    r[u] = acc;
+}
+
+// M[c][p][q] = sum over the channels b of block q of Z[c][b] * Wq[row0 + c][b], Z = Wq[rows, block p] H[block p, :]
+__global__ void group_gram_kernel(const float* __restrict__ Wq, size_t ldw, const float* __restrict__ Z, size_t ldz, int row0, int C, int KB,
+                                  int p, float* __restrict__ Mm) {
+    const size_t u = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (u >= (size_t)C * KB) return;
+    const size_t c = u / KB, q = u - c * KB;
+    const float* a = Wq + (size_t)(row0 + c) * ldw + 24 * q;
+    const float* z = Z + c * ldz + 24 * q;
+    float acc = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 24; k++) acc = fmaf(z[k], a[k], acc);
+    Mm[(c * KB + (size_t)p) * KB + q] = acc;
+}
+
+// One workgroup per row: solves (M + lambda I) s = r by a Cholesky factorisation in place (lower triangle), then
+// rescales the row's blocks and gains.  A matrix that is not positive definite in fp32 leaves the row as it is (s = 1).
+constexpr int kGroupSolveThreads = 256;
+__global__ void __launch_bounds__(kGroupSolveThreads) group_solve_kernel(float* __restrict__ Mm, const float* __restrict__ r, float lambda,
+                                                                        int row0, int C, int KB, float* __restrict__ Wq, size_t ldw,
+                                                                        uint16_t* __restrict__ gain, float* __restrict__ s_out) {
+    const int c = blockIdx.x;
+    if (c >= C) return;
+    float* A = Mm + (size_t)c * KB * KB;
+    const float* b = r + (size_t)(row0 + c) * KB;
+    __shared__ float sol[1024];            // KB <= 1024 is checked by the host
+    __shared__ int failed;
+    const int tid = threadIdx.x;
+    if (tid == 0) failed = 0;
+    for (int i = tid; i < KB; i += kGroupSolveThreads) A[(size_t)i * KB + i] += lambda;
+    __syncthreads();
+    for (int j = 0; j < KB; j++) {
+        const float d = A[(size_t)j * KB + j];
+        if (!(d > 0.0f)) { if (tid == 0) failed = 1; break; }       // every thread reads the same value: uniform exit
+        const float inv = 1.0f / sqrtf(d);
+        __syncthreads();
+        for (int i = j + tid; i < KB; i += kGroupSolveThreads) A[(size_t)i * KB + j] *= inv;       // column j of L (diagonal: sqrt d)
+        __syncthreads();
+        // trailing update of the lower triangle: A[i][k] -= L[i][j] L[k][j], j < k <= i
+        const int n = KB - j - 1;
+        for (int u = tid; u < n * n; u += kGroupSolveThreads) {
+            const int i = j + 1 + u / n, k = j + 1 + u % n;
+            if (k <= i) A[(size_t)i * KB + k] -= A[(size_t)i * KB + j] * A[(size_t)k * KB + j];
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    if (!failed) {
+        // L z = b, then L^T s = z: short dependent chains, one thread
+        if (tid == 0) {
+            for (int i = 0; i < KB; i++) {
+                float acc = b[i];
+                for (int k = 0; k < i; k++) acc -= A[(size_t)i * KB + k] * sol[k];
+                sol[i] = acc / A[(size_t)i * KB + i];
+            }
+            for (int i = KB - 1; i >= 0; i--) {
+                float acc = sol[i];
+                for (int k = i + 1; k < KB; k++) acc -= A[(size_t)k * KB + i] * sol[k];
+                sol[i] = acc / A[(size_t)i * KB + i];
+            }
+        }
+    } else {
+        for (int i = tid; i < KB; i += kGroupSolveThreads) sol[i] = 1.0f;
+    }
+    __syncthreads();
+    // new gain = old gain * s rounded to fp16; the block is rescaled by the ratio of the two fp16 gains
+    const size_t row = (size_t)(row0 + c);
+    for (int u = tid; u < KB * 24; u += kGroupSolveThreads) {
+        const int p = u / 24;
+        const float g_old = __half2float(__ushort_as_half(gain[row * KB + p]));
+        const float g_new = __half2float(__float2half_rn(g_old * sol[p]));
+        const float ratio = g_old != 0.0f ? g_new / g_old : 0.0f;
+        Wq[row * ldw + u] *= ratio;
+    }
+    __syncthreads();
+    for (int p = tid; p < KB; p += kGroupSolveThreads) {
+        const float g_old = __half2float(__ushort_as_half(gain[row * KB + p]));
+        gain[row * KB + p] = __half_as_ushort(__float2half_rn(g_old * sol[p]));
+        if (s_out) s_out[row * KB + p] = sol[p];
+    }
 }
 
 }  // namespace

@@ -69,3 +69,57 @@ def test_gptq_argument_checks(gpu):
         gpu.llvq_gptq_quantize(W, torch.eye(24, dtype=torch.float32, device="cuda:0"))
     with pytest.raises(LLVQError):
         gpu.llvq_gptq_quantize(W.half(), torch.eye(48, dtype=torch.float32, device="cuda:0"))
+
+
+def test_gptq_loop_with_a_scalar_gain_quantiser(gpu, oracle13):
+    """App. B Alg. 1 with the optional Q_gain: every stored gain is one of the levels, the first block column (which
+    sees the original weights) takes exactly the oracle's levels, and the layer is what the decoder reconstructs"""
+    import torch
+    N, KB = 40, 3
+    W, H = _layer(901, N, KB, 40.0)
+    U = inverse_hessian_factor(H)
+    norms = np.linalg.norm(W.reshape(N, KB, 24), axis=2)
+    levels = np.quantile(norms, [0.125, 0.375, 0.625, 0.875]).astype(np.float16)
+    d_W = _dev(W.copy())
+    idx, gain = gpu.llvq_gptq_quantize(d_W, _dev(U.astype(np.float32)), LLVQ_IDX_U48, gain_levels=_dev(levels))
+    g = gain.cpu().numpy()
+    assert set(np.unique(g)) <= set(levels)
+    W_ref, pts_ref, gain_ref = spherical_gptq(oracle13, W.astype(np.float64), U, gain_levels=levels)
+    # norms far enough from a midpoint between levels cannot flip between fp32 and fp64
+    mid = (levels[1:].astype(np.float64) + levels[:-1].astype(np.float64)) / 2
+    safe = np.abs(norms[:, 0][:, None] - mid[None, :]).min(axis=1) > 1e-5
+    assert safe.sum() >= N - 3 and np.array_equal(g[safe, 0], gain_ref[safe, 0])
+    rec = gpu.llvq_decode(idx.reshape(-1), gain.reshape(-1), out_dtype=torch.float32).cpu().numpy().reshape(N, KB * 24)
+    assert np.allclose(rec, d_W.cpu().numpy(), rtol=1e-5, atol=1e-8)
+    lg, lr = proxy_loss(d_W.cpu().numpy().astype(np.float64), W, H), proxy_loss(W_ref, W, H)
+    assert abs(lg - lr) <= 0.05 * lr, (lg, lr)
+
+
+@pytest.mark.parametrize("N,KB,lam", [(16, 4, 0.0), (37, 7, 0.0), (140, 3, 0.25), (5, 12, 0.0)])
+def test_group_scales_match_the_oracle(gpu, oracle13, N, KB, lam):
+    """closed-form group scales (App. J) on the GPU's own quantised layer against the oracle's normal equations in fp64"""
+    import torch
+    from oracle.gptq_oracle import apply_group_scales, group_scales
+    W, H = _layer(950 + N, N, KB, 60.0)
+    U = inverse_hessian_factor(H)
+    d_Wq = _dev(W.copy())
+    idx, gain = gpu.llvq_gptq_quantize(d_Wq, _dev(U.astype(np.float32)), LLVQ_IDX_U48)
+    Wq = d_Wq.cpu().numpy().astype(np.float64)
+    g0 = gain.cpu().numpy().copy()
+    s = gpu.llvq_gptq_group_scales(d_Wq, _dev(W), _dev(H.astype(np.float32)), gain, lam=lam).cpu().numpy().astype(np.float64)
+    want = group_scales(W.astype(np.float64), Wq, H.astype(np.float32).astype(np.float64), lam=lam)
+    assert np.allclose(s, want, rtol=2e-3, atol=2e-4), np.abs(s - want).max()
+    # stored format: new gains are old gain * s in fp16 (the GPU's own s decides the rounding), and the layer written back is
+    # what the decoder reconstructs from the indices and the new gains
+    W_want, g_want = apply_group_scales(Wq, g0, s)
+    g1 = gain.cpu().numpy()
+    assert (np.abs(g1.astype(np.float64) - g_want.astype(np.float64)) <= 2 ** -10 * np.abs(g_want.astype(np.float64))).all()
+    rec = gpu.llvq_decode(idx.reshape(-1), gain.reshape(-1), out_dtype=torch.float32).cpu().numpy().reshape(N, KB * 24)
+    assert np.allclose(rec, d_Wq.cpu().numpy(), rtol=1e-5, atol=1e-8)
+    # the refinement lowers the local objective, to what the oracle's scales give
+    refined = d_Wq.cpu().numpy().astype(np.float64)
+    oracle_refined = Wq * np.repeat(want, 24, axis=1)
+    l0, l1, l_ref = proxy_loss(Wq, W, H), proxy_loss(refined, W, H), proxy_loss(oracle_refined, W, H)
+    if lam == 0.0:
+        assert l1 <= l0 * (1 + 1e-4)
+        assert abs(l1 - l_ref) <= 0.02 * l_ref + 1e-12, (l1, l_ref)
