@@ -47,7 +47,8 @@ enum {
 /* index storage formats */
 enum {
     LLVQ_IDX_U48 = 0,    /* 6 bytes per index, little endian, densely packed; 2-byte aligned base        */
-    LLVQ_IDX_U64 = 1,    /* one uint64 per index (upper 16 bits ignored); 8-byte aligned base            */
+    LLVQ_IDX_U64 = 1,    /* one uint64 per index (upper 16 bits ignored; upper 8 bits in contexts with
+                            m_max > 13); 8-byte aligned base                                             */
     LLVQ_IDX_U24 = 2     /* 3 bytes per word, little endian, densely packed; no alignment requirement: the
                             1 bit/weight layout of a single small shell (paper App. C, "single shell")      */
 };
@@ -65,7 +66,13 @@ enum {
     LLVQ_F32 = 2
 };
 
-/* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 13, on HIP device `device`.
+/* Create a context for the code Lambda_24(m_max), 2 <= m_max <= 19, on HIP device `device`.
+ * m_max <= 13 (indices below 2^48; 13 is the paper's 2 bits per weight) gets the full library.  14 <= m_max <= 19 (paper
+ * Table 1, row m = 19: 23,546,209,100,646,960 points, 55-bit indices) gets the dequantiser only: llvq_decode_i8,
+ * llvq_decode, llvq_matmul with M <= 16 (LLVQ_ENOTIMPL above), llvq_matmul_ws (same as llvq_matmul), llvq_validate,
+ * llvq_validate_static, llvq_num_points, llvq_num_classes and llvq_shell_offset, through a slower decoder that keeps
+ * its tables in global memory; every other call returns LLVQ_ENOTIMPL.  In these contexts a LLVQ_IDX_U64 word carries
+ * the index in its low 56 bits (upper 8 bits ignored), and llvq_matmul combines partial sums with fp32 atomic adds.
  * Builds the constant tables (Golay words, class records, ranking tables) on the host and copies
  * them to the device.  The tables are immutable afterwards; llvq_decode*, llvq_matmul, llvq_matmul_multi, llvq_matmul_coded, llvq_encode,
  * llvq_repack, llvq_quantize and llvq_shell_offset may be called on one context from several threads.  llvq_matmul_ws,
@@ -79,9 +86,9 @@ const char* llvq_strerror(int rc);
  * same context can fail.                                                                                   */
 const char* llvq_last_hip_error(const llvq_ctx* ctx);
 
-/* N(m_max) = |Lambda_24(m_max)| (paper Table 1): 280,974,212,784,720 for m_max = 13. */
+/* N(m_max) = |Lambda_24(m_max)| (paper Table 1): 280,974,212,784,720 for m_max = 13, 23,546,209,100,646,960 for 19. */
 uint64_t llvq_num_points(const llvq_ctx* ctx);
-/* number of classes over all shells (383 for m_max = 13) */
+/* number of classes over all shells (383 for m_max = 13, 1,457 for m_max = 19) */
 int llvq_num_classes(const llvq_ctx* ctx);
 
 /* Index of the first point of shell m, i.e. N(m-1) of paper Table 1 (0 for m <= 2, N(m_max) for m > m_max):

@@ -22,6 +22,7 @@
 #include "llvq_decode_core.h"
 #include "llvq_encode_core.h"
 #include "llvq_tables.h"
+#include "llvq_wide.h"
 
 namespace {
 
@@ -1202,10 +1203,10 @@ __global__ void repack_kernel(const void* __restrict__ idx, const uint16_t* __re
 
 // ---- llvq_validate ------------------------------------------------------------------------------------
 template <int FMT>
-__global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints, unsigned long long* __restrict__ bad) {
+__global__ void validate_kernel(const void* __restrict__ idx, size_t n, uint64_t index_mask, uint64_t npoints, unsigned long long* __restrict__ bad) {
     unsigned long long local = 0;
     for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
-        local += (load_index<FMT>(idx, k) & 0xFFFFFFFFFFFFull) >= npoints;
+        local += (load_index<FMT>(idx, k) & index_mask) >= npoints;
     for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
     if ((threadIdx.x & 63) == 0 && local) atomicAdd(bad, local);
 }
@@ -1219,12 +1220,12 @@ static __device__ __align__(256) unsigned int g_validate_scratch[kValidateStatic
 
 // every workgroup overwrites its own slot, so nothing has to be cleared between calls
 template <int FMT>
-__global__ void __launch_bounds__(kValidateStaticThreads) validate_partial_kernel(const void* __restrict__ idx, size_t n, uint64_t npoints,
-                                                                                  unsigned int* __restrict__ partial) {
+__global__ void __launch_bounds__(kValidateStaticThreads) validate_partial_kernel(const void* __restrict__ idx, size_t n, uint64_t index_mask,
+                                                                                  uint64_t npoints, unsigned int* __restrict__ partial) {
     __shared__ unsigned int wave_count[kValidateStaticThreads / 64];
     unsigned int local = 0;
     for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x)
-        local += (load_index<FMT>(idx, k) & 0xFFFFFFFFFFFFull) >= npoints;
+        local += (load_index<FMT>(idx, k) & index_mask) >= npoints;
     for (int off = 32; off > 0; off >>= 1) local += __shfl_down(local, off);
     if ((threadIdx.x & 63) == 0) wave_count[threadIdx.x >> 6] = local;
     __syncthreads();
@@ -1253,6 +1254,78 @@ __global__ void __launch_bounds__(kValidateStaticThreads) validate_sum_kernel(co
 
 }  // namespace
 
+// ---- contexts with m_max > 13: the dequantiser of llvq_wide.h, one thread per block ----------------------------------
+namespace {
+
+constexpr uint64_t kWideIndexMask = (1ull << 56) - 1;      // 64-bit words of these contexts carry the index in their low 56 bits
+
+template <int FMT>
+__device__ __forceinline__ uint64_t wide_index(const void* __restrict__ idx, size_t k) {
+    return load_index<FMT>(idx, k) & kWideIndexMask;
+}
+
+template <int FMT>
+__global__ void __launch_bounds__(256) wide_decode_i8_kernel(llvq::WidePtrs T, const void* __restrict__ idx, size_t n, uint2* __restrict__ out) {
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x) {
+        const uint64_t I = wide_index<FMT>(idx, k);
+        uint32_t o[6] = {0, 0, 0, 0, 0, 0};
+        float rnorm;
+        if (I < T.npoints) llvq::wide_decode(T, I, o, rnorm);
+        out[3 * k] = make_uint2(o[0], o[1]);
+        out[3 * k + 1] = make_uint2(o[2], o[3]);
+        out[3 * k + 2] = make_uint2(o[4], o[5]);
+    }
+}
+
+__device__ __forceinline__ float wide_coord(const uint32_t (&o)[6], int i) { return (float)(int8_t)(o[i >> 2] >> (8 * (i & 3))); }
+
+template <int FMT, int OUT>
+__global__ void __launch_bounds__(256) wide_dequant_kernel(llvq::WidePtrs T, const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                           size_t n, void* __restrict__ out) {
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x) {
+        const uint64_t I = wide_index<FMT>(idx, k);
+        uint32_t o[6] = {0, 0, 0, 0, 0, 0};
+        float rnorm = 0.0f;
+        if (I < T.npoints) llvq::wide_decode(T, I, o, rnorm);
+        const float scale = __half2float(__ushort_as_half(gain[k])) * rnorm;
+#pragma unroll
+        for (int i = 0; i < 24; i++) {
+            const float v = wide_coord(o, i) * scale;
+            if constexpr (OUT == LLVQ_F32) reinterpret_cast<float*>(out)[24 * k + i] = v;
+            else if constexpr (OUT == LLVQ_F16) reinterpret_cast<__half*>(out)[24 * k + i] = __float2half_rn(v);
+            else reinterpret_cast<__bf16*>(out)[24 * k + i] = (__bf16)v;
+        }
+    }
+}
+
+// y must be zero when this kernel starts: every block adds its M partial dot products to y with atomic adds
+template <int FMT, bool BF16>
+__global__ void __launch_bounds__(256) wide_matmul_kernel(llvq::WidePtrs T, const uint16_t* __restrict__ x, int M, const void* __restrict__ idx,
+                                                          const uint16_t* __restrict__ gain, int N, int KB, float* __restrict__ y) {
+    const size_t n = (size_t)N * KB;
+    for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < n; k += (size_t)gridDim.x * blockDim.x) {
+        const uint64_t I = wide_index<FMT>(idx, k);
+        if (I >= T.npoints) continue;                                   // the zero block contributes nothing
+        uint32_t o[6];
+        float rnorm;
+        llvq::wide_decode(T, I, o, rnorm);
+        const float scale = __half2float(__ushort_as_half(gain[k])) * rnorm;
+        const size_t row = k / KB, b = k - row * KB;
+        for (int m = 0; m < M; m++) {
+            const uint16_t* xp = x + ((size_t)m * KB + b) * 24;
+            float acc = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 24; i++) {
+                const float xv = BF16 ? __builtin_bit_cast(float, (uint32_t)xp[i] << 16) : __half2float(__ushort_as_half(xp[i]));
+                acc = fmaf(wide_coord(o, i), xv, acc);
+            }
+            atomicAdd(y + (size_t)m * N + row, acc * scale);
+        }
+    }
+}
+
+}  // namespace
+
 // ---- C ABI -------------------------------------------------------------------------------------------
 struct llvq_ctx {
     int device = 0;
@@ -1270,6 +1343,15 @@ struct llvq_ctx {
     float* d_tile_scale = nullptr;          // per-class factor and offset in accumulator order
     unsigned long long* d_counter = nullptr;
     unsigned int* d_validate_scratch = nullptr;   // address of g_validate_scratch on this context's device (not owned)
+    uint64_t index_mask = 0xFFFFFFFFFFFFull;      // bits of a stored word that hold the index (56 for 64-bit words of wide contexts)
+    // contexts with m_max > 13: the tables of llvq_wide.h in global memory; the table-driven kernels are not available
+    bool wide = false;
+    llvq::WideRec* d_wrecs = nullptr;
+    uint64_t* d_wcls_off = nullptr;
+    uint32_t* d_wgs = nullptr;
+    uint32_t* d_wbinom = nullptr;
+    uint64_t wide_shell_off[24] = {};
+    llvq::WidePtrs wide_ptrs() const { return llvq::WidePtrs{d_wrecs, d_wcls_off, d_wgs, d_wbinom, lay.ncls, lay.npoints}; }
     rocblas_handle blas = nullptr;          // created at the first llvq_matmul_ws call that takes the two-step path
     // text of the last failure: written under the lock (calls may fail on several threads at once), read without it
     std::mutex err_mu;
@@ -1476,13 +1558,13 @@ static int launch_search(llvq_ctx* ctx, int metric, const float* d_w, size_t ldw
 
 template <int FMT>
 static int launch_validate(llvq_ctx* ctx, int grid, const void* d_idx, size_t n, hipStream_t st) {
-    hipLaunchKernelGGL(validate_kernel<FMT>, dim3(grid), dim3(256), 0, st, d_idx, n, ctx->lay.npoints, ctx->d_counter);
+    hipLaunchKernelGGL(validate_kernel<FMT>, dim3(grid), dim3(256), 0, st, d_idx, n, ctx->index_mask, ctx->lay.npoints, ctx->d_counter);
     return 0;
 }
 
 template <int FMT>
-static int launch_validate_partial(int grid, const void* d_idx, size_t n, uint64_t npoints, unsigned int* partial, hipStream_t st) {
-    hipLaunchKernelGGL(validate_partial_kernel<FMT>, dim3(grid), dim3(kValidateStaticThreads), 0, st, d_idx, n, npoints, partial);
+static int launch_validate_partial(int grid, const void* d_idx, size_t n, uint64_t index_mask, uint64_t npoints, unsigned int* partial, hipStream_t st) {
+    hipLaunchKernelGGL(validate_partial_kernel<FMT>, dim3(grid), dim3(kValidateStaticThreads), 0, st, d_idx, n, index_mask, npoints, partial);
     return 0;
 }
 
@@ -1669,6 +1751,46 @@ bool plain_fmt(int fmt) { return fmt == LLVQ_IDX_U48 || fmt == LLVQ_IDX_U64 || f
 
 }  // namespace
 
+namespace {
+
+int wide_grid(const llvq_ctx* ctx, size_t n) { return (int)std::max<size_t>(1, std::min<size_t>((n + 255) / 256, (size_t)ctx->num_cu * 16)); }
+
+template <int FMT>
+int wide_launch_decode_i8(llvq_ctx* ctx, const void* d_idx, size_t n, int8_t* d_out, hipStream_t st) {
+    hipLaunchKernelGGL(wide_decode_i8_kernel<FMT>, dim3(wide_grid(ctx, n)), dim3(256), 0, st, ctx->wide_ptrs(), d_idx, n, reinterpret_cast<uint2*>(d_out));
+    return 0;
+}
+
+template <int FMT>
+int wide_launch_dequant(llvq_ctx* ctx, const void* d_idx, const void* d_gain, size_t n, void* d_out, int out_dtype, hipStream_t st) {
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
+    const dim3 grid(wide_grid(ctx, n));
+    if (out_dtype == LLVQ_F16) hipLaunchKernelGGL((wide_dequant_kernel<FMT, LLVQ_F16>), grid, dim3(256), 0, st, ctx->wide_ptrs(), d_idx, g, n, d_out);
+    else if (out_dtype == LLVQ_BF16) hipLaunchKernelGGL((wide_dequant_kernel<FMT, LLVQ_BF16>), grid, dim3(256), 0, st, ctx->wide_ptrs(), d_idx, g, n, d_out);
+    else hipLaunchKernelGGL((wide_dequant_kernel<FMT, LLVQ_F32>), grid, dim3(256), 0, st, ctx->wide_ptrs(), d_idx, g, n, d_out);
+    return 0;
+}
+
+template <int FMT>
+int wide_launch_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, const void* d_gain, int N, int KB, float* d_y, hipStream_t st) {
+    const size_t ny = (size_t)M * N, n = (size_t)N * KB;
+    hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+    const uint16_t* x = reinterpret_cast<const uint16_t*>(d_x);
+    const uint16_t* g = reinterpret_cast<const uint16_t*>(d_gain);
+    if (x_dtype == LLVQ_BF16) hipLaunchKernelGGL((wide_matmul_kernel<FMT, true>), dim3(wide_grid(ctx, n)), dim3(256), 0, st, ctx->wide_ptrs(), x, M, d_idx, g, N, KB, d_y);
+    else hipLaunchKernelGGL((wide_matmul_kernel<FMT, false>), dim3(wide_grid(ctx, n)), dim3(256), 0, st, ctx->wide_ptrs(), x, M, d_idx, g, N, KB, d_y);
+    return 0;
+}
+
+constexpr int kWideMaxBatch = 16;      // activation rows the wide contexts' product accepts
+
+int wide_finish(llvq_ctx* ctx, const char* what) {
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, what);
+}
+
+}  // namespace
+
 extern "C" {
 
 const char* llvq_strerror(int rc) {
@@ -1684,11 +1806,40 @@ const char* llvq_strerror(int rc) {
 
 const char* llvq_last_hip_error(const llvq_ctx* ctx) { return ctx ? ctx->err : ""; }
 
+// a context for 14 <= m_max <= 19: the tables of llvq_wide.h in global memory
+static int create_wide(llvq_ctx** out, int m_max, int device) {
+    llvq::WideTables tabs;
+    if (!llvq::build_wide_tables(m_max, tabs)) return LLVQ_EINVAL;
+    llvq_ctx* ctx = new (std::nothrow) llvq_ctx;
+    if (!ctx) return LLVQ_EINVAL;
+    ctx->device = device; ctx->m_max = m_max; ctx->wide = true;
+    ctx->lay = llvq::TableLayout{};
+    ctx->lay.ncls = tabs.lay.ncls; ctx->lay.npoints = tabs.lay.npoints;
+    ctx->index_mask = kWideIndexMask;
+    for (int m = 0; m < 24; m++) ctx->wide_shell_off[m] = tabs.shell_off[m];
+    hipDeviceProp_t prop;
+    auto upload = [&](auto** dst, const auto& v) {
+        const size_t bytes = v.size() * sizeof(v[0]);
+        return hipMalloc(reinterpret_cast<void**>(dst), bytes) == hipSuccess && hipMemcpy(*dst, v.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+    };
+    if (hipSetDevice(device) != hipSuccess || hipGetDeviceProperties(&prop, device) != hipSuccess ||
+        !upload(&ctx->d_wrecs, tabs.recs) || !upload(&ctx->d_wcls_off, tabs.cls_off) || !upload(&ctx->d_wgs, tabs.gs) ||
+        !upload(&ctx->d_wbinom, tabs.binom) || hipMalloc(&ctx->d_counter, sizeof(unsigned long long)) != hipSuccess ||
+        hipGetSymbolAddress(reinterpret_cast<void**>(&ctx->d_validate_scratch), HIP_SYMBOL(g_validate_scratch)) != hipSuccess) {
+        llvq_destroy(ctx);
+        return LLVQ_EHIP;
+    }
+    ctx->num_cu = prop.multiProcessorCount;
+    *out = ctx;
+    return LLVQ_OK;
+}
+
 int llvq_create(llvq_ctx** out, int m_max, int device) {
-    if (!out || m_max < 2 || m_max > 13 || device < 0) return LLVQ_EINVAL;
+    if (!out || m_max < 2 || m_max > llvq::kWideMaxM || device < 0) return LLVQ_EINVAL;
     *out = nullptr;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) return LLVQ_EHIP;
+    if (m_max > 13) return create_wide(out, m_max, device);
     llvq::Tables tabs;
     if (!llvq::build_tables(m_max, tabs)) return LLVQ_EINVAL;
     llvq_ctx* ctx = new (std::nothrow) llvq_ctx;
@@ -1747,6 +1898,10 @@ void llvq_destroy(llvq_ctx* ctx) {
     if (ctx->d_tile_a) (void)hipFree(ctx->d_tile_a);
     if (ctx->d_tile_scale) (void)hipFree(ctx->d_tile_scale);
     if (ctx->blas) (void)rocblas_destroy_handle(ctx->blas);
+    if (ctx->d_wrecs) (void)hipFree(ctx->d_wrecs);
+    if (ctx->d_wcls_off) (void)hipFree(ctx->d_wcls_off);
+    if (ctx->d_wgs) (void)hipFree(ctx->d_wgs);
+    if (ctx->d_wbinom) (void)hipFree(ctx->d_wbinom);
     delete ctx;
 }
 
@@ -1756,29 +1911,57 @@ int llvq_num_classes(const llvq_ctx* ctx) { return ctx ? (int)ctx->lay.ncls : 0;
 uint64_t llvq_shell_offset(const llvq_ctx* ctx, int m) {
     if (!ctx || m < 2) return 0;
     if (m > ctx->m_max) return ctx->lay.npoints;
-    return ctx->shell_off[m];
+    return ctx->wide ? ctx->wide_shell_off[m] : ctx->shell_off[m];
 }
+
 
 int llvq_decode_i8(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blocks, int8_t* d_out, void* stream) {
     if (!ctx || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    if (ctx->wide) {
+        if (n_blocks == 0) return LLVQ_OK;
+        if (!d_out) return LLVQ_EINVAL;
+        if (int rc = check_idx(d_idx, fmt)) return rc;
+        if (!aligned(d_out, 8)) return LLVQ_EALIGN;
+        LLVQ_BY_FMT(fmt, wide_launch_decode_i8<F>(ctx, d_idx, n_blocks, d_out, reinterpret_cast<hipStream_t>(stream)));
+        return wide_finish(ctx, "decode_i8 launch");
+    }
     return decode_i8_impl(ctx, d_idx, fmt, plain_code(fmt), n_blocks, d_out, stream);
 }
 
 int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks, void* d_out, int out_dtype, void* stream) {
     if (!ctx || !plain_fmt(fmt)) return LLVQ_EINVAL;
     if (n_blocks && !d_gain) return LLVQ_EINVAL;
+    if (ctx->wide) {
+        if (out_dtype != LLVQ_F16 && out_dtype != LLVQ_BF16 && out_dtype != LLVQ_F32) return LLVQ_EINVAL;
+        if (n_blocks == 0) return LLVQ_OK;
+        if (!d_out) return LLVQ_EINVAL;
+        if (int rc = check_idx(d_idx, fmt)) return rc;
+        if (!aligned(d_out, 16) || !aligned(d_gain, 2)) return LLVQ_EALIGN;
+        LLVQ_BY_FMT(fmt, wide_launch_dequant<F>(ctx, d_idx, d_gain, n_blocks, d_out, out_dtype, reinterpret_cast<hipStream_t>(stream)));
+        return wide_finish(ctx, "dequant launch");
+    }
     return decode_impl(ctx, d_idx, fmt, d_gain, plain_code(fmt), n_blocks, d_out, out_dtype, stream);
 }
 
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
                 int N, int KB, float* d_y, void* stream) {
     if (!ctx || !d_gain || !plain_fmt(fmt)) return LLVQ_EINVAL;
+    if (ctx->wide) {
+        if (!d_x || !d_y || M < 1 || N < 1 || KB < 1 || KB >= (1 << 24)) return LLVQ_EINVAL;
+        if (x_dtype != LLVQ_F16 && x_dtype != LLVQ_BF16) return LLVQ_EINVAL;
+        if (M > kWideMaxBatch) return LLVQ_ENOTIMPL;
+        if (int rc = check_idx(d_idx, fmt)) return rc;
+        if (!aligned(d_x, 16) || !aligned(d_gain, 2) || !aligned(d_y, 4)) return LLVQ_EALIGN;
+        LLVQ_BY_FMT(fmt, wide_launch_matmul<F>(ctx, d_x, x_dtype, M, d_idx, d_gain, N, KB, d_y, reinterpret_cast<hipStream_t>(stream)));
+        return wide_finish(ctx, "matmul launch");
+    }
     return matmul_impl(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, plain_code(fmt), N, KB, d_y, stream);
 }
 
 int llvq_matmul_multi(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_items, const void* const* d_idx, int fmt,
                       const void* const* d_gain, const int* N, int KB, float* const* d_y, void* stream) {
     if (!ctx) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (!plain_fmt(fmt)) return LLVQ_EINVAL;
     return matmul_multi_impl(ctx, d_x, x_dtype, M, n_items, d_idx, fmt, d_gain, N, KB, d_y, stream);
 }
@@ -1786,6 +1969,7 @@ int llvq_matmul_multi(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
 int llvq_decode_i8_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index, size_t n_blocks,
                          int8_t* d_out, void* stream) {
     if (!ctx) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, nullptr, cd)) return rc;
     return decode_i8_impl(ctx, d_idx, fmt, cd, n_blocks, d_out, stream);
@@ -1794,6 +1978,7 @@ int llvq_decode_i8_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bi
 int llvq_decode_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits, uint64_t base_index, const void* d_gain_lut,
                       const void* d_gain, size_t n_blocks, void* d_out, int out_dtype, void* stream) {
     if (!ctx) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
     cd.gain_in_word = !d_gain_lut && !d_gain && fmt == LLVQ_IDX_U64 && shape_bits == 48;     // the layout llvq_repack writes
@@ -1803,6 +1988,7 @@ int llvq_decode_coded(llvq_ctx* ctx, const void* d_idx, int fmt, int shape_bits,
 int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, int shape_bits,
                       uint64_t base_index, const void* d_gain_lut, const void* d_gain, int N, int KB, float* d_y, void* stream) {
     if (!ctx) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     Code cd;
     if (int rc = make_code(fmt, shape_bits, base_index, d_gain_lut, cd)) return rc;
     cd.gain_in_word = !d_gain_lut && !d_gain && fmt == LLVQ_IDX_U64 && shape_bits == 48;     // the layout llvq_repack writes
@@ -1811,6 +1997,7 @@ int llvq_matmul_coded(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const 
 
 int llvq_repack(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, size_t n_blocks, uint64_t* d_packed, void* stream) {
     if (!ctx || (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64)) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (n_blocks == 0) return LLVQ_OK;
     if (!d_gain || !d_packed) return LLVQ_EINVAL;
     if (int rc = check_idx(d_idx, fmt)) return rc;
@@ -1823,6 +2010,7 @@ int llvq_repack(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
 
 int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, int fmt, void* stream) {
     if (!ctx || (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64)) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (n_blocks == 0) return LLVQ_OK;
     if (!d_x) return LLVQ_EINVAL;
     if (int rc = check_idx(d_idx, fmt)) return rc;
@@ -1834,6 +2022,7 @@ int llvq_encode(llvq_ctx* ctx, const int8_t* d_x, size_t n_blocks, void* d_idx, 
 int llvq_quantize(llvq_ctx* ctx, const float* d_w, size_t n_blocks, int metric, int8_t* d_points, void* d_idx, int fmt,
                   float* d_score, void* stream) {
     if (!ctx || (metric != LLVQ_ANGULAR && metric != LLVQ_EUCLIDEAN)) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (d_idx && fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
     if (n_blocks == 0) return LLVQ_OK;
     if (!d_w || !d_points) return LLVQ_EINVAL;
@@ -1854,6 +2043,7 @@ int llvq_gptq_quantize(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, con
 int llvq_gptq_quantize_levels(llvq_ctx* ctx, float* d_W, int N, int KB, size_t ldw, const float* d_U, void* d_idx, int fmt,
                               void* d_gain, const void* d_gain_levels, int n_levels, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx || !d_W || !d_U || !d_gain || !d_ws || N < 1 || KB < 1 || ldw < (size_t)24 * KB) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (d_gain_levels && (n_levels < 1 || n_levels > 4096)) return LLVQ_EINVAL;
     if (!aligned(d_gain_levels, 2)) return LLVQ_EALIGN;
     if (fmt != LLVQ_IDX_U48 && fmt != LLVQ_IDX_U64) return LLVQ_EINVAL;
@@ -1906,6 +2096,7 @@ size_t llvq_gptq_group_scales_workspace_bytes(int N, int KB) {
 int llvq_gptq_group_scales(llvq_ctx* ctx, float* d_Wq, const float* d_W0, int N, int KB, size_t ldw, const float* d_H, float lambda,
                            void* d_gain, float* d_s, void* d_ws, size_t ws_bytes, void* stream) {
     if (!ctx || !d_Wq || !d_W0 || !d_H || !d_gain || !d_ws || N < 1 || KB < 1 || KB > 1024 || ldw < (size_t)24 * KB) return LLVQ_EINVAL;
+    if (ctx->wide) return LLVQ_ENOTIMPL;
     if (!(lambda >= 0.0f)) return LLVQ_EINVAL;
     if (ws_bytes < llvq_gptq_group_scales_workspace_bytes(N, KB)) return LLVQ_EINVAL;
     if (!aligned(d_Wq, 4) || !aligned(d_W0, 4) || !aligned(d_H, 4) || !aligned(d_gain, 2) || !aligned(d_s, 4) || !aligned(d_ws, 16)) return LLVQ_EALIGN;
@@ -1949,6 +2140,7 @@ int llvq_gptq_group_scales(llvq_ctx* ctx, float* d_Wq, const float* d_W0, int N,
 
 int llvq_matmul_ws(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, const void* d_idx, int fmt, const void* d_gain,
                    int N, int KB, float* d_y, void* d_ws, size_t ws_bytes, void* stream) {
+    if (ctx && ctx->wide) return llvq_matmul(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, N, KB, d_y, stream);
     const size_t need = (size_t)N * (size_t)KB * 24 * 2;
     if (!ctx || !d_ws || ws_bytes < need || M < kGemmMinM)
         return llvq_matmul(ctx, d_x, x_dtype, M, d_idx, fmt, d_gain, N, KB, d_y, stream);
@@ -2004,7 +2196,7 @@ int llvq_validate_static(llvq_ctx* ctx, const void* d_idx, int fmt, size_t n_blo
     if (n_blocks) {
         const size_t wgs = (n_blocks + kValidateStaticThreads - 1) / kValidateStaticThreads;
         grid = (int)std::min<size_t>(wgs, (size_t)std::min(kValidateStaticMaxWg, 4 * ctx->num_cu));
-        LLVQ_BY_FMT(fmt, launch_validate_partial<F>(grid, d_idx, n_blocks, ctx->lay.npoints, ctx->d_validate_scratch, st));
+        LLVQ_BY_FMT(fmt, launch_validate_partial<F>(grid, d_idx, n_blocks, ctx->index_mask, ctx->lay.npoints, ctx->d_validate_scratch, st));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(ctx, e, "validate_static launch");
     }

@@ -10,6 +10,7 @@
 // The orders the paper leaves free (class order, word order, sign-bit order, ranking of placements)
 // are those of this library's index format; they are restated where each table is built.
 #include "llvq_tables.h"
+#include "llvq_wide.h"
 
 #include <algorithm>
 #include <cmath>
@@ -105,14 +106,16 @@ uint32_t append(std::vector<unsigned char>& blob, const std::vector<T>& v) {
     return off;
 }
 
-}  // namespace
 
-bool build_tables(int m_max, Tables& out) {
-    if (m_max < 2 || m_max > 13) return false;
+
+// The 4096 Golay words in (weight, message) order and every class of shells 2..m_max in index order (paper Sec. 2.3-2.5,
+// 3.2): shell_off[m] receives N(m-1) for m <= m_max, `total` N(m_max).
+bool enumerate_leaders(int m_max, std::vector<uint32_t>& gs, int (&woff)[25], std::vector<Leader>& cls, uint64_t* shell_off,
+                       uint64_t& total) {
     init_binom();
-
     // ---- Golay words ----------------------------------------------------------------------------
-    std::vector<uint32_t> word(4096), gs;
+    std::vector<uint32_t> word(4096);
+    gs.clear();
     const uint32_t gen = 0xC75;
     for (uint32_t u = 0; u < 4096; u++) {
         uint32_t c = 0;
@@ -120,7 +123,6 @@ bool build_tables(int m_max, Tables& out) {
         if (popcnt(c) & 1) c |= 1u << 23;
         word[u] = c;
     }
-    int woff[25];
     for (int wt = 0; wt <= 24; wt++) {
         woff[wt] = (int)gs.size();
         for (uint32_t u = 0; u < 4096; u++) if (popcnt(word[u]) == wt) gs.push_back(word[u]);
@@ -128,11 +130,10 @@ bool build_tables(int m_max, Tables& out) {
     if (gs.size() != 4096 || woff[8] != 1 || woff[12] != 760 || woff[16] != 3336 || woff[24] != 4095) return false;
 
     // ---- classes ----------------------------------------------------------------------------------
-    std::vector<Leader> cls;
+    cls.clear();
     uint64_t running = 0;
-    for (int m = 0; m < 16; m++) out.shell_off[m] = 0;
     for (int m = 2; m <= m_max; m++) {
-        out.shell_off[m] = running;
+        shell_off[m] = running;
         std::vector<Leader> shell;
         int vmax = (int)std::floor(std::sqrt(16.0 * m) + 1e-9);
         for (int odd = 0; odd < 2; odd++) {
@@ -166,9 +167,110 @@ bool build_tables(int m_max, Tables& out) {
         std::sort(shell.begin(), shell.end(), leader_less);
         for (Leader& L : shell) { L.offset = running; running += L.size; cls.push_back(L); }
     }
+    total = running;
+    return true;
+}
+
+// How a class lays its values out (shared by the two decoders' table builders): the values that go through the Golay
+// word directly, the outer domain's outside value and minority values, and the parity that condition (iii) forces on
+// the number of negative F1 coordinates.
+struct ClassShape {
+    bool f1direct, outer_all;
+    std::vector<int> mv, mc, dv, dc;     // minority values / direct F1 values, descending, with multiplicities
+    int outside, n, q, kappa;
+};
+
+ClassShape shape_of(const Leader& L) {
+    ClassShape S;
+    S.f1direct = !L.odd && L.w > 0 && L.w <= 16;
+    S.outer_all = L.odd || L.w == 24;
+    std::vector<int> ov, oc;
+    for (size_t i = 0; i < L.val.size(); i++) {
+        bool isF1 = !L.odd && (L.val[i] % 4 == 2);
+        if (S.f1direct && isF1) { S.dv.push_back(L.val[i]); S.dc.push_back(L.cnt[i]); }
+        else { ov.push_back(L.val[i]); oc.push_back(L.cnt[i]); }
+    }
+    S.n = 0;
+    for (int c : oc) S.n += c;
+    // outside value: 0 for the F0 domain of even classes (whether present or not), otherwise the most
+    // frequent value, ties towards the smaller value
+    S.outside = 0;
+    if (S.outer_all) {
+        size_t best = 0;
+        for (size_t i = 0; i < ov.size(); i++)
+            if (oc[i] > oc[best] || (oc[i] == oc[best] && ov[i] < ov[best])) best = i;
+        S.outside = ov[best];
+    }
+    for (size_t i = 0; i < ov.size(); i++) if (ov[i] != S.outside) { S.mv.push_back(ov[i]); S.mc.push_back(oc[i]); }
+    S.q = 0;
+    for (int c : S.mc) S.q += c;
+    // parity of the number of negative signs on F1 (condition (iii) of L_even): with a = 4y on F0 and
+    // a = 2 + 4u on F1, sum x = 4 (sum y + sum u + #negative F1) (mod 8) because 2w = 0 (mod 8).
+    S.kappa = 0;
+    if (!L.odd) for (size_t i = 0; i < L.val.size(); i++) {
+        int t = (L.val[i] % 4 == 2) ? (L.val[i] - 2) / 4 : L.val[i] / 4;
+        S.kappa ^= (t * L.cnt[i]) & 1;
+    }
+    return S;
+}
+
+}  // namespace
+
+bool build_wide_tables(int m_max, WideTables& out) {
+    if (m_max < 2 || m_max > kWideMaxM) return false;
+    std::vector<Leader> cls;
+    int woff[25];
+    uint64_t total = 0;
+    for (int m = 0; m < 24; m++) out.shell_off[m] = 0;
+    if (!enumerate_leaders(m_max, out.gs, woff, cls, out.shell_off, total)) return false;
+    for (int m = m_max + 1; m < 24; m++) out.shell_off[m] = total;
+    if (total >= (1ull << 56)) return false;
+    out.lay.ncls = (uint32_t)cls.size();
+    out.lay.m_max = (uint32_t)m_max;
+    out.lay.npoints = total;
+    out.binom.assign(25 * 25, 0);
+    for (int n = 0; n <= 24; n++)
+        for (int k = 0; k <= 24; k++) {
+            if (g_binom[n][k] > 0xFFFFFFFFull) return false;
+            out.binom[n * 25 + k] = (uint32_t)g_binom[n][k];
+        }
+    out.recs.assign(cls.size(), WideRec{});
+    out.cls_off.assign(cls.size() + 1, total);
+    for (size_t ci = 0; ci < cls.size(); ci++) {
+        const Leader& L = cls[ci];
+        const ClassShape S = shape_of(L);
+        WideRec R{};
+        out.cls_off[ci] = L.offset;
+        if (S.mv.size() > (size_t)kWideMaxMinor || S.dv.size() > (size_t)kWideMaxDirect) return false;
+        const uint64_t Pin = multinomial(S.mc), P1 = S.f1direct ? multinomial(S.dc) : 1;
+        if (g_binom[S.n][S.q] * Pin * P1 != L.P1 * L.P0 || P1 > 0xFFFFFFFFull) return false;     // consistency with the class cardinality
+        R.Pin = Pin; R.P1 = (uint32_t)P1; R.A = (uint32_t)L.A;
+        R.rnorm = (float)(1.0 / std::sqrt(16.0 * L.m));
+        R.goff = (uint16_t)(L.odd ? 0 : woff[L.w]);
+        R.B = (uint8_t)L.B; R.w = (uint8_t)L.w; R.m = (uint8_t)L.m; R.n = (uint8_t)S.n; R.q = (uint8_t)S.q;
+        R.flags = (uint8_t)((L.odd ? WF_ODD : 0) | (S.f1direct ? WF_F1DIRECT : 0) | (S.outer_all ? WF_OUTER_ALL : 0) |
+                            ((!L.odd && L.w > 0) ? WF_FEN : 0) | (S.kappa ? WF_KAPPA : 0));
+        R.nm = (uint8_t)S.mv.size(); R.nd = (uint8_t)S.dv.size();
+        // odd classes: the sign a coordinate takes where the Golay word has a 0 (+a for a = 1 mod 4, -a for a = 3 mod 4)
+        auto signed_value = [&](int a) { return (int8_t)((L.odd && a % 4 == 3) ? -a : a); };
+        R.outside = signed_value(S.outside);
+        for (size_t i = 0; i < S.mv.size(); i++) { R.mv[i] = signed_value(S.mv[i]); R.mc[i] = (uint8_t)S.mc[i]; }
+        for (size_t i = 0; i < S.dv.size(); i++) { R.dv[i] = (int8_t)S.dv[i]; R.dc[i] = (uint8_t)S.dc[i]; }
+        out.recs[ci] = R;
+    }
+    return true;
+}
+
+bool build_tables(int m_max, Tables& out) {
+    if (m_max < 2 || m_max > 13) return false;
+    std::vector<uint32_t> gs;
+    int woff[25];
+    std::vector<Leader> cls;
+    uint64_t running = 0, shell_off[24] = {};
+    if (!enumerate_leaders(m_max, gs, woff, cls, shell_off, running)) return false;
+    for (int m = 0; m < 16; m++) out.shell_off[m] = m <= m_max ? shell_off[m] : running;
     const uint32_t ncls = (uint32_t)cls.size();
     if (running >= (1ull << 48)) return false;
-    for (int m = m_max + 1; m < 16; m++) out.shell_off[m] = running;
 
     // ---- lut12: colex rank -> mask, grouped by popcount ---------------------------------------------
     std::vector<uint16_t> lut12;
@@ -277,30 +379,10 @@ bool build_tables(int m_max, Tables& out) {
         const Leader& L = cls[ci];
         ClassRec R{};
         cls_off[ci] = L.offset;
-        bool f1direct = !L.odd && L.w > 0 && L.w <= 16;
-        bool outer_all = L.odd || L.w == 24;
-        // values of the outer domain and of the direct F1 word
-        std::vector<int> ov, oc, dv, dc;
-        for (size_t i = 0; i < L.val.size(); i++) {
-            bool isF1 = !L.odd && (L.val[i] % 4 == 2);
-            if (f1direct && isF1) { dv.push_back(L.val[i]); dc.push_back(L.cnt[i]); }
-            else { ov.push_back(L.val[i]); oc.push_back(L.cnt[i]); }
-        }
-        int n = 0;
-        for (int c : oc) n += c;
-        // outside value: 0 for the F0 domain of even classes (whether present or not), otherwise the most
-        // frequent value, ties towards the smaller value
-        int outside = 0;
-        if (outer_all) {
-            size_t best = 0;
-            for (size_t i = 0; i < ov.size(); i++)
-                if (oc[i] > oc[best] || (oc[i] == oc[best] && ov[i] < ov[best])) best = i;
-            outside = ov[best];
-        }
-        std::vector<int> mv, mc;    // minority values, descending
-        for (size_t i = 0; i < ov.size(); i++) if (ov[i] != outside) { mv.push_back(ov[i]); mc.push_back(oc[i]); }
-        int q = 0;
-        for (int c : mc) q += c;
+        const ClassShape S = shape_of(L);
+        const bool f1direct = S.f1direct, outer_all = S.outer_all;
+        const std::vector<int>&mv = S.mv, &mc = S.mc, &dv = S.dv, &dc = S.dc;
+        const int n = S.n, q = S.q, outside = S.outside;
         uint64_t Pin = multinomial(mc);
         uint64_t P1 = f1direct ? multinomial(dc) : 1;
         // consistency with the class cardinality
@@ -319,13 +401,7 @@ bool build_tables(int m_max, Tables& out) {
         while ((double)i1 * (double)P1 < 1.0) i1 = std::nextafterf(i1, 2.0f);
         R.invP1 = i1;
         R.P1 = (uint16_t)P1; R.tb0 = (uint16_t)tb0; R.tb1 = (uint16_t)tb1; R.sp = si.sp;
-        // parity of the number of negative signs on F1 (condition (iii) of L_even): with a = 4y on F0 and
-        // a = 2 + 4u on F1, sum x = 4 (sum y + sum u + #negative F1) (mod 8) because 2w = 0 (mod 8).
-        int kappa = 0;
-        if (!L.odd) for (size_t i = 0; i < L.val.size(); i++) {
-            int t = (L.val[i] % 4 == 2) ? (L.val[i] - 2) / 4 : L.val[i] / 4;
-            kappa ^= (t * L.cnt[i]) & 1;
-        }
+        const int kappa = S.kappa;
         int acode = L.A == 1 ? 0 : (L.A == 759 ? 1 : (L.A == 2576 ? 2 : 3));
         int wm1 = (!L.odd && L.w > 0) ? L.w - 1 : 0;
         R.f0 = (uint32_t)(L.odd ? 1 : 0) << F0_ODD | (uint32_t)(f1direct ? 1 : 0) << F0_F1DIRECT |

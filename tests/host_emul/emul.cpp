@@ -7,6 +7,7 @@
 #include "../../paper_2603_11021_amd/csrc/llvq_decode_core.h"
 #include "../../paper_2603_11021_amd/csrc/llvq_encode_core.h"
 #include "../../paper_2603_11021_amd/csrc/llvq_tables.h"
+#include "../../paper_2603_11021_amd/csrc/llvq_wide.h"
 
 static llvq::Tables g_tabs;
 static bool g_ok = false;
@@ -48,6 +49,27 @@ uint64_t emul_encode(const int8_t* pts, uint64_t n, uint64_t* idx) {
         std::memcpy(x, pts + 24 * k, 24);
         idx[k] = llvq::encode_block(T, x);
         bad += idx[k] == llvq::kInvalidIndex;
+    }
+    return bad;
+}
+
+// ---- the decoder of the larger unions (m_max up to 19) ------------------------------------------------------
+static llvq::WideTables g_wide;
+
+int emul_wide_init(int m_max) { return llvq::build_wide_tables(m_max, g_wide) ? 0 : -1; }
+uint32_t emul_wide_num_classes() { return g_wide.lay.ncls; }
+uint64_t emul_wide_num_points() { return g_wide.lay.npoints; }
+uint64_t emul_wide_shell_offset(int m) { return (m >= 0 && m < 24) ? g_wide.shell_off[m] : 0; }
+
+uint64_t emul_wide_decode_i8(const uint64_t* idx, uint64_t n, int8_t* out) {
+    llvq::WidePtrs T = {g_wide.recs.data(), g_wide.cls_off.data(), g_wide.gs.data(), g_wide.binom.data(), g_wide.lay.ncls, g_wide.lay.npoints};
+    uint64_t bad = 0;
+    for (uint64_t k = 0; k < n; k++) {
+        if (idx[k] >= T.npoints) { bad++; std::memset(out + 24 * k, 0, 24); continue; }
+        uint32_t o[6];
+        float rnorm;
+        llvq::wide_decode(T, idx[k], o, rnorm);
+        std::memcpy(out + 24 * k, o, 24);
     }
     return bad;
 }

@@ -17,7 +17,7 @@ EMUL = os.path.join(ROOT, "tests", "host_emul", "libemul.so")
 def emul():
     srcs = [os.path.join(ROOT, "tests", "host_emul", "emul.cpp")] + [
         os.path.join(ROOT, "paper_2603_11021_amd", "csrc", f)
-        for f in ("llvq_tables.cpp", "llvq_tables.h", "llvq_decode_core.h", "llvq_encode_core.h")]
+        for f in ("llvq_tables.cpp", "llvq_tables.h", "llvq_decode_core.h", "llvq_encode_core.h", "llvq_wide.h")]
     if not os.path.exists(EMUL) or os.path.getmtime(EMUL) < max(os.path.getmtime(f) for f in srcs):
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-o", EMUL,
                                os.path.join(ROOT, "tests", "host_emul", "emul.cpp"),
@@ -72,7 +72,7 @@ def test_no_cpu_fallback_without_gpu():
     assert rc == -3 and not h.value                       # LLVQ_EHIP: fails loudly, no context
     lib.llvq_strerror.restype = ctypes.c_char_p
     assert b"HIP" in lib.llvq_strerror(rc)
-    assert lib.llvq_create(ctypes.byref(h), 14, 0) == -1  # LLVQ_EINVAL
+    assert lib.llvq_create(ctypes.byref(h), 20, 0) == -1  # LLVQ_EINVAL
     assert lib.llvq_create(None, 13, 0) == -1
 
 
@@ -161,3 +161,66 @@ def test_synth_pack_u48():
     assert np.array_equal(back, idx)
     x = synth.activations(synth.rng_for(2), 2, 4096)
     assert x.shape == (2, 4104) and not x[:, 4096:].any() and x[:, :4096].any()
+
+
+# ---- the decoder of the larger unions (contexts with m_max > 13) -------------------------------------------------
+@pytest.fixture(scope="module")
+def wide19(emul):
+    lib = emul.lib
+    lib.emul_wide_num_points.restype = ctypes.c_uint64
+    lib.emul_wide_shell_offset.restype = ctypes.c_uint64
+    lib.emul_wide_decode_i8.restype = ctypes.c_uint64
+    lib.emul_wide_decode_i8.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+    assert lib.emul_wide_init(19) == 0
+
+    def decode(idx):
+        idx = np.ascontiguousarray(idx, dtype=np.uint64)
+        out = np.empty((idx.size, 24), dtype=np.int8)
+        bad = lib.emul_wide_decode_i8(idx.ctypes.data, idx.size, out.ctypes.data)
+        return out, int(bad)
+
+    decode.lib = lib
+    return decode
+
+
+@pytest.fixture(scope="module")
+def oracle19():
+    from oracle.llvq_oracle import Oracle
+    return Oracle(19)
+
+
+def test_wide_tables_match_table_1(wide19, oracle19):
+    """1,457 classes and the cumulative count of the paper's Table 1, row m = 19"""
+    lib = wide19.lib
+    assert lib.emul_wide_num_points() == 23546209100646960 == oracle19.num_points
+    assert lib.emul_wide_num_classes() == 1457 == len(oracle19.classes())
+    assert lib.emul_wide_shell_offset(14) == 280974212784720           # N(13)
+
+
+def test_wide_decoder_matches_the_oracle_on_every_class(wide19, oracle19):
+    rng = np.random.default_rng(191)
+    idx = []
+    for c in oracle19.classes():
+        off, size = int(c["offset"]), int(c["size"])
+        idx += [off, off + size - 1] + [off + int(v) for v in rng.integers(0, size, size=40, dtype=np.uint64)]
+    idx = np.array(idx, dtype=np.uint64)
+    got, bad = wide19(idx)
+    want, wbad = oracle19.decode(idx)
+    assert bad == 0 and wbad == 0
+    assert np.array_equal(got, want)
+
+
+def test_wide_decoder_matches_the_oracle_on_random_indices_and_small_shells(wide19, oracle19, oracle13):
+    rng = np.random.default_rng(192)
+    idx = rng.integers(0, oracle19.num_points, size=200000, dtype=np.uint64)
+    got, bad = wide19(idx)
+    want, _ = oracle19.decode(idx)
+    assert bad == 0 and np.array_equal(got, want)
+    # the first N(13) indices are the points of the smaller union, in the same order
+    idx = rng.integers(0, oracle13.num_points, size=50000, dtype=np.uint64)
+    assert np.array_equal(wide19(idx)[0], oracle13.decode(idx)[0])
+    # all of shell 2, and out-of-range indices decode to zero
+    got, _ = wide19(np.arange(196560, dtype=np.uint64))
+    assert np.array_equal(got, oracle13.decode(np.arange(196560, dtype=np.uint64))[0])
+    got, bad = wide19(np.array([oracle19.num_points, 2 ** 63], dtype=np.uint64))
+    assert bad == 2 and not got.any()
