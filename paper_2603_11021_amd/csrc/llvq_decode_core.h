@@ -213,9 +213,10 @@ struct Front {
     float rnorm;
 };
 
-// BIG_GLOBAL: the Golay words and the inner-word planes are read from global memory instead of LDS;
+// BIG_GLOBAL: the Golay words and the inner-word planes are read from global memory instead of LDS
+// (GS_LDS: only the inner-word planes are; the kernel has copied the blob up to kOffInner);
 // REC_GLOBAL: so is the class record
-template <bool BIG_GLOBAL = false, bool REC_GLOBAL = false>
+template <bool BIG_GLOBAL = false, bool REC_GLOBAL = false, bool GS_LDS = false>
 LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     Front F;
     const ClassRec R = REC_GLOBAL ? gtab_at<ClassRec, kOffCls>(T, mul24(hit.cid, (uint32_t)sizeof(ClassRec)))
@@ -241,7 +242,7 @@ LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     const uint32_t rin = (uint32_t)((double)rem * (double)R.invP1);
     const uint32_t rho1 = rem - mul24(rin, R.P1);             // rem < 2^22
     const uint32_t oc = (((f1 >> F1_GOFF) & 4095u) + r) * 4u, o0 = (R.tb0 + rin) * 4u, o1 = (R.tb1 + rho1) * 4u;
-    F.c = BIG_GLOBAL ? gtab_at<uint32_t, kOffGs>(T, oc) : tab_at<uint32_t, kOffGs>(T, oc);
+    F.c = (BIG_GLOBAL && !GS_LDS) ? gtab_at<uint32_t, kOffGs>(T, oc) : tab_at<uint32_t, kOffGs>(T, oc);
     F.e0 = BIG_GLOBAL ? gtab_at<uint32_t, kOffInner>(T, o0) : tab_at<uint32_t, kOffInner>(T, o0);
     F.e1 = BIG_GLOBAL ? gtab_at<uint32_t, kOffInner>(T, o1) : tab_at<uint32_t, kOffInner>(T, o1);
     const uint32_t j = tab_at<uint8_t, kOffGuess>(T, ((f1 >> F1_GROW) & 63u) * kGuessBuckets + (F.d >> ((f1 >> F1_GSHIFT) & 31u)));

@@ -873,18 +873,25 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
     constexpr int kWaves = kThreads / 64;
     constexpr int kPassTiles = kTilePassSlots / TT;                      // row tiles per pass
     constexpr int kTerms = Mma<X2>::kTerms;
-    load_tables(blob, lay.lds_bytes);
+    load_tables(blob, llvq::kOffInner);          // the small tables and the Golay words; the inner-word planes stay in global memory
     const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
-    float* slots = reinterpret_cast<float*>(g_lds + lay.lds_bytes);      // [kWaves][kPassTiles][TT][256]
+    float* slots = reinterpret_cast<float*>(g_lds + llvq::kOffInner);      // [kWaves][kPassTiles][TT][256]
     const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int col = lane & 15, kgrp = lane >> 4;
     const uint32_t S = ((uint32_t)KB + 3) / 4;                            // steps per row tile
     const size_t xpitch = (size_t)KB * 12;                              // dwords per activation row
     const int wg_t0 = blockIdx.x * tiles_per_wg, wg_t1 = min(n_tiles, wg_t0 + tiles_per_wg);
-    // activation rows of this lane as dword offsets, one per token tile (clamped: tokens past M are never stored)
-    uint32_t xoff[TT];
+    // The activation tile of a step (16 tokens x 96 channels per token tile) is fetched with four neighbouring lanes on
+    // one token row (lane = 4 token + group: 16 rows per load instead of 64 distinct lines with the MFMA's own lane
+    // order, which made the vector memory pipe the limit of this kernel) and turned into the MFMA's order through LDS.
+    // The staging buffer is the slot the wave will park the current row tile in: until then it is free.  Unit (token t,
+    // group g) of 16 bytes sits at g * 16 + (t + 2 g) % 16, which spreads a store over all banks.
+    const int ld_tok = lane >> 2, ld_grp = lane & 3;
+    uint32_t xoff[TT];                                   // row of the token this lane FETCHES, as a dword offset (clamped)
 #pragma unroll
-    for (int t = 0; t < TT; t++) xoff[t] = (uint32_t)min(M - 1, 16 * t + col) * (uint32_t)xpitch;
+    for (int t = 0; t < TT; t++) xoff[t] = (uint32_t)min(M - 1, 16 * t + ld_tok) * (uint32_t)xpitch;
+    const uint32_t st_unit = (uint32_t)(ld_grp * 16 + ((ld_tok + 2 * ld_grp) & 15)) * 4;      // in floats
+    const uint32_t rd_unit = (uint32_t)(kgrp * 16 + ((col + 2 * kgrp) & 15)) * 4;
 
     // the matrix a row tile belongs to and the tile's first row inside it (wave-uniform)
     struct Mat { const void* idx; const uint16_t* gain; float* y; int N, row0; };
@@ -925,7 +932,7 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
             uint64_t I;
             finish_block<FMT>(q.raw, cd, I, gb);
             ok = q.live && I < T.npoints;
-            return llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
+            return llvq::decode_front<true, false, true>(T, llvq::find_class(T, ok ? I : 0));
         };
         Blk cur_blk, nxt_blk;
         llvq::Front F, Fn;
@@ -940,12 +947,12 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
         auto step = [&](auto more_tag, uint32_t tl_n, uint32_t st_n) {
             constexpr bool kMore = decltype(more_tag)::value;
             if constexpr (kMore) fetch_blk(tl_n, st_n, nxt_blk);
-            const uint32_t bx = min(4 * st + (uint32_t)kgrp, (uint32_t)KB - 1) * 12;
-            u32x4 xa[TT][3];
+            const uint32_t bx = min(4 * st + (uint32_t)ld_grp, (uint32_t)KB - 1) * 12;
+            u32x4 xl[TT][3];
 #pragma unroll
             for (int t = 0; t < TT; t++) {
                 const u32x4* xp = reinterpret_cast<const u32x4*>(x + (size_t)(xoff[t] + bx));
-                xa[t][0] = xp[0]; xa[t][1] = xp[1]; xa[t][2] = xp[2];
+                xl[t][0] = xp[0]; xl[t][1] = xp[1]; xl[t][2] = xp[2];
             }
             uint32_t w[4];
             const llvq::BlockInfo bi = llvq::decode_back(T, F, w);
@@ -966,18 +973,26 @@ __global__ void __launch_bounds__(kThreads) tile_kernel(const unsigned char* __r
                 for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
             }
             if constexpr (kMore) Fn = front_of(nxt_blk, ok_nxt, g_nxt);
+            // one channel group j at a time through the wave's buffer: LDS operations of a wave execute in order, so
+            // the store of group j + 1 cannot overtake the loads of group j
+            float* stage = slots + ((size_t)(wave * kPassTiles + (int)tl) * TT) * 256;
 #pragma unroll
             for (int j = 0; j < 3; j++) {
+                u32x4 xa[TT];
+#pragma unroll
+                for (int t = 0; t < TT; t++) *reinterpret_cast<u32x4*>(stage + t * 256 + st_unit) = xl[t][j];
+#pragma unroll
+                for (int t = 0; t < TT; t++) xa[t] = *reinterpret_cast<const u32x4*>(stage + t * 256 + rd_unit);
 #pragma unroll
                 for (int r = 0; r < kTerms; r++) {
                     const u32x4 bw = {wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]};
 #pragma unroll
-                    for (int t = 0; t < TT; t++) acc[t] = Mma16<X2>::mma(xa[t][j], bw, acc[t]);
+                    for (int t = 0; t < TT; t++) acc[t] = Mma16<X2>::mma(xa[t], bw, acc[t]);
                 }
             }
             // leaving this row tile (or the pass): park the accumulated tile in this wave's slot and start from zero
             if (!kMore || tl_n != tl) {
-                float* dst = slots + ((size_t)(wave * kPassTiles + (int)tl) * TT) * 256 + lane * 4;
+                float* dst = stage + lane * 4;
 #pragma unroll
                 for (int t = 0; t < TT; t++) {
                     *reinterpret_cast<float4_t*>(dst + t * 256) = acc[t];
@@ -1515,7 +1530,7 @@ static int launch_tile(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx,
     int grid = std::min(ctx->num_cu, n_tiles);
     const int per_wg = (n_tiles + grid - 1) / grid;
     grid = (n_tiles + per_wg - 1) / per_wg;
-    const size_t lds = ctx->lay.lds_bytes + (size_t)(kThreads / 64) * kTilePassSlots * 256 * sizeof(float);
+    const size_t lds = llvq::kOffInner + (size_t)(kThreads / 64) * kTilePassSlots * 256 * sizeof(float);
     if (int rc = set_lds<tile_kernel<FMT, X2, TT, MULTI>>(ctx, lds)) return rc;
     hipLaunchKernelGGL((tile_kernel<FMT, X2, TT, MULTI>), dim3(grid), dim3(kThreads), lds, st, ctx->d_blob, ctx->lay, d_idx,
                        reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, n_tiles, per_wg, items, d_y);
