@@ -433,7 +433,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
         load_raw_near<FMT>(idx0, gain0, min((uint32_t)wave * 64u + (uint32_t)lane, nblk - 1), first_raw);
     }
     // one workgroup per compute unit: the tables are copied once per launch and workgroup
-    const uint32_t table_bytes = BIG_GLOBAL ? lay.lds_bytes : lay.blob_bytes;
+    const uint32_t table_bytes = BIG_GLOBAL ? llvq::kOffInner : lay.blob_bytes;      // short launches: small tables + Golay words
     float* ysum = reinterpret_cast<float*>(g_lds + table_bytes);      // [kRowsPerPass][kMaxMChunk]
     // the first block number no wave has taken yet: the first two batches of a wave are fixed, after them it takes the
     // next free one, so waves on a SIMD that gets through its batches sooner end up with more of them
@@ -483,7 +483,7 @@ __global__ void __launch_bounds__(kThreads) matmul_kernel(const unsigned char* _
                 ok = f.live && I < T.npoints;
                 // long launches (all tables in LDS) read the class record through the otherwise idle vector cache: the LDS
                 // gather pipe is as busy as the vector ALUs there, and three 16-byte gathers per block are a tenth of its load
-                return llvq::decode_front<BIG_GLOBAL, !BIG_GLOBAL>(T, llvq::find_class(T, ok ? I : 0));
+                return llvq::decode_front<BIG_GLOBAL, !BIG_GLOBAL, true>(T, llvq::find_class(T, ok ? I : 0));
             };
             uint32_t base = (uint32_t)wave * 64, next = base + kThreads, taken = 0;
             Fetch cur, nxt;
@@ -1485,7 +1485,7 @@ static int launch_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_id
     // from 64 batches of 64 blocks per compute unit on (four per wave; measured on Llama-3-8B and 70B shapes), copying
     // all tables into LDS pays, and so does dealing the batches to the waves as they finish
     const bool short_launch = (size_t)N * (size_t)KB / 64 < (size_t)ctx->num_cu * 64;
-    const size_t lds = (short_launch ? ctx->lay.lds_bytes : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;   // row sums + batch counter
+    const size_t lds = (short_launch ? llvq::kOffInner : ctx->lay.blob_bytes) + (size_t)kRowsPerPass * kMaxMChunk * sizeof(float) + 16;   // row sums + batch counter
     const int rows_pass = std::max(1, std::min(kRowsPerPass, ((1 << 24) - 1) / KB));       // KB < 2^24 (checked by the caller)
 #define LLVQ_LAUNCH_MATMUL(BG, DYN)                                                                                         \
     do {                                                                                                                    \
