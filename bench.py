@@ -107,6 +107,21 @@ def main():
         for (_, idxs, gains, Ns, KB, ys) in ring[i % args.ring]:
             q.llvq_matmul_multi(d_x[KB], idxs, gains, Ns, KB, outs=ys)
 
+    # what a plain device copy reaches on this machine: 1 GiB read + 1 GiB written, HIP events, best of five (measured before
+    # the timed region: it is not part of a step)
+    csrc = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    cdst = torch.empty_like(csrc)
+    cdst.copy_(csrc)
+    copy_gbs = 0.0
+    for _ in range(5):
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        cdst.copy_(csrc)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = max(copy_gbs, 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9)
+    del csrc, cdst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -170,20 +185,6 @@ def main():
     single = None
     if not args.no_single:
         single = single_layer(q, synth, torch, dev, args, oracle)
-
-    # what a plain device copy reaches on this machine: 1 GiB read + 1 GiB written, HIP events, best of five
-    csrc = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-    cdst = torch.empty_like(csrc)
-    cdst.copy_(csrc)
-    copy_gbs = 0.0
-    for _ in range(5):
-        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        c0.record()
-        cdst.copy_(csrc)
-        c1.record()
-        torch.cuda.synchronize()
-        copy_gbs = max(copy_gbs, 2.0 * (1 << 30) / (c0.elapsed_time(c1) * 1e-3) / 1e9)
-    del csrc, cdst
 
     if args.extra:
         extra_layer_set(q, synth, torch, dev)
