@@ -183,8 +183,18 @@ def main():
 
     # the single layer of the paper's own timing table (App. C: 4096 x 4104), ring of distinct layers, one launch per step
     single = None
+    batch16 = None
+    set70b = None
     if not args.no_single:
         single = single_layer(q, synth, torch, dev, args, oracle)
+        # the same ring of transformer blocks at batch 16 (the batched-decode kernel), same launches
+        batch16 = layer_set_pass(q, synth, torch, dev, ring, {KB: synth.activations(synth.rng_for(3, 950 + KB), 16, 24 * KB) for KB in x_host},
+                                 nblk, max(args.steps // 4, 5), max(args.warmup // 4, 2))
+        batch16["ms_per_step_batch1_events"] = ev_ms
+        batch16["ratio_to_batch1"] = batch16["ms_per_step_events"] / ev_ms
+        del ring
+        # the Llama-3-70B-shaped layer set at batch 1: one transformer block (285.6 MB packed), same four launches per step
+        set70b = llama70b_set(q, synth, torch, dev, max(args.steps // 10, 5), max(args.warmup // 10, 2))
 
     if args.extra:
         extra_layer_set(q, synth, torch, dev)
@@ -234,9 +244,79 @@ def main():
                      "launches_timed": args.steps * n_launch,
                      "alu": alu},
         "single_layer_4096x4104": single,
+        "layer_set_batch16": batch16,
+        "llama3_70b_layer_set": set70b,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
+
+
+def layer_set_pass(q, synth, torch, dev, ring, x_host, nblk, steps, warmup):
+    """the ring of transformer blocks with other activations (M rows): HIP-event time per step"""
+    import numpy as np
+    d_x = {KB: torch.from_numpy(x.astype(np.float16)).to(dev) for KB, x in x_host.items()}
+    M = next(iter(x_host.values())).shape[0]
+    outs = [[[torch.empty((M, N), dtype=torch.float32, device=dev) for N in Ns] for (_, _, _, Ns, _, _) in blk] for blk in ring]
+
+    def step(i):
+        b = i % len(ring)
+        for (launch, ys) in zip(ring[b], outs[b]):
+            _, idxs, gains, Ns, KB, _ = launch
+            q.llvq_matmul_multi(d_x[KB], idxs, gains, Ns, KB, outs=ys)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        step(warmup + i)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return {"workload": "the same ring of transformer blocks at batch %d (llvq_matmul_multi, 4 launches per step)" % M, "M": M, "steps": steps,
+            "warmup": warmup, "ms_per_step_events": ms, "packed_GBs_events": BYTES_PER_BLOCK * nblk / ms / 1e6,
+            "blocks_per_s": nblk / (ms * 1e-3)}
+
+
+def llama70b_set(q, synth, torch, dev, steps, warmup):
+    import numpy as np
+    shapes = synth.LLAMA3_70B
+    mats = {}
+    nblk = 0
+    for i, (name, (N, K)) in enumerate(shapes.items()):
+        KB = synth.blocks_per_row(K)
+        r = synth.rng_for(5, i)
+        mats[name] = (torch.from_numpy(synth.pack_u48(synth.indices(r, (N, KB))).reshape(-1)).to(dev),
+                      torch.from_numpy(synth.gains(r, (N, KB)).reshape(-1)).to(dev), N, KB)
+        nblk += N * KB
+    launches = []
+    for group in GROUPS:
+        ms_ = [mats[g] for g in group]
+        KB = ms_[0][3]
+        x = torch.from_numpy(synth.activations(synth.rng_for(5, 900 + KB % 997), 1, 24 * KB).astype(np.float16)).to(dev)
+        launches.append((x, [m[0] for m in ms_], [m[1] for m in ms_], [m[2] for m in ms_], KB,
+                         [torch.empty((1, m[2]), dtype=torch.float32, device=dev) for m in ms_]))
+
+    def step():
+        for (x, idxs, gains, Ns, KB, ys) in launches:
+            q.llvq_matmul_multi(x, idxs, gains, Ns, KB, outs=ys)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    return {"workload": "Llama-3-70B-shaped layer set, batch 1: q/o 8192x8192, k/v 1024x8192, gate/up 28672x8192, down 8192x28672; one transformer "
+                        "block (%.1f MB packed, larger than the last-level cache), 4 launches per step" % (nblk * 8 / 1e6),
+            "blocks_per_step": nblk, "steps": steps, "warmup": warmup, "ms_per_step_events": ms,
+            "packed_GBs_events": BYTES_PER_BLOCK * nblk / ms / 1e6, "hbm_frac_events": BYTES_PER_BLOCK * nblk / ms / 1e6 / HBM_PEAK_GBS,
+            "blocks_per_s": nblk / (ms * 1e-3)}
 
 
 def single_layer(q, synth, torch, dev, args, oracle):
