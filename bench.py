@@ -55,7 +55,9 @@ def main():
     ap.add_argument("--rows", type=int, default=4096,
                     help="output rows N of the single-layer figure; larger values amortise the per-launch fixed cost")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-single", action="store_true", help="skip the single 4096 x 4104 layer figure")
+    ap.add_argument("--no-single", action="store_true", help="skip the figures that ride along: single 4096 x 4104 layer, batch 16, 70B-shaped set")
+    ap.add_argument("--only-single", action="store_true",
+                    help="run ONLY the single rows x 4104 layer loop and print its figures (for rocprofv3 runs of that launch)")
     ap.add_argument("--extra", action="store_true", help="also time the layer sets launch by launch, batch 16, prefill and bulk decode (stderr)")
     ap.add_argument("--sweep", action="store_true",
                     help="also run the batch-1 product over a range of sizes, 320 launches each (stderr); under "
@@ -75,6 +77,10 @@ def main():
     dev = torch.device("cuda:0")
     q = LLVQ(13, 0)
     M = 1
+    if args.only_single:
+        from oracle.llvq_oracle import Oracle
+        print(json.dumps(single_layer(q, synth, torch, dev, args, Oracle(13))))
+        return
 
     # ring of distinct Llama-3-8B-shaped transformer blocks: uniform indices over the union of shells 2..13, log-normal gains
     shapes = synth.LLAMA3_8B
@@ -651,6 +657,15 @@ def extra_shapes(q, synth, torch, dev):
     us = timeit(lambda: q.llvq_matmul_coded(x, w24, N, KB, 24, base, gain=gain, fmt=LLVQ_IDX_U24, out=y))
     print("matmul %dx%d M=1 single shell 3, 24-bit words + fp16 gain (5 B/block): %9.2f us  %.1f GB/s packed  %.2f G blocks/s" %
           (N, 24 * KB, us, n * 5 / us / 1e3, n / us / 1e3), file=sys.stderr)
+    # a context for the union up to shell 19 (55-bit indices): the generic decoder with tables in global memory
+    q19 = type(q)(19, 0)
+    i19 = torch.from_numpy(r.integers(0, q19.num_points, size=n, dtype=np.uint64).view(np.int64)).to(dev)
+    out8 = torch.empty((n, 24), dtype=torch.int8, device=dev)
+    us = timeit(lambda: q19.llvq_decode_i8(i19, out=out8), reps=5)
+    print("m_max = 19 (1,457 classes, 55-bit indices): decode to int8 %d blocks: %9.2f us  %.2f G blocks/s" % (n, us, n / us / 1e3), file=sys.stderr)
+    us = timeit(lambda: q19.llvq_matmul(x, i19, gain, N, KB, out=y), reps=5)
+    print("m_max = 19: matmul %dx%d M=1: %9.2f us  %.2f G blocks/s" % (N, 24 * KB, us, n / us / 1e3), file=sys.stderr)
+    del q19, i19, out8
     # the configuration of the paper's own timing table (App. C): 4096 x 4104, single shell, 24-bit words, constant norm
     Np, KBp = 4096, 171
     one = torch.ones(1, dtype=torch.float16, device=dev)
