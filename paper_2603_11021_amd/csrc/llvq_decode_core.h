@@ -253,9 +253,9 @@ LLVQ_HD Front decode_front(const TabPtrs& T, const ClassHit& hit) {
     return F;
 }
 
-// App. A step 4: placement and signs.  w[0..3] receive the nibble words of the block.
-LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]) {
-    // the q-subset U of the outer domain's n slots with rank d
+// App. A step 4, first part: the q-subset U of the outer domain's n slots with rank d, relative to the domain
+// (bit i = slot i of the domain); needs only the digits, not the Golay word
+LLVQ_HD uint32_t decode_subset(const TabPtrs& T, const Front& F) {
     uint32_t j = F.sp_j >> 16, eo = (F.sp_j & 0xFFFFu) * (uint32_t)sizeof(SplitEnt);
     SplitEnt e = tab_at<SplitEnt, kOffSplit>(T, eo);
     uint32_t nbase = tab_at<uint32_t, kOffSplit + sizeof(SplitEnt)>(T, eo);   // one past the last entry is never used
@@ -273,9 +273,12 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
     const uint32_t dl = F.d - e.base;
     const uint32_t rk_hi = (uint32_t)((double)dl * (double)e.inv);
     const uint32_t rk_lo = dl - mul24(rk_hi, e.div);          // dl < C(24, 12) < 2^22
-    const uint32_t U = (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12lo + rk_lo) * 2u) |
-                       ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12hi + rk_hi) * 2u) << 12);
+    return (uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12lo + rk_lo) * 2u) |
+           ((uint32_t)tab_at<uint16_t, kOffLut12>(T, (e.b12hi + rk_hi) * 2u) << 12);
+}
 
+// App. A step 4, second part: placement and signs for the subset U.  w[0..3] receive the nibble words of the block.
+LLVQ_HD BlockInfo decode_place(const TabPtrs& T, const Front& F, uint32_t U, uint32_t (&w)[4]) {
     BlockInfo info;
     const uint32_t f0 = F.f0;
     info.cid = F.cid; info.m = (f0 >> F0_M) & 15u;
@@ -342,6 +345,11 @@ LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]
         }
     }
     return info;
+}
+
+// App. A step 4 in one call
+LLVQ_HD BlockInfo decode_back(const TabPtrs& T, const Front& F, uint32_t (&w)[4]) {
+    return decode_place(T, F, decode_subset(T, F), w);
 }
 
 // Decodes one index I (must be < npoints); w[0..3] receive the nibble words.

@@ -1177,6 +1177,235 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
     }
 }
 
+// ---- llvq_matmul, prefill kernel for M >= kPanelMinM: decoded weights shared through LDS ------------------------
+// The index decode costs the vector ALUs and the LDS gather pipe as much per block as 500 tokens cost the matrix cores,
+// so a block should be decoded once per as many tokens as the accumulators can hold.  A workgroup of eight waves owns a
+// panel of 128 weight rows x 512 tokens: wave w keeps ALL 128 rows x tokens 64 w .. 64 w + 63 (eight 32 x 32 tiles, 128
+// accumulator registers), i.e. the waves split the tokens, not the rows.  Per step (a block pair = 48 channels) the four
+// 32-row tiles are decoded by four of the waves (the two halves of the workgroup take turns, so a SIMD always hosts
+// one decoding and one multiplying wave) and written to LDS as ready-made MFMA B operands; every wave reads the 12 KB
+// of the step's weights from there and the A operands of its own 64 tokens from a private region of LDS that it fills
+// itself (six lanes fetch the 96 bytes of a token row: few cache lines per load), which needs no barrier: the LDS
+// operations of a wave execute in order.  One barrier per step publishes the weights.  Against prefill_kernel a step
+// moves 18 KB instead of 24 KB per wave through LDS for twice the tokens per decoded block.
+// The decode of a step is spread over two steps of its wave: class search and digits while the wave's half is off
+// duty, placement, signs and scaling in the step before the weights are needed.
+constexpr int kPanelRows = 128, kPanelTokens = 512, kPanelWaves = 8;
+constexpr int kPanelMinM = 384;
+
+template <int FMT, typename X2>
+__global__ void __launch_bounds__(64 * kPanelWaves) panel_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
+                                                                   const void* __restrict__ idx, const uint16_t* __restrict__ gain,
+                                                                   const uint32_t* __restrict__ x, int M, int N, int KB, Code cd,
+                                                                   int ksplit, float* __restrict__ y) {
+    constexpr int kTerms = Mma<X2>::kTerms;
+    constexpr int kBBufs = kTerms == 1 ? 2 : 1;                      // two-term weights: one buffer, a second barrier per step
+    constexpr uint32_t kBBytes = 4 * 3 * 1024 * kTerms;              // [term][row tile][k group][lane] x 16 bytes
+    constexpr uint32_t kARegion = 7 * 1024;                          // one wave's 64 token rows: seven staging instructions x 1 KB
+    load_tables<64 * kPanelWaves>(blob, lay.lds_bytes);
+    const TabPtrs T = llvq::make_tab_ptrs(lds_origin(), blob, lay);
+    unsigned char* bbuf = g_lds + lay.lds_bytes;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    unsigned char* abuf = bbuf + kBBufs * kBBytes + (uint32_t)wave * kARegion;
+    const int col = lane & 31, half = lane >> 5;
+    const uint32_t spt_all = ((uint32_t)KB + 1) / 2;
+    const uint32_t st_first = (uint32_t)(((uint64_t)spt_all * blockIdx.z) / (uint32_t)ksplit);
+    const uint32_t st_end = (uint32_t)(((uint64_t)spt_all * (blockIdx.z + 1)) / (uint32_t)ksplit);
+    const int row0 = (int)blockIdx.x * kPanelRows;
+    const int m0 = (int)blockIdx.y * kPanelTokens + wave * 64;        // first token of this wave
+    const uint32_t xpitch = (uint32_t)KB * 12u;                       // dwords per activation row
+
+    // decoding role: row tile (wave % 4), steps of parity (wave / 4) counted from st_first
+    const int drt = wave & 3;
+    const uint32_t dpar = (uint32_t)wave >> 2;
+    const int wrow = row0 + 32 * drt + col;
+    struct Blk { RawBlock raw; bool live; };
+    auto fetch_blk = [&](uint32_t st, Blk& q) {
+        const uint32_t b = 2 * st + (uint32_t)half;
+        q.live = wrow < N && b < (uint32_t)KB;
+        const size_t k = (size_t)min(wrow, N - 1) * KB + min(b, (uint32_t)KB - 1);
+        load_raw<FMT>(idx, gain, cd.gain_array(), k, q.raw);
+    };
+    // first part of a block's decode: class, digits and the subset U (everything that does not need the Golay word and
+    // the inner-word planes, whose reads from global memory are left in flight)
+    auto front_of = [&](const Blk& q, bool& ok, uint16_t& gb, uint32_t& U) {
+        uint64_t I;
+        finish_block<FMT>(q.raw, cd, I, gb);
+        ok = q.live && I < T.npoints;
+        const llvq::Front f = llvq::decode_front<true>(T, llvq::find_class(T, ok ? I : 0));
+        U = llvq::decode_subset(T, f);
+        return f;
+    };
+    // second part: placement, signs, scaling; the weights go to LDS as B operands of `buf`
+    auto back_to_lds = [&](const llvq::Front& F, uint32_t U, bool ok, uint16_t gb, uint32_t buf) {
+        uint32_t w[4];
+        const llvq::BlockInfo bi = llvq::decode_place(T, F, U, w);
+        const float scale = ok ? __half2float(__ushort_as_half(gb)) * bi.rnorm : 0.0f;
+        uint32_t wt[kTerms][12];
+#pragma unroll
+        for (int c = 0; c < 4; c++) {
+            uint32_t fe, fo, o[kTerms];
+            chunk_fp8(w[c], bi.vt8_lo, bi.vt8_hi, fe, fo);
+            Mma<X2>::weights(fe, false, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 0] = o[r];
+            Mma<X2>::weights(fo, false, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 1] = o[r];
+            Mma<X2>::weights(fe, true, scale, o);
+#pragma unroll
+            for (int r = 0; r < kTerms; r++) wt[r][3 * c + 2] = o[r];
+        }
+        unsigned char* dst = bbuf + buf * kBBytes + (uint32_t)(drt * 3) * 1024u + (uint32_t)lane * 16u;
+#pragma unroll
+        for (int r = 0; r < kTerms; r++) {
+#pragma unroll
+            for (int j = 0; j < 3; j++)
+                *reinterpret_cast<u32x4*>(dst + (uint32_t)(r * 12 + j) * 1024u) = u32x4{wt[r][4 * j], wt[r][4 * j + 1], wt[r][4 * j + 2], wt[r][4 * j + 3]};
+        }
+    };
+
+    // Staging of this wave's activation rows, global memory -> LDS without passing registers: one wave instruction moves
+    // 64 x 16 bytes to 1 KB of consecutive LDS addresses.  Lane 6 k + q of instruction i fetches piece q (channels
+    // 8 (q % 3) .. + 7 of block 2 st + q / 3) of token 10 i + k, so the 96 bytes of a token row are fetched by six
+    // neighbouring lanes (few cache lines per instruction) and land at i * 1024 + k * 96; seven instructions cover the 64
+    // tokens (lanes 60..63 and the tail of the last instruction fetch copies that nobody reads).
+    const int s_tok = lane / 6, s_q = lane - 6 * s_tok;
+    // byte offsets of this lane's seven token rows in x (M * KB * 48 < 2^32, checked by the host)
+    uint32_t s_row[7];
+#pragma unroll
+    for (int i = 0; i < 7; i++) s_row[i] = (uint32_t)min(M - 1, m0 + min(10 * i + s_tok, 63)) * (xpitch * 4u) + (uint32_t)(s_q % 3) * 16u;
+    auto stage_dma = [&](uint32_t st) {
+        const uint32_t b = min(2 * st + (uint32_t)(s_q / 3), (uint32_t)KB - 1);      // past the last block: any valid data, its weights are zero
+        const uint32_t boff = b * 48u;
+#pragma unroll
+        for (int i = 0; i < 7; i++)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(reinterpret_cast<const unsigned char*>(x) + (s_row[i] + boff)),
+                                             (__attribute__((address_space(3))) void*)(abuf + i * 1024), 16, 0, 0);
+    };
+    // A operands of the staged step in the MFMA's order: token 32 t + col, the lane half's block, channel group j
+    uint32_t a_off[2];
+#pragma unroll
+    for (int t = 0; t < 2; t++) a_off[t] = (uint32_t)((32 * t + col) / 10) * 1024u + (uint32_t)((32 * t + col) % 10) * 96u + (uint32_t)half * 48u;
+    u32x4 a[3][2];
+    auto read_a = [&]() {
+#pragma unroll
+        for (int j = 0; j < 3; j++) {
+#pragma unroll
+            for (int t = 0; t < 2; t++) a[j][t] = *reinterpret_cast<const u32x4*>(abuf + a_off[t] + (uint32_t)j * 16u);
+        }
+    };
+
+    float16_t acc[4][2];
+#pragma unroll
+    for (int rt = 0; rt < 4; rt++) {
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) acc[rt][t][v] = 0.0f;
+        }
+    }
+
+    // Prologue.  Relative step r = st - st_first; the half with parity r % 2 decodes step r.  Before the first step:
+    // half 0 decodes step 0 completely and requests the word of step 2; half 1 does the first part of step 1.
+    Blk blk;
+    llvq::Front F;
+    uint32_t U = 0;
+    bool ok = false;
+    uint16_t gb = 0;
+    const uint32_t my_first = st_first + dpar;
+    if (my_first < st_end) {
+        fetch_blk(my_first, blk);
+        F = front_of(blk, ok, gb, U);
+    }
+    if (dpar == 0) {
+        if (my_first < st_end) back_to_lds(F, U, ok, gb, 0);
+        if (my_first + 2 < st_end) fetch_blk(my_first + 2, blk);
+    }
+    stage_dma(st_first);
+    __builtin_amdgcn_s_waitcnt(0);              // vmcnt(0): the rows have landed
+    read_a();
+    __syncthreads();
+
+    for (uint32_t st = st_first; st < st_end; st++) {
+        const uint32_t r = st - st_first;
+        const bool back_turn = ((r + 1) & 1u) == dpar;               // this wave finishes step st + 1 now (wave-uniform)
+        const uint32_t bcur = kBBufs == 2 ? (r & 1u) : 0u, bnext = kBBufs == 2 ? ((r + 1) & 1u) : 0u;
+        // the A operands of step st are in registers (read before the barrier that ended the last step), so the
+        // activation rows of step st + 1 can be requested into the same region right away
+        // (the decoding half asks after its decode: all eight waves asking at once right after the barrier queue at the
+        // vector memory pipe, 56 KB per step, and every one of them waits for the issue of its seven loads)
+        const uint32_t st_stage = st + 1 < st_end ? st + 1 : st;
+        if (!(kBBufs == 2 && back_turn)) stage_dma(st_stage);
+        // second part of step st + 1 before the products: the other wave of this SIMD multiplies meanwhile
+        if (kBBufs == 2 && back_turn) {
+            if (st + 1 < st_end) back_to_lds(F, U, ok, gb, bnext);
+            if (st + 3 < st_end) fetch_blk(st + 3, blk);
+        }
+        if (kBBufs == 2 && back_turn) stage_dma(st_stage);
+        // The products of step st: A operands of all three channel groups first, B operands one group ahead.
+        // Waves whose tokens lie past M work on copies of token M - 1 and store nothing at the end.
+        {
+            const unsigned char* brow = bbuf + bcur * kBBytes + (uint32_t)lane * 16u;
+            u32x4 b[2][kTerms][4];
+            auto load_b = [&](int j, u32x4 (&dst)[kTerms][4]) {
+#pragma unroll
+                for (int rr = 0; rr < kTerms; rr++) {
+#pragma unroll
+                    for (int rt = 0; rt < 4; rt++) dst[rr][rt] = *reinterpret_cast<const u32x4*>(brow + (uint32_t)(rr * 12 + rt * 3 + j) * 1024u);
+                }
+            };
+            load_b(0, b[0]);
+#pragma unroll
+            for (int j = 0; j < 3; j++) {
+                if (j + 1 < 3) load_b(j + 1, b[(j + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);                   // keep the reads ahead of the products they are not needed for
+#pragma unroll
+                for (int rt = 0; rt < 4; rt++) {
+#pragma unroll
+                    for (int rr = 0; rr < kTerms; rr++) {
+#pragma unroll
+                        for (int t = 0; t < 2; t++) acc[rt][t] = Mma<X2>::mma(a[j][t], b[j & 1][rr][rt], acc[rt][t]);
+                    }
+                }
+            }
+        }
+        if (kBBufs == 1) {
+            __syncthreads();                                         // every wave has read the weights of step st
+            if (back_turn) {
+                if (st + 1 < st_end) back_to_lds(F, U, ok, gb, 0);
+                if (st + 3 < st_end) fetch_blk(st + 3, blk);
+            }
+        }
+        if (!back_turn && st + 2 < st_end) F = front_of(blk, ok, gb, U);       // first part of step st + 2
+        // No load stays in flight across the end of a step: the values are carried in registers around the loop, and a
+        // pending one makes the compiler wait for ALL loads at the top of the next step, before it requests the
+        // activation rows.  Both were requested at least one phase ago.
+        asm volatile("" :: "v"(F.c), "v"(F.e0), "v"(F.e1), "v"(blk.raw.a), "v"(blk.raw.b), "v"(blk.raw.c), "v"(blk.raw.g));
+        __builtin_amdgcn_s_waitcnt(0);          // vmcnt(0): the rows of step st + 1 have landed in LDS
+        read_a();
+        __syncthreads();
+    }
+
+    // y[token][row]: register v of tile (rt, t) belongs to token m0 + 32 t + 8 (v / 4) + 4 half + v % 4, row row0 + 32 rt + col
+#pragma unroll
+    for (int rt = 0; rt < 4; rt++) {
+        const int row = row0 + 32 * rt + col;
+        if (row >= N) continue;
+#pragma unroll
+        for (int t = 0; t < 2; t++) {
+#pragma unroll
+            for (int v = 0; v < 16; v++) {
+                const int tok = m0 + 32 * t + 8 * (v / 4) + 4 * half + (v % 4);
+                if (tok < M) {
+                    if (ksplit == 1) y[(size_t)tok * N + row] = acc[rt][t][v];
+                    else atomicAdd(y + (size_t)tok * N + row, acc[rt][t][v]);
+                }
+            }
+        }
+    }
+}
+
 // ---- llvq_encode --------------------------------------------------------------------------------------
 // One lane per vector: 24 bytes in, one index out.  The encoder's tables (68.5 KB) are copied to LDS first.
 template <int FMT, bool DYNAMIC>
@@ -1612,8 +1841,34 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
 }
 
 template <int FMT, typename X2>
+static int launch_panel(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
+    const unsigned strips = (unsigned)((N + kPanelRows - 1) / kPanelRows), passes = (unsigned)((M + kPanelTokens - 1) / kPanelTokens);
+    // enough workgroups for the chip: split the block pairs of a row among up to ksplit workgroups (at least 16 steps each)
+    const unsigned spt = ((unsigned)KB + 1) / 2;
+    unsigned ksplit = (unsigned)ctx->num_cu / (strips * passes);
+    ksplit = std::max(1u, std::min(ksplit, std::max(1u, spt / 16)));
+    if (ksplit > 1) {
+        const size_t ny = (size_t)M * N;
+        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+    }
+    const dim3 grid(strips, passes, ksplit);
+    constexpr int kTerms = Mma<X2>::kTerms;
+    const size_t lds = ctx->lay.lds_bytes + (size_t)(kTerms == 1 ? 2 : 1) * (4 * 3 * 1024 * kTerms) + (size_t)kPanelWaves * 7 * 1024;
+    if (int rc = set_lds<panel_kernel<FMT, X2>>(ctx, lds)) return rc;
+    hipLaunchKernelGGL((panel_kernel<FMT, X2>), grid, dim3(64 * kPanelWaves), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, d_y);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "panel matmul launch");
+}
+
+template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
+    // panels of 128 rows x 512 tokens from kPanelMinM tokens on, when there are enough of them for a quarter of the chip
+    // (the rest comes from splitting the rows' block pairs); activation offsets inside the kernel are 32-bit byte offsets
+    if (M >= kPanelMinM && (uint64_t)M * (uint64_t)KB * 48u < (1ull << 32) &&
+        (uint64_t)((N + kPanelRows - 1) / kPanelRows) * (uint64_t)((M + kPanelTokens - 1) / kPanelTokens) * 4u >= (uint64_t)ctx->num_cu)
+        return launch_panel<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M > 64) return launch_prefill<FMT, X2, 8, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M <= 16) return launch_tile<FMT, X2, 1>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M <= kTileMaxM) return launch_tile<FMT, X2, 2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);

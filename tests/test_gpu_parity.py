@@ -300,6 +300,17 @@ def test_strip_prefill_ragged_shapes(gpu, oracle13, N, K, M):
     _matmul_case(gpu, oracle13, 8, N + K + M, N, K, M, sample_rows=200)
 
 
+@pytest.mark.parametrize("N,K,M,xd", [(8200, 24 * 33, 385, "f16"), (8200, 24 * 33, 385, "bf16"), (16500, 24, 400, "f16"),
+                                      (8193, 48, 1024, "bf16"), (9000, 24 * 70, 513, "f16"), (4100, 24 * 131, 1000, "bf16")])
+def test_panel_prefill_ragged_shapes(gpu, oracle13, N, K, M, xd):
+    """M >= 384 with enough rows: panels of 128 rows x 512 tokens whose waves split the tokens and share the decoded
+    weights through LDS.  Ragged last panel (rows and tokens), token groups past M, an odd block count, one or two steps
+    only, rows split along K with the parts added into a cleared y (the last two shapes); both activation types"""
+    err = _matmul_case(gpu, oracle13, 8, 500 + N + K + M, N, K, M, x_dtype=np.float16 if xd == "f16" else "bf16", sample_rows=160)
+    if xd == "bf16":
+        assert err <= 1e-4, err
+
+
 @pytest.mark.parametrize("name,M,xd", [("q", 96, "f16"), ("k", 256, "bf16"), ("q", 1024, "bf16"), ("gate", 130, "f16")])
 def test_prefill_with_workspace(gpu, oracle13, name, M, xd):
     """llvq_matmul_ws: weights dequantised once into the caller's workspace, then a dense GEMM.  The result must
