@@ -8,6 +8,7 @@ Each DIR holds the CSV files of one rocprofv3 run (`--output-format csv`) of the
   --trace   rocprofv3 --kernel-trace --stats          -> *_kernel_trace.csv   (durations)
   --sq      rocprofv3 --pmc SQ_WAVES SQ_INSTS_VALU SQ_INSTS_LDS SQ_BUSY_CYCLES SQ_ACTIVE_INST_VALU SQ_LDS_IDX_ACTIVE
                           SQ_LDS_BANK_CONFLICT SQ_THREAD_CYCLES_VALU   -> *_counter_collection.csv
+            (matrix-core kernels: SQ_VALU_MFMA_BUSY_CYCLES SQ_INSTS_MFMA in place of the last two SQ_ACTIVE/THREAD counters)
   --fetch   rocprofv3 --pmc FETCH_SIZE                                  -> *_counter_collection.csv
   --write   rocprofv3 --pmc WRITE_SIZE                                  -> *_counter_collection.csv
 Only dispatches whose kernel name contains --kernel are counted; a step is --launches-per-step consecutive ones.
@@ -108,6 +109,10 @@ def main(argv=None):
                 put("valu_issue_share_of_busy_cycles = %.3f   # SQ_INSTS_VALU x 4 / 1024 SIMDs against SQ_BUSY_CYCLES / 32" % (tot["SQ_INSTS_VALU"] * 4.0 / 1024.0 / cyc))
                 if "SQ_LDS_IDX_ACTIVE" in tot:
                     put("lds_active_share_of_busy_cycles = %.3f   # SQ_LDS_IDX_ACTIVE / 256 CUs" % (tot["SQ_LDS_IDX_ACTIVE"] / 256.0 / cyc))
+                if "SQ_VALU_MFMA_BUSY_CYCLES" in tot:
+                    put("mfma_busy_share_of_busy_cycles = %.3f   # SQ_VALU_MFMA_BUSY_CYCLES / 1024 SIMDs" % (tot["SQ_VALU_MFMA_BUSY_CYCLES"] / 1024.0 / cyc))
+            if "SQ_INSTS_MFMA" in tot and tot.get("SQ_VALU_MFMA_BUSY_CYCLES"):
+                put("mfma_busy_cycles_per_mfma_instruction = %.1f" % (tot["SQ_VALU_MFMA_BUSY_CYCLES"] / tot["SQ_INSTS_MFMA"]))
     traffic = 0.0
     have = 0
     for what, d, ctr in (("fetch", a.fetch, "FETCH_SIZE"), ("write", a.write, "WRITE_SIZE")):
