@@ -1308,46 +1308,61 @@ __global__ void __launch_bounds__(64 * kPanelWaves) panel_kernel(const unsigned 
 
     // Prologue.  Relative step r = st - st_first; the half with parity r % 2 decodes step r.  Before the first step:
     // half 0 decodes step 0 completely and requests the word of step 2; half 1 does the first part of step 1.
+    // Steps past the last one are replaced by the last one wherever something is requested or decoded ahead: the loop
+    // then has no conditional assignments, and what is decoded in excess is never read.
+    const uint32_t st_last = st_end - 1;
     Blk blk;
     llvq::Front F;
     uint32_t U = 0;
     bool ok = false;
     uint16_t gb = 0;
-    const uint32_t my_first = st_first + dpar;
-    if (my_first < st_end) {
-        fetch_blk(my_first, blk);
-        F = front_of(blk, ok, gb, U);
-    }
+    fetch_blk(min(st_first + dpar, st_last), blk);
+    F = front_of(blk, ok, gb, U);
     if (dpar == 0) {
-        if (my_first < st_end) back_to_lds(F, U, ok, gb, 0);
-        if (my_first + 2 < st_end) fetch_blk(my_first + 2, blk);
+        back_to_lds(F, U, ok, gb, 0);
+        fetch_blk(min(st_first + 2, st_last), blk);
     }
     stage_dma(st_first);
     __builtin_amdgcn_s_waitcnt(0);              // vmcnt(0): the rows have landed
     read_a();
     __syncthreads();
 
-    for (uint32_t st = st_first; st < st_end; st++) {
+    // s_waitcnt vmcnt(n): wait until at most n of this wave's loads are outstanding (they complete in order)
+    auto wait_loads_but = [](auto n_tag) {
+        constexpr unsigned n = decltype(n_tag)::value;
+        __builtin_amdgcn_s_waitcnt((n & 15u) | (7u << 4) | (15u << 8) | ((n >> 4) << 14));
+    };
+    constexpr unsigned kFetchLoads = FMT == LLVQ_IDX_U24 ? 4u : 3u;      // loads of fetch_blk
+
+    // One step.  kBack: this wave finishes the decode of step st + 1 (its half's turn); otherwise it starts that of
+    // step st + 2.  The role alternates from step to step and is fixed per position in the loop below, so that every
+    // value carried from one step to the next is assigned unconditionally: a load may then stay in flight across steps
+    // (with an assignment under a condition the compiler copies the register where the paths join and waits for ALL
+    // loads there, i.e. at the top of the next step, before the activation rows are requested).
+    auto slot = [&](auto back_tag, uint32_t st) {
+        constexpr bool kBack = decltype(back_tag)::value;
         const uint32_t r = st - st_first;
-        const bool back_turn = ((r + 1) & 1u) == dpar;               // this wave finishes step st + 1 now (wave-uniform)
         const uint32_t bcur = kBBufs == 2 ? (r & 1u) : 0u, bnext = kBBufs == 2 ? ((r + 1) & 1u) : 0u;
         // the A operands of step st are in registers (read before the barrier that ended the last step), so the
         // activation rows of step st + 1 can be requested into the same region right away
         // (the decoding half asks after its decode: all eight waves asking at once right after the barrier queue at the
         // vector memory pipe, 56 KB per step, and every one of them waits for the issue of its seven loads)
-        const uint32_t st_stage = st + 1 < st_end ? st + 1 : st;
-        if (!(kBBufs == 2 && back_turn)) stage_dma(st_stage);
+        const uint32_t st_stage = min(st + 1, st_last);
+        if (!(kBBufs == 2 && kBack)) stage_dma(st_stage);
         // second part of step st + 1 before the products: the other wave of this SIMD multiplies meanwhile
-        if (kBBufs == 2 && back_turn) {
-            if (st + 1 < st_end) back_to_lds(F, U, ok, gb, bnext);
-            if (st + 3 < st_end) fetch_blk(st + 3, blk);
+        if (kBBufs == 2 && kBack) {
+            back_to_lds(F, U, ok, gb, bnext);
+            fetch_blk(min(st + 3, st_last), blk);
+            stage_dma(st_stage);
         }
-        if (kBBufs == 2 && back_turn) stage_dma(st_stage);
-        // The products of step st: A operands of all three channel groups first, B operands one group ahead.
+        // The products of step st: B operands one channel group ahead.
         // Waves whose tokens lie past M work on copies of token M - 1 and store nothing at the end.
         {
             const unsigned char* brow = bbuf + bcur * kBBytes + (uint32_t)lane * 16u;
-            u32x4 b[2][kTerms][4];
+            // one term per weight: the operands of the next channel group are read while this one is multiplied; two
+            // terms: twice the operands and twice the products per read, no room in the register file for reading ahead
+            constexpr int kAhead = kTerms == 1 ? 1 : 0;
+            u32x4 b[1 + kAhead][kTerms][4];
             auto load_b = [&](int j, u32x4 (&dst)[kTerms][4]) {
 #pragma unroll
                 for (int rr = 0; rr < kTerms; rr++) {
@@ -1355,36 +1370,50 @@ __global__ void __launch_bounds__(64 * kPanelWaves) panel_kernel(const unsigned 
                     for (int rt = 0; rt < 4; rt++) dst[rr][rt] = *reinterpret_cast<const u32x4*>(brow + (uint32_t)(rr * 12 + rt * 3 + j) * 1024u);
                 }
             };
-            load_b(0, b[0]);
+            if (kAhead) load_b(0, b[0]);
 #pragma unroll
             for (int j = 0; j < 3; j++) {
-                if (j + 1 < 3) load_b(j + 1, b[(j + 1) & 1]);
-                __builtin_amdgcn_sched_barrier(0);                   // keep the reads ahead of the products they are not needed for
+                if (kAhead) {
+                    if (j + 1 < 3) load_b(j + 1, b[(j + 1) & kAhead]);
+                    __builtin_amdgcn_sched_barrier(0);               // keep the reads ahead of the products they are not needed for
+                } else {
+                    load_b(j, b[0]);
+                }
 #pragma unroll
                 for (int rt = 0; rt < 4; rt++) {
 #pragma unroll
                     for (int rr = 0; rr < kTerms; rr++) {
 #pragma unroll
-                        for (int t = 0; t < 2; t++) acc[rt][t] = Mma<X2>::mma(a[j][t], b[j & 1][rr][rt], acc[rt][t]);
+                        for (int t = 0; t < 2; t++) acc[rt][t] = Mma<X2>::mma(a[j][t], b[j & kAhead][rr][rt], acc[rt][t]);
                     }
                 }
             }
         }
         if (kBBufs == 1) {
             __syncthreads();                                         // every wave has read the weights of step st
-            if (back_turn) {
-                if (st + 1 < st_end) back_to_lds(F, U, ok, gb, 0);
-                if (st + 3 < st_end) fetch_blk(st + 3, blk);
+            if (kBack) {
+                back_to_lds(F, U, ok, gb, 0);
+                fetch_blk(min(st + 3, st_last), blk);
             }
         }
-        if (!back_turn && st + 2 < st_end) F = front_of(blk, ok, gb, U);       // first part of step st + 2
-        // No load stays in flight across the end of a step: the values are carried in registers around the loop, and a
-        // pending one makes the compiler wait for ALL loads at the top of the next step, before it requests the
-        // activation rows.  Both were requested at least one phase ago.
-        asm volatile("" :: "v"(F.c), "v"(F.e0), "v"(F.e1), "v"(blk.raw.a), "v"(blk.raw.b), "v"(blk.raw.c), "v"(blk.raw.g));
-        __builtin_amdgcn_s_waitcnt(0);          // vmcnt(0): the rows of step st + 1 have landed in LDS
+        if (!kBack) F = front_of(blk, ok, gb, U);                    // first part of step st + 2 (its word was requested a step ago)
+        // the rows of step st + 1 have landed in LDS once the loads requested after them are the only ones outstanding:
+        // the three table reads that front_of leaves in flight, or the words requested behind the rows
+        if (!kBack) wait_loads_but(std::integral_constant<unsigned, 3>{});
+        else if (kBBufs == 1) wait_loads_but(std::integral_constant<unsigned, kFetchLoads>{});
+        else wait_loads_but(std::integral_constant<unsigned, 0>{});
         read_a();
         __syncthreads();
+    };
+    {
+        uint32_t st = st_first;
+        if (dpar == 1) {                                             // relative steps 0, 2, ..: second part; 1, 3, ..: first part
+            for (; st + 1 < st_end; st += 2) { slot(std::true_type{}, st); slot(std::false_type{}, st + 1); }
+            if (st < st_end) slot(std::true_type{}, st);
+        } else {
+            for (; st + 1 < st_end; st += 2) { slot(std::false_type{}, st); slot(std::true_type{}, st + 1); }
+            if (st < st_end) slot(std::false_type{}, st);
+        }
     }
 
     // y[token][row]: register v of tile (rt, t) belongs to token m0 + 32 t + 8 (v / 4) + 4 half + v % 4, row row0 + 32 rt + col
