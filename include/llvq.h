@@ -114,11 +114,14 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
  * M <= 2: products activation * integer coordinate are exact in fp32, accumulated in fp32 and scaled by
  *   gain / sqrt(16 m) per block (v_dot2 kernel); the partial sums of a row are combined with fp32 atomic adds in
  *   LDS, so the last bits of y can differ between calls (about 1e-7 relative).
- * M >= 3 (batched decode, prefill): the weights gain * x / sqrt(16 m) are rounded to the activation type
- *   (fp16: relative 2^-10, bf16: 2^-9) and contracted on the matrix cores with fp32 accumulation; partial sums
- *   of different K ranges are combined with fp32 atomic adds, so the last bits of y can differ between calls
- *   (launches with M > 64 and at least one strip of 256 rows x 256 tokens per compute unit do not split K and are
- *   reproducible).
+ * M >= 3 (batched decode, prefill): the weights gain * x / sqrt(16 m) are formed in fp32, brought to the activation
+ *   type (fp16: one value, relative rounding error 2^-11; bf16: two values, the rounding and the rounding of what it
+ *   leaves, together 2^-17) and contracted on the matrix cores with fp32 accumulation.
+ *   3 <= M <= 32: a tile of 16 rows is reduced over K inside one workgroup in a fixed order: no clearing, no atomic
+ *   adds, the same bits from call to call.  33 <= M <= 64: partial sums of different K ranges are combined with fp32
+ *   atomic adds after y was cleared, so the last bits of y can differ between calls.  M > 64: strips of 256 rows x
+ *   256 tokens, from M = 384 on panels of 128 rows x 512 tokens; when there are at least as many of them as compute
+ *   units K is not split and y is reproducible, otherwise as for 33 <= M <= 64.
  *   Requires N*KB < 2^32, KB < 2^24 and M*N < 2^32 (LLVQ_EINVAL otherwise).                            */
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
