@@ -120,8 +120,8 @@ int llvq_decode(llvq_ctx* ctx, const void* d_idx, int fmt, const void* d_gain, s
  *   3 <= M <= 32: a tile of 16 rows is reduced over K inside one workgroup in a fixed order: no clearing, no atomic
  *   adds, the same bits from call to call.  33 <= M <= 64: partial sums of different K ranges are combined with fp32
  *   atomic adds after y was cleared, so the last bits of y can differ between calls.  M > 64: strips of 256 rows x
- *   256 tokens, from M = 384 on panels of 128 rows x 512 tokens; when there are at least as many of them as compute
- *   units K is not split and y is reproducible, otherwise as for 33 <= M <= 64.
+ *   256 tokens, from M = 384 on panels of 128 rows x 512 tokens; when they number more than half the compute units
+ *   K is not split and y is reproducible, otherwise as for 33 <= M <= 64.
  *   Requires N*KB < 2^32, KB < 2^24 and M*N < 2^32 (LLVQ_EINVAL otherwise).                            */
 int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
                 const void* d_idx, int fmt, const void* d_gain, int N, int KB,
