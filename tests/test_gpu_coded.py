@@ -228,6 +228,17 @@ def test_coded_formats_on_a_long_launch(gpu, oracle13):
     d48 = _dev(synth.pack_u48((code << np.uint64(47)) | shape).reshape(-1))
     y = gpu.llvq_matmul_coded(d_x, d48, N, KB, 47, gain_lut=_dev(lut)).cpu().numpy()
     assert _rel(y[:, rows], oracle13.matmul(x, shape[rows], lut[code[rows].astype(np.int64)])) <= 1e-5
+    # the same three formats through the prefill kernel for M >= 384 (panels of 128 rows x 512 tokens; the gain table
+    # adds a load to the part of the decode that leaves reads in flight across steps)
+    rows = rows[:200]
+    x400 = synth.activations(rng, 400, K)
+    d_x400 = _dev(x400).half()
+    y = gpu.llvq_matmul_coded(d_x400, d24, N, KB, 24, base, gain=d_gain, fmt=LLVQ_IDX_U24).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x400, words[rows] + np.uint64(base), gain[rows])) <= TOL
+    y = gpu.llvq_matmul_coded(d_x400, packed, N, KB, 48).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x400, idx[rows], gain[rows])) <= TOL
+    y = gpu.llvq_matmul_coded(d_x400, d48, N, KB, 47, gain_lut=_dev(lut)).cpu().numpy()
+    assert _rel(y[:, rows], oracle13.matmul(x400, shape[rows], lut[code[rows].astype(np.int64)])) <= TOL
 
 
 def test_repack_empty_and_invalid(gpu):
