@@ -311,6 +311,22 @@ def test_panel_prefill_ragged_shapes(gpu, oracle13, N, K, M, xd):
         assert err <= 1e-4, err
 
 
+def test_panel_prefill_is_reproducible_when_k_is_not_split(gpu, oracle13):
+    """more panels than half the compute units: every output is written once by one workgroup, two calls agree bit for bit"""
+    import torch
+    N, K, M = 16500, 24 * 40, 512
+    idx, gain, x = synth.layer(8, 777, N, K, M)
+    KB = idx.shape[1]
+    d_x, d_idx, d_gain = _dev(x).half(), _dev(synth.pack_u48(idx).reshape(-1)), _dev(gain.reshape(-1))
+    y1 = gpu.llvq_matmul(d_x, d_idx, d_gain, N, KB)
+    y2 = torch.full_like(y1, float("nan"))
+    gpu.llvq_matmul(d_x, d_idx, d_gain, N, KB, out=y2)
+    assert torch.equal(y1, y2)
+    rows = np.sort(np.random.default_rng(3).choice(N, 100, replace=False))
+    ref = oracle13.matmul(x, idx[rows], gain[rows])
+    assert np.abs(y1.cpu().numpy().astype(np.float64)[:, rows] - ref).max() / np.abs(ref).max() <= TOL
+
+
 @pytest.mark.parametrize("name,M,xd", [("q", 96, "f16"), ("k", 256, "bf16"), ("q", 1024, "bf16"), ("gate", 130, "f16")])
 def test_prefill_with_workspace(gpu, oracle13, name, M, xd):
     """llvq_matmul_ws: weights dequantised once into the caller's workspace, then a dense GEMM.  The result must
