@@ -1185,8 +1185,9 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
 // 32-row tiles are decoded by four of the waves (the two halves of the workgroup take turns, so a SIMD always hosts
 // one decoding and one multiplying wave) and written to LDS as ready-made MFMA B operands; every wave reads the 12 KB
 // of the step's weights from there and the A operands of its own 64 tokens from a private region of LDS that it fills
-// itself (six lanes fetch the 96 bytes of a token row: few cache lines per load), which needs no barrier: the LDS
-// operations of a wave execute in order.  One barrier per step publishes the weights.  Against prefill_kernel a step
+// itself with direct global-to-LDS loads (six lanes fetch the 96 bytes of a token row: few cache lines per load).  The
+// region needs no barrier: the wave reads a step's operands into registers once its own loads have landed, and asks
+// for the next step's rows after that.  One barrier per step publishes the weights.  Against prefill_kernel a step
 // moves 18 KB instead of 24 KB per wave through LDS for twice the tokens per decoded block.
 // The decode of a step is spread over two steps of its wave: class search and digits while the wave's half is off
 // duty, placement, signs and scaling in the step before the weights are needed.
