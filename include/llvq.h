@@ -131,8 +131,10 @@ int llvq_matmul(llvq_ctx* ctx, const void* d_x, int x_dtype, int M,
  * format: the q/k/v or the gate/up matrices of a transformer block (the fused product of paper App. C, several
  * weight matrices per launch).  d_idx, d_gain, N and d_y are HOST arrays of n_items entries (device pointers and row
  * counts, read during the call); every matrix and every output is laid out as for llvq_matmul (y_i is [M][N_i]).  For
- * M <= 64 all products run in ONE launch (for M >= 3 after one launch that clears all outputs), which pays the
- * per-launch start-up once; for larger M the call is the same as n_items calls of llvq_matmul.  Requires
+ * M <= 64 all products run in ONE launch (for 33 <= M <= 64 after one launch that clears all outputs), which pays the
+ * per-launch start-up once.  For M >= 384 the 128-row strips of all matrices share one launch of the prefill kernel
+ * when at least one matrix alone would leave more than half of the compute units idle (k and v next to q; gate and up
+ * below 1024 tokens); otherwise, and for 64 < M < 384, the call is the same as n_items calls of llvq_matmul.  Requires
  * (N_0 + .. + N_last)*KB < 2^32; arguments and errors otherwise as for llvq_matmul (LLVQ_EINVAL also for n_items
  * outside 1..4).                                                                                              */
 int llvq_matmul_multi(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_items,

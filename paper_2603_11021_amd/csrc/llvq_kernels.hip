@@ -394,6 +394,7 @@ struct MatItems {
     int row_end[kMaxItems];        // rows of matrices 0..i together; entries past the last matrix repeat the total
     int tile_end[kMaxItems];       // the same in tiles of 32 rows, every matrix rounded up (mfma_kernel)
     int tile16_end[kMaxItems];     // the same in tiles of 16 rows (tile_kernel)
+    int strip_end[kMaxItems];      // the same in strips of 128 rows (panel_kernel)
 };
 
 template <int FMT, typename X2, bool BIG_GLOBAL, bool DYNAMIC, bool MULTI = false>
@@ -1194,11 +1195,27 @@ __global__ void __launch_bounds__(64 * WAVES) prefill_kernel(const unsigned char
 constexpr int kPanelRows = 128, kPanelTokens = 512, kPanelWaves = 8;
 constexpr int kPanelMinM = 384;
 
-template <int FMT, typename X2>
+// MULTI: the strips are those of up to four matrices that share x, one matrix after the other (`items`).
+template <int FMT, typename X2, bool MULTI = false>
 __global__ void __launch_bounds__(64 * kPanelWaves) panel_kernel(const unsigned char* __restrict__ blob, TableLayout lay,
-                                                                   const void* __restrict__ idx, const uint16_t* __restrict__ gain,
-                                                                   const uint32_t* __restrict__ x, int M, int N, int KB, Code cd,
-                                                                   int ksplit, float* __restrict__ y) {
+                                                                   const void* __restrict__ idx_in, const uint16_t* __restrict__ gain_in,
+                                                                   const uint32_t* __restrict__ x, int M, int N_in, int KB, Code cd,
+                                                                   int ksplit, MatItems items, float* __restrict__ y_in) {
+    // the matrix this workgroup's strip belongs to and the strip's first row inside it (wave-uniform)
+    const void* idx = idx_in;
+    const uint16_t* gain = gain_in;
+    float* y = y_in;
+    int N = N_in, strip = (int)blockIdx.x;
+    if constexpr (MULTI) {
+        int it = 0, first_strip = 0, first_row = 0;
+#pragma unroll
+        for (int i = 0; i + 1 < kMaxItems; i++) {
+            if (strip >= items.strip_end[i]) { it = i + 1; first_strip = items.strip_end[i]; first_row = items.row_end[i]; }
+        }
+        idx = items.idx[it]; gain = items.gain[it]; y = items.y[it];
+        N = items.row_end[it] - first_row;
+        strip -= first_strip;
+    }
     constexpr int kTerms = Mma<X2>::kTerms;
     constexpr int kBBufs = kTerms == 1 ? 2 : 1;                      // two-term weights: one buffer, a second barrier per step
     constexpr uint32_t kBBytes = 4 * 3 * 1024 * kTerms;              // [term][row tile][k group][lane] x 16 bytes
@@ -1212,7 +1229,7 @@ __global__ void __launch_bounds__(64 * kPanelWaves) panel_kernel(const unsigned 
     const uint32_t spt_all = ((uint32_t)KB + 1) / 2;
     const uint32_t st_first = (uint32_t)(((uint64_t)spt_all * blockIdx.z) / (uint32_t)ksplit);
     const uint32_t st_end = (uint32_t)(((uint64_t)spt_all * (blockIdx.z + 1)) / (uint32_t)ksplit);
-    const int row0 = (int)blockIdx.x * kPanelRows;
+    const int row0 = strip * kPanelRows;
     const int m0 = (int)blockIdx.y * kPanelTokens + wave * 64;        // first token of this wave
     const uint32_t xpitch = (uint32_t)KB * 12u;                       // dwords per activation row
 
@@ -1870,34 +1887,50 @@ static int launch_prefill(llvq_ctx* ctx, const void* d_x, int M, const void* d_i
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "prefill matmul launch");
 }
 
-template <int FMT, typename X2>
-static int launch_panel(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
-    const unsigned strips = (unsigned)((N + kPanelRows - 1) / kPanelRows), passes = (unsigned)((M + kPanelTokens - 1) / kPanelTokens);
+// MULTI: N is not used; the strips are those of `items`
+template <int FMT, typename X2, bool MULTI = false>
+static int launch_panel(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st,
+                        const MatItems& items = MatItems{}, int n_items = 1) {
+    const unsigned strips = MULTI ? (unsigned)items.strip_end[kMaxItems - 1] : (unsigned)((N + kPanelRows - 1) / kPanelRows);
+    const unsigned passes = (unsigned)((M + kPanelTokens - 1) / kPanelTokens);
     // enough workgroups for the chip: split the block pairs of a row among up to ksplit workgroups (at least 16 steps each)
     const unsigned spt = ((unsigned)KB + 1) / 2;
     unsigned ksplit = (unsigned)ctx->num_cu / (strips * passes);
     ksplit = std::max(1u, std::min(ksplit, std::max(1u, spt / 16)));
     if (ksplit > 1) {
-        const size_t ny = (size_t)M * N;
-        hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+        if (MULTI) {
+            int widest = 0;
+            for (int i = 0; i < n_items; i++) widest = std::max(widest, items.row_end[i] - (i ? items.row_end[i - 1] : 0));
+            const size_t ny = (size_t)M * (size_t)widest;
+            hipLaunchKernelGGL(fill_multi_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 2048), (unsigned)n_items), dim3(256), 0, st, items, M, 0.0f);
+        } else {
+            const size_t ny = (size_t)M * N;
+            hipLaunchKernelGGL(fill_kernel, dim3((unsigned)std::min<size_t>((ny / 4 + 256) / 256, 4096)), dim3(256), 0, st, d_y, ny, 0.0f);
+        }
     }
     const dim3 grid(strips, passes, ksplit);
     constexpr int kTerms = Mma<X2>::kTerms;
     const size_t lds = ctx->lay.lds_bytes + (size_t)(kTerms == 1 ? 2 : 1) * (4 * 3 * 1024 * kTerms) + (size_t)kPanelWaves * 7 * 1024;
-    if (int rc = set_lds<panel_kernel<FMT, X2>>(ctx, lds)) return rc;
-    hipLaunchKernelGGL((panel_kernel<FMT, X2>), grid, dim3(64 * kPanelWaves), lds, st, ctx->d_blob, ctx->lay, d_idx,
-                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, d_y);
+    if (int rc = set_lds<panel_kernel<FMT, X2, MULTI>>(ctx, lds)) return rc;
+    hipLaunchKernelGGL((panel_kernel<FMT, X2, MULTI>), grid, dim3(64 * kPanelWaves), lds, st, ctx->d_blob, ctx->lay, d_idx,
+                       reinterpret_cast<const uint16_t*>(d_gain), reinterpret_cast<const uint32_t*>(d_x), M, N, KB, cd, (int)ksplit, items, d_y);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? LLVQ_OK : hip_fail(ctx, e, "panel matmul launch");
+}
+
+// whether a product with this many strips of 128 rows takes the panel kernel: from kPanelMinM tokens on, when there are
+// panels for at least a sixteenth of the chip (the rest comes from splitting the rows' block pairs, at least 16 steps
+// per part; measured on Llama-3-8B shapes: 4096 rows at M = 512 take 72 us against 92 us in the strip kernel, 1024 rows
+// are level at M = 1024 and slower below); activation offsets inside the kernel are 32-bit byte offsets
+static bool panel_fits(const llvq_ctx* ctx, int M, uint64_t strips, int KB) {
+    return M >= kPanelMinM && (uint64_t)M * (uint64_t)KB * 48u < (1ull << 32) &&
+           strips * (uint64_t)((M + kPanelTokens - 1) / kPanelTokens) * 16u >= (uint64_t)ctx->num_cu;
 }
 
 template <int FMT, typename X2>
 static int launch_any_matmul(llvq_ctx* ctx, const void* d_x, int M, const void* d_idx, const void* d_gain, const Code& cd, int N, int KB, float* d_y, hipStream_t st) {
     if (M < kMfmaMinM) return launch_matmul<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
-    // panels of 128 rows x 512 tokens from kPanelMinM tokens on, when there are enough of them for a quarter of the chip
-    // (the rest comes from splitting the rows' block pairs); activation offsets inside the kernel are 32-bit byte offsets
-    if (M >= kPanelMinM && (uint64_t)M * (uint64_t)KB * 48u < (1ull << 32) &&
-        (uint64_t)((N + kPanelRows - 1) / kPanelRows) * (uint64_t)((M + kPanelTokens - 1) / kPanelTokens) * 4u >= (uint64_t)ctx->num_cu)
+    if (panel_fits(ctx, M, (uint64_t)((N + kPanelRows - 1) / kPanelRows), KB))
         return launch_panel<FMT, X2>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M > 64) return launch_prefill<FMT, X2, 8, 8>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
     if (M <= 16) return launch_tile<FMT, X2, 1>(ctx, d_x, M, d_idx, d_gain, cd, N, KB, d_y, st);
@@ -2004,18 +2037,13 @@ int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
         }
         if (tiles * (size_t)((KB + 1) / 2) >= (1ull << 32) || (size_t)M * (size_t)KB * 12 >= (1ull << 32)) return LLVQ_EINVAL;
     }
-    if (n_items == 1 || M > 64) {
-        // one matrix, or a batch that takes the strip kernel: one product after the other
-        for (int i = 0; i < n_items; i++)
-            if (int rc = matmul_impl(ctx, d_x, x_dtype, M, d_idx[i], fmt, d_gain[i], cd, N[i], KB, d_y[i], stream)) return rc;
-        return LLVQ_OK;
-    }
     MatItems items;
-    int rows = 0, tiles = 0, tiles16 = 0;
+    int rows = 0, tiles = 0, tiles16 = 0, strips = 0;
     for (int i = 0; i < kMaxItems; i++) {
         const int k = i < n_items ? i : n_items - 1;
-        if (i < n_items) { rows += N[i]; tiles += (N[i] + 31) / 32; tiles16 += (N[i] + kTileRows - 1) / kTileRows; }
+        if (i < n_items) { rows += N[i]; tiles += (N[i] + 31) / 32; tiles16 += (N[i] + kTileRows - 1) / kTileRows; strips += (N[i] + kPanelRows - 1) / kPanelRows; }
         items.tile16_end[i] = tiles16;
+        items.strip_end[i] = strips;
         items.idx[i] = d_idx[k];
         items.gain[i] = reinterpret_cast<const uint16_t*>(d_gain[k]);
         items.y[i] = d_y[k];
@@ -2023,6 +2051,23 @@ int matmul_multi_impl(llvq_ctx* ctx, const void* d_x, int x_dtype, int M, int n_
         items.tile_end[i] = tiles;
     }
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // prefill: the 128-row strips of all matrices in one launch when at least one of them has panels for less than half
+    // of the chip (small matrices such as k and v then run at the rate of the large ones; matrices that fill the chip
+    // on their own gain nothing from sharing a launch and lose to the uneven last round)
+    bool small_item = false;
+    for (int i = 0; i < n_items; i++)
+        small_item = small_item || (uint64_t)((N[i] + kPanelRows - 1) / kPanelRows) * (uint64_t)((M + kPanelTokens - 1) / kPanelTokens) * 2u < (uint64_t)ctx->num_cu;
+    if (n_items > 1 && small_item && panel_fits(ctx, M, (uint64_t)strips, KB)) {
+        if (x_dtype == LLVQ_F16)
+            return LLVQ_BY_FMT(fmt, (launch_panel<F, half2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items, n_items)));
+        return LLVQ_BY_FMT(fmt, (launch_panel<F, bf16x2_t, true>(ctx, d_x, M, d_idx[0], d_gain[0], cd, rows, KB, d_y[0], st, items, n_items)));
+    }
+    if (n_items == 1 || M > 64) {
+        // one matrix, or a batch that takes the strip kernel: one product after the other
+        for (int i = 0; i < n_items; i++)
+            if (int rc = matmul_impl(ctx, d_x, x_dtype, M, d_idx[i], fmt, d_gain[i], cd, N[i], KB, d_y[i], stream)) return rc;
+        return LLVQ_OK;
+    }
     if (M >= kMfmaMinM && M <= kTileMaxM) {
         // row tiles of all matrices in one launch, each tile reduced inside its workgroup
         if (x_dtype == LLVQ_F16) {

@@ -520,6 +520,29 @@ def test_matmul_multi_small(gpu, oracle13, Ns, K, M):
         assert np.abs(y.cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max() <= TOL
 
 
+@pytest.mark.parametrize("Ns,K,M,xd", [((4096, 1024, 1024), 4096, 1024, "f16"), ((4100, 1000, 130, 3000), 24 * 37, 400, "bf16"),
+                                        ((5000, 7000), 24 * 9, 513, "f16")])
+def test_matmul_multi_prefill_panels(gpu, oracle13, Ns, K, M, xd):
+    """several matrices that share x at M >= 384: the 128-row strips of all of them in one launch of the panel kernel
+    (q/k/v of a Llama-3-8B-shaped block; ragged row counts so that every matrix ends in a partial strip; both
+    activation types); sampled rows of every output against the oracle"""
+    import torch
+    rng = synth.rng_for(3, 7400 + M + len(Ns))
+    KB = synth.blocks_per_row(K)
+    x = synth.activations(rng, M, K, "bf16" if xd == "bf16" else np.float16)
+    idx = [synth.indices(rng, (N, KB)) for N in Ns]
+    gain = [synth.gains(rng, (N, KB)) for N in Ns]
+    d_x = _dev(x).to(torch.bfloat16 if xd == "bf16" else torch.float16)
+    ys = gpu.llvq_matmul_multi(d_x, [_dev(synth.pack_u48(i).reshape(-1)) for i in idx], [_dev(g.reshape(-1)) for g in gain], list(Ns), KB)
+    for y, i, g, N in zip(ys, idx, gain, Ns):
+        assert y.shape == (M, N)
+        rows = np.sort(np.random.default_rng(N + M).choice(N, min(N, 100), replace=False))
+        rows[0], rows[-1] = 0, N - 1
+        ref = oracle13.matmul(x, i[rows], g[rows])
+        err = np.abs(y[:, rows].cpu().numpy().astype(np.float64) - ref).max() / np.abs(ref).max()
+        assert err <= (1e-4 if xd == "bf16" else TOL), err
+
+
 @pytest.mark.parametrize("M", [1, 16])
 def test_matmul_multi_llama3_8b_qkv_and_gate_up(gpu, oracle13, M):
     """q/k/v (4096 + 1024 + 1024 rows: a short launch) and gate/up (2 x 14336 rows: a long launch) of a
